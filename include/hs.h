@@ -1,0 +1,155 @@
+/*
+ * hs.h -- C ABI of the HieraSparse hot path for AMD MI355X (gfx950).
+ *
+ * The library implements attention over a hierarchically pruned KV cache
+ * (paper Sec. III): the cache is cut into blocks ("tiles") of 64 tokens; a tile
+ * is stored dense, or pruned 2:4 along the contraction axis and stored as kept
+ * values + 2-bit positions (Sec. III-A/B), or -- an extension the benchmark
+ * workloads add on top of the paper -- skipped.  A signed block index map
+ * (Sec. III-B) locates every tile in its pool.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers unless marked [host].
+ *   - bf16 tensors are raw 16-bit patterns; D (head dim) is contiguous.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
+ *     the default stream).  The library allocates nothing, frees nothing and
+ *     keeps no pointer after a call returns; the caller owns every buffer.
+ *   - Return value: HS_OK (0) or a negative hs_status.  Arguments are checked
+ *     on the host before anything is launched; nothing is launched when an
+ *     error is returned.  Faults inside a kernel are not recoverable.
+ *   - A process may call from several threads as long as two calls do not share
+ *     an output or workspace buffer.
+ */
+#ifndef HS_H_
+#define HS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HS_OK = 0,
+  HS_EINVAL = -1,       /* null pointer, bad fraction, inconsistent states, capacity too small */
+  HS_EUNSUPPORTED = -2, /* D != 128, tile != 64, L % 64 != 0, Hq % Hkv != 0, group size > 8 ... */
+  HS_EHIP = -3          /* a HIP runtime call failed; hs_last_hip_error() has the text */
+} hs_status;
+
+/* Tile states (Sec. III-A block-level mask M, plus SKIP). */
+enum { HS_SKIP = 0, HS_DENSE = 1, HS_SPARSE24 = 2 };
+
+/* Sizes in bytes of one 64 x 128 bf16 tile in each pool (Sec. III-D: nnz = 1/2,
+ * metadata = 1/16 of the dense tile). */
+enum { HS_TILE_DENSE_BYTES = 16384, HS_TILE_NNZ_BYTES = 8192, HS_TILE_META_BYTES = 1024 };
+
+/* Geometry.  Supported: D == 128, tile == 64, L % 64 == 0, Hq % Hkv == 0,
+ * Hq / Hkv <= 8. */
+typedef struct {
+  int32_t B;    /* batch */
+  int32_t Hq;   /* query heads */
+  int32_t Hkv;  /* KV heads */
+  int32_t L;    /* tokens in the cache */
+  int32_t D;    /* head dim */
+  int32_t tile; /* tokens per tile */
+} hs_shape;
+
+/* Policy of the built-in magnitude pruner (Sec. III-A, Eq. 2a-d).
+ *   skip_frac      floor(skip_frac * T) tiles per (b, kv head) with the lowest
+ *                  energy  sum(K^2) + sum(V^2)  are dropped for K and V alike.
+ *   sparse_frac_x  the paper's block sparsity S_K / S_V: of the tiles that are
+ *                  kept, floor(S * n_kept) with the lowest pruning loss
+ *                  || X * (1 - m) ||_1  (Eq. 2c) are stored 2:4, the rest dense.
+ *   state_k/_v     [host] optional explicit per-tile states, int8 [B, Hkv, T];
+ *                  when non-NULL (both or neither) they replace the fractions.
+ *                  A tile must be SKIP in both or in neither.
+ * Ties in either ranking go to the lower tile index. */
+typedef struct {
+  double skip_frac;
+  double sparse_frac_k;
+  double sparse_frac_v;
+  const int8_t* state_k;
+  const int8_t* state_v;
+} hs_policy;
+
+/* Packed cache: caller-owned device buffers, rectangular per (b, kv head).
+ *   x_dense  [B, Hkv, cap_dense_x,  16384 B]   dense pool
+ *   x_nnz    [B, Hkv, cap_sparse_x,  8192 B]   kept values of 2:4 tiles
+ *   x_meta   [B, Hkv, cap_sparse_x,  1024 B]   2-bit positions
+ *   x_map    [B, Hkv, T] int32: +(slot+1) dense, -(slot+1) sparse, 0 skipped;
+ *            slots are handed out in ascending tile order per pool (the two
+ *            running counters of Sec. III-B).
+ * Inside a tile the bytes are in matrix-core operand order (documented in
+ * DESIGN notes of the repository and mirrored by hs_unpack_kv); the pools of a
+ * capacity-0 kind may be NULL. */
+typedef struct {
+  void* k_dense; void* k_nnz; void* k_meta; int32_t* k_map;
+  void* v_dense; void* v_nnz; void* v_meta; int32_t* v_map;
+  int32_t cap_dense_k, cap_sparse_k, cap_dense_v, cap_sparse_v;
+} hs_kv;
+
+/* Library version (major * 100 + minor). [host, pure] */
+int hs_version(void);
+
+/* Text for a status code. [host, pure] */
+const char* hs_strerror(int status);
+
+/* Text of the last HIP error this thread saw inside the library. [host] */
+const char* hs_last_hip_error(void);
+
+/* Tile counts a policy yields per (b, kv head): counts[0..4] = n_skip,
+ * n_dense_k, n_sparse_k, n_dense_v, n_sparse_v.  With explicit states the
+ * counts are the per-row maxima.  These are the pool capacities to allocate.
+ * [host, pure] */
+int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_t counts[5]);
+
+/* Bytes of the packed cache for given capacities, whole batch:
+ * bytes[0..7] = k_dense, k_nnz, k_meta, k_map, v_dense, v_nnz, v_meta, v_map.
+ * (Sec. III-D byte accounting.) [host, pure] */
+int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t bytes[8]);
+
+/* Workspace bytes needed by each call.  [host, pure]
+ *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto) */
+int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes);
+
+/* Number of KV splits hs_decode_attn uses when n_splits == 0. [host, pure] */
+int hs_decode_auto_splits(const hs_shape* shape);
+
+/* Compress (Sec. III-A + III-B; fused top-2-of-4 compressor of Sec. IV-B).
+ * K, V: bf16 [B, Hkv, L, D]; kv_strides = element strides of the b, head and
+ * token axes (NULL = contiguous).  Element mask: K keeps the 2 largest
+ * magnitudes of every 4 consecutive channels of a token, V of every 4
+ * consecutive tokens of a channel (magnitude = bits & 0x7fff, ties to the lower
+ * position).  Writes maps and pools of `out`; slots beyond the used count are
+ * left untouched.  workspace: hs_workspace_bytes(op 0). */
+int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
+                   const void* K, const void* V, const int64_t kv_strides[3],
+                   const hs_kv* out, void* workspace, void* stream);
+
+/* Inverse of the packing, for tests and debugging: dense bf16 [B, Hkv, L, D]
+ * (contiguous) with zeros at pruned positions and in skipped tiles. */
+int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_out, void* stream);
+
+/* Prefill attention (Algorithm 1 with the mixed dense/sparse dispatch of
+ * Sec. III-C-2).  Q: bf16 [B, Hq, Lq, D] contiguous, Lq % 64 == 0, Lq <= L.
+ * Query i sees token j iff tile(j) is not skipped and (!causal or
+ * j <= i + L - Lq).  scale == 0 selects 1/sqrt(D) (Eq. 1).
+ * O: bf16 [B, Hq, Lq, D]; LSE: fp32 [B, Hq, Lq] or NULL.  A query that sees no
+ * token gets O = 0, LSE = -inf. */
+int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal,
+                    const void* Q, const hs_kv* kv, void* O, float* LSE,
+                    void* workspace, void* stream);
+
+/* Decode attention (split-KV kernel + merge, Sec. IV-C): one query token per
+ * (b, query head) against all L cached tokens.  Q, O: bf16 [B, Hq, D];
+ * LSE: fp32 [B, Hq] or NULL.  n_splits == 0 picks hs_decode_auto_splits.
+ * workspace: hs_workspace_bytes(op 2, n_splits). */
+int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
+                   const void* Q, const hs_kv* kv, void* O, float* LSE,
+                   void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HS_H_ */

@@ -1,0 +1,401 @@
+"""Plain, slow, obviously-correct CPU oracle for HieraSparse (numpy, fp64).
+
+TEST INFRASTRUCTURE ONLY -- the product path never imports this module, and this
+module imports nothing from the HIP package.
+
+What the method computes (paper Sec. III): the KV cache is cut into blocks of
+``Bt`` tokens; each block is stored dense, or pruned 2:4 along the contraction
+axis and stored as kept values + 2-bit positions (Sec. III-A, Eq. 2a-b;
+Sec. III-B), or -- the extension this build's workloads add -- skipped
+altogether.  A signed block index map locates each block in its pool
+(Sec. III-B).  Attention over the packed cache (Algorithm 1) is, given the
+pruned cache, exactly softmax(Q K~^T / sqrt(d)) V~ (Eq. 1) over the
+decompressed, masked K~, V~.  So the oracle is that definition written out:
+prune -> pack -> unpack -> plain attention, all in fp64 on the exact values of
+the bf16 inputs.
+
+Pins (tests/test_oracle_*.py): top-2-of-4 invariants over exhaustive small
+alphabets; pack/unpack bit-exact round trip; pool byte counts and compression
+ratios printed in Sec. III-D; attention special cases against an independent
+library routine (all-dense, masked, token-deleted); decode == last causal row;
+brute force in Python floats on tiny shapes; exact rational tile ranking.
+No function here is "parity unpinned".
+
+All tensors are numpy arrays.  bf16 tensors are carried as uint16 bit patterns.
+Shapes: K, V [B, Hkv, L, D]; Q prefill [B, Hq, Lq, D]; q decode [B, Hq, D].
+Tile states: 0 = SKIP, 1 = DENSE, 2 = SPARSE24.
+"""
+import numpy as np
+
+SKIP, DENSE, SPARSE24 = 0, 1, 2
+
+
+# ----------------------------------------------------------------------------
+# bf16 <-> real numbers
+# ----------------------------------------------------------------------------
+def bf16_to_f64(bits):
+    """Exact value of bf16 bit patterns (uint16) as float64."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------
+# element-level 2:4 mask (Sec. III-A, Eq. 2a-b; fused top-2 form of Sec. IV-B)
+# ----------------------------------------------------------------------------
+def _top2_of_4(bits_g):
+    """bits_g: uint16 [..., 4].  Boolean keep mask with exactly two True per group.
+
+    Order is by magnitude, i.e. by the integer (bits & 0x7FFF), descending; equal
+    magnitudes are resolved in favour of the lower position, so that exactly two
+    survive (Eq. 2b would keep more than two on ties, which the 2:4 format cannot
+    store).
+    """
+    key = (bits_g & np.uint16(0x7FFF)).astype(np.int32)
+    pos = np.arange(4, dtype=np.int32)
+    # beats[..., i, j] = element j is ranked ahead of element i
+    ki = key[..., :, None]
+    kj = key[..., None, :]
+    beats = (kj > ki) | ((kj == ki) & (pos[None, :] < pos[:, None]))
+    rank = beats.sum(axis=-1)
+    return rank < 2
+
+
+def element_mask_k(K_bits):
+    """K is the sparse operand of S^T = K Q^T, contraction over channels: groups
+    are 4 consecutive channels of one token (Sec. III-C, Table II)."""
+    K_bits = np.asarray(K_bits, dtype=np.uint16)
+    B, H, L, D = K_bits.shape
+    assert D % 4 == 0
+    m = _top2_of_4(K_bits.reshape(B, H, L, D // 4, 4))
+    return m.reshape(B, H, L, D)
+
+
+def element_mask_v(V_bits):
+    """V^T is the sparse operand of O^T = V^T P^T, contraction over tokens: groups
+    are 4 consecutive tokens of one channel (Sec. III-C, Table II)."""
+    V_bits = np.asarray(V_bits, dtype=np.uint16)
+    B, H, L, D = V_bits.shape
+    assert L % 4 == 0
+    g = V_bits.reshape(B, H, L // 4, 4, D).transpose(0, 1, 2, 4, 3)  # [..., L/4, D, 4]
+    m = _top2_of_4(g)
+    return m.transpose(0, 1, 2, 4, 3).reshape(B, H, L, D)
+
+
+# ----------------------------------------------------------------------------
+# block-level decisions (Sec. III-A Eq. 2c-d; skip = workload extension)
+# ----------------------------------------------------------------------------
+def tile_energy(K_bits, V_bits, Bt):
+    """Skip score per tile: sum of squares of the tile's K and V entries (the
+    squared joint L2 norm), accumulated in fp64.  [B, Hkv, T]."""
+    K = bf16_to_f64(K_bits)
+    V = bf16_to_f64(V_bits)
+    B, H, L, D = K.shape
+    T = L // Bt
+    e = (K * K).reshape(B, H, T, Bt * D).sum(axis=-1) + (V * V).reshape(B, H, T, Bt * D).sum(axis=-1)
+    return e
+
+
+def tile_prune_loss(X_bits, mask, Bt):
+    """Eq. 2c: L1 norm of what the element mask removes, per block.  [B, Hkv, T]."""
+    X = np.abs(bf16_to_f64(X_bits)) * (~mask)
+    B, H, L, D = X.shape
+    return X.reshape(B, H, L // Bt, Bt * D).sum(axis=-1)
+
+
+def _lowest(scores_row, n, eligible):
+    """Indices of the n eligible tiles with the lowest score; ties -> lower index."""
+    idx = [t for t in range(len(scores_row)) if eligible[t]]
+    idx.sort(key=lambda t: (scores_row[t], t))
+    return idx[:n]
+
+
+def select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v):
+    """Tile states for K and V, per (b, hkv) row.
+
+    n_skip = floor(skip_frac * T) lowest-energy tiles are SKIP for both tensors.
+    Of the remaining n_keep tiles, floor(sparse_frac_x * n_keep) with the lowest
+    pruning loss (Eq. 2c-d) become SPARSE24, the rest stay DENSE.
+    Returns (state_k, state_v) int8 [B, Hkv, T].
+    """
+    B, H, T = energy.shape
+    sk = np.full((B, H, T), DENSE, dtype=np.int8)
+    sv = np.full((B, H, T), DENSE, dtype=np.int8)
+    n_skip = int(np.floor(skip_frac * T))
+    for b in range(B):
+        for h in range(H):
+            all_ok = [True] * T
+            skipped = _lowest(energy[b, h], n_skip, all_ok)
+            kept = [True] * T
+            for t in skipped:
+                kept[t] = False
+                sk[b, h, t] = SKIP
+                sv[b, h, t] = SKIP
+            n_keep = T - n_skip
+            for st, loss, frac in ((sk, loss_k, sparse_frac_k), (sv, loss_v, sparse_frac_v)):
+                n_sp = int(np.floor(frac * n_keep))
+                for t in _lowest(loss[b, h], n_sp, kept):
+                    st[b, h, t] = SPARSE24
+    return sk, sv
+
+
+def build_map(state):
+    """Signed block index map (Sec. III-B): walking the blocks in sequence order
+    with one counter per pool, a dense block gets +(slot+1), a sparse block
+    -(slot+1); 0 marks a skipped block.  int32 [B, Hkv, T]."""
+    B, H, T = state.shape
+    mp = np.zeros((B, H, T), dtype=np.int32)
+    for b in range(B):
+        for h in range(H):
+            nd = ns = 0
+            for t in range(T):
+                if state[b, h, t] == DENSE:
+                    nd += 1
+                    mp[b, h, t] = nd
+                elif state[b, h, t] == SPARSE24:
+                    ns += 1
+                    mp[b, h, t] = -ns
+    return mp
+
+
+# ----------------------------------------------------------------------------
+# pack / unpack in the canonical logical layout (Sec. III-B, Sec. IV-B)
+# ----------------------------------------------------------------------------
+def _nibbles_to_words(nib):
+    """nib: uint32 [..., n] -> uint32 [..., ceil(n/8)], nibble g in bits 4*(g%8) of
+    word g//8 (a short last word is zero-filled)."""
+    n = nib.shape[-1]
+    if n % 8:
+        pad = np.zeros(nib.shape[:-1] + (8 - n % 8,), dtype=nib.dtype)
+        nib = np.concatenate([nib, pad], axis=-1)
+        n = nib.shape[-1]
+    w = nib.reshape(nib.shape[:-1] + (n // 8, 8)).astype(np.uint32)
+    sh = (4 * np.arange(8, dtype=np.uint32))
+    return (w << sh).sum(axis=-1).astype(np.uint32)
+
+
+def _words_to_nibbles(words):
+    sh = (4 * np.arange(8, dtype=np.uint32))
+    nib = (words[..., None] >> sh) & np.uint32(0xF)
+    return nib.reshape(words.shape[:-1] + (words.shape[-1] * 8,))
+
+
+def _compress_groups(bits_g, mask_g):
+    """bits_g, mask_g: [..., 4] with exactly two kept per group.
+    Returns (vals [..., 2] uint16 in ascending position order, nibble [...] uint32
+    = i0 | i1 << 2)."""
+    pos = np.arange(4)
+    # positions of the two kept entries, ascending
+    order = np.argsort(np.where(mask_g, pos, pos + 4), axis=-1, kind="stable")
+    i0 = order[..., 0]
+    i1 = order[..., 1]
+    v0 = np.take_along_axis(bits_g, i0[..., None], axis=-1)[..., 0]
+    v1 = np.take_along_axis(bits_g, i1[..., None], axis=-1)[..., 0]
+    vals = np.stack([v0, v1], axis=-1).astype(np.uint16)
+    nib = (i0 | (i1 << 2)).astype(np.uint32)
+    return vals, nib
+
+
+def pack_k_tile(tile_bits, tile_mask):
+    """One K tile [Bt, D] -> nnz [Bt, D/2] uint16, meta [Bt, ceil(D/32)] uint32."""
+    Bt, D = tile_bits.shape
+    vals, nib = _compress_groups(tile_bits.reshape(Bt, D // 4, 4), tile_mask.reshape(Bt, D // 4, 4))
+    return vals.reshape(Bt, D // 2), _nibbles_to_words(nib)
+
+
+def pack_v_tile(tile_bits, tile_mask):
+    """One V tile [Bt, D] -> nnz [Bt/4, 2, D] uint16, meta [Bt/4, D/8] uint32
+    (one nibble per (token group, channel))."""
+    Bt, D = tile_bits.shape
+    g = tile_bits.reshape(Bt // 4, 4, D).transpose(0, 2, 1)
+    mg = tile_mask.reshape(Bt // 4, 4, D).transpose(0, 2, 1)
+    vals, nib = _compress_groups(g, mg)          # [Bt/4, D, 2], [Bt/4, D]
+    return vals.transpose(0, 2, 1).copy(), _nibbles_to_words(nib)
+
+
+def unpack_k_tile(nnz, meta):
+    Bt = nnz.shape[0]
+    D = nnz.shape[1] * 2
+    nib = _words_to_nibbles(meta)[:, : D // 4]
+    out = np.zeros((Bt, D // 4, 4), dtype=np.uint16)
+    v = nnz.reshape(Bt, D // 4, 2)
+    i0 = (nib & 3).astype(np.int64)
+    i1 = ((nib >> 2) & 3).astype(np.int64)
+    np.put_along_axis(out, i0[..., None], v[..., 0:1], axis=-1)
+    np.put_along_axis(out, i1[..., None], v[..., 1:2], axis=-1)
+    return out.reshape(Bt, D)
+
+
+def unpack_v_tile(nnz, meta):
+    G, _, D = nnz.shape
+    nib = _words_to_nibbles(meta)[:, :D]
+    out = np.zeros((G, D, 4), dtype=np.uint16)
+    i0 = (nib & 3).astype(np.int64)
+    i1 = ((nib >> 2) & 3).astype(np.int64)
+    np.put_along_axis(out, i0[..., None], nnz[:, 0, :, None], axis=-1)
+    np.put_along_axis(out, i1[..., None], nnz[:, 1, :, None], axis=-1)
+    return out.transpose(0, 2, 1).reshape(G * 4, D)
+
+
+class PackedKV:
+    """Canonical packed cache for one tensor (K or V): pools + signed map."""
+
+    def __init__(self, kind, Bt, D, mp, dense, nnz, meta):
+        self.kind, self.Bt, self.D = kind, Bt, D
+        self.map, self.dense, self.nnz, self.meta = mp, dense, nnz, meta
+
+    def nbytes(self):
+        """Bytes actually occupied (used slots only) + the map."""
+        nd = int((self.map > 0).sum())
+        ns = int((self.map < 0).sum())
+        tile = self.Bt * self.D * 2
+        return nd * tile + ns * (tile // 2 + tile // 16) + 4 * self.map.size
+
+
+def pack_tensor(kind, X_bits, mask, state, Bt):
+    """Walk the blocks in sequence order (Sec. III-B) and fill the pools.
+    Pools are rectangular [B, Hkv, cap, ...] with cap = the largest per-row count;
+    unused slots stay zero."""
+    X_bits = np.asarray(X_bits, dtype=np.uint16)
+    B, H, L, D = X_bits.shape
+    T = L // Bt
+    mp = build_map(state)
+    cap_d = max(1, int((state == DENSE).sum(axis=-1).max()))
+    cap_s = max(1, int((state == SPARSE24).sum(axis=-1).max()))
+    dense = np.zeros((B, H, cap_d, Bt, D), dtype=np.uint16)
+    if kind == "k":
+        nnz = np.zeros((B, H, cap_s, Bt, D // 2), dtype=np.uint16)
+        meta = np.zeros((B, H, cap_s, Bt, (D // 4 + 7) // 8), dtype=np.uint32)
+    else:
+        nnz = np.zeros((B, H, cap_s, Bt // 4, 2, D), dtype=np.uint16)
+        meta = np.zeros((B, H, cap_s, Bt // 4, (D + 7) // 8), dtype=np.uint32)
+    for b in range(B):
+        for h in range(H):
+            for t in range(T):
+                m = mp[b, h, t]
+                tile = X_bits[b, h, t * Bt:(t + 1) * Bt]
+                if m > 0:
+                    dense[b, h, m - 1] = tile
+                elif m < 0:
+                    tm = mask[b, h, t * Bt:(t + 1) * Bt]
+                    if kind == "k":
+                        nnz[b, h, -m - 1], meta[b, h, -m - 1] = pack_k_tile(tile, tm)
+                    else:
+                        nnz[b, h, -m - 1], meta[b, h, -m - 1] = pack_v_tile(tile, tm)
+    return PackedKV(kind, Bt, D, mp, dense, nnz, meta)
+
+
+def unpack_tensor(p):
+    """Packed -> dense bf16 bits [B, Hkv, L, D] with zeros at pruned positions and
+    in skipped tiles."""
+    B, H, T = p.map.shape
+    out = np.zeros((B, H, T * p.Bt, p.D), dtype=np.uint16)
+    for b in range(B):
+        for h in range(H):
+            for t in range(T):
+                m = p.map[b, h, t]
+                if m > 0:
+                    out[b, h, t * p.Bt:(t + 1) * p.Bt] = p.dense[b, h, m - 1]
+                elif m < 0:
+                    if p.kind == "k":
+                        out[b, h, t * p.Bt:(t + 1) * p.Bt] = unpack_k_tile(p.nnz[b, h, -m - 1], p.meta[b, h, -m - 1])
+                    else:
+                        out[b, h, t * p.Bt:(t + 1) * p.Bt] = unpack_v_tile(p.nnz[b, h, -m - 1], p.meta[b, h, -m - 1])
+    return out
+
+
+def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0,
+                state_k=None, state_v=None):
+    """Whole compress step: element masks, tile states (policy or explicit),
+    maps, pools.  Returns (PackedKV for K, PackedKV for V, dict of intermediates)."""
+    K_bits = np.asarray(K_bits, dtype=np.uint16)
+    V_bits = np.asarray(V_bits, dtype=np.uint16)
+    mk = element_mask_k(K_bits)
+    mv = element_mask_v(V_bits)
+    info = {"mask_k": mk, "mask_v": mv}
+    if state_k is None:
+        energy = tile_energy(K_bits, V_bits, Bt)
+        loss_k = tile_prune_loss(K_bits, mk, Bt)
+        loss_v = tile_prune_loss(V_bits, mv, Bt)
+        state_k, state_v = select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v)
+        info.update(energy=energy, loss_k=loss_k, loss_v=loss_v)
+    state_k = np.asarray(state_k, dtype=np.int8)
+    state_v = np.asarray(state_v, dtype=np.int8)
+    assert ((state_k == SKIP) == (state_v == SKIP)).all(), "a skipped tile removes its tokens from K and V alike"
+    info.update(state_k=state_k, state_v=state_v)
+    pk = pack_tensor("k", K_bits, mk, state_k, Bt)
+    pv = pack_tensor("v", V_bits, mv, state_v, Bt)
+    return pk, pv, info
+
+
+# ----------------------------------------------------------------------------
+# attention (Eq. 1) over the decompressed cache
+# ----------------------------------------------------------------------------
+def _softmax_av(s, Vt):
+    """s [n] fp64 scores of the visible tokens, Vt [n, D].  Returns (o [D], lse)."""
+    if s.size == 0:
+        return np.zeros(Vt.shape[1], dtype=np.float64), -np.inf
+    m = s.max()
+    p = np.exp(s - m)
+    l = p.sum()
+    return (p @ Vt) / l, m + np.log(l)
+
+
+def attention_rows(Q_bits, pk, pv, rows, causal, scale=None, q_offset=None):
+    """Attention for selected query rows.
+
+    Q_bits [B, Hq, Lq, D]; rows = iterable of (b, hq, i).  Query i sees token j
+    iff j's tile is not SKIP and (not causal or j <= i + q_offset), with
+    q_offset = L - Lq by default.  Returns (O [n, D] fp64, LSE [n] fp64);
+    a row that sees nothing has O = 0, LSE = -inf.
+    """
+    Q_bits = np.asarray(Q_bits, dtype=np.uint16)
+    B, Hq, Lq, D = Q_bits.shape
+    Hkv = pk.map.shape[1]
+    G = Hq // Hkv
+    L = pk.map.shape[2] * pk.Bt
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    if q_offset is None:
+        q_offset = L - Lq
+    Kd = bf16_to_f64(unpack_tensor(pk))
+    Vd = bf16_to_f64(unpack_tensor(pv))
+    tok_visible = np.repeat(pk.map != 0, pk.Bt, axis=-1)       # [B, Hkv, L]
+    rows = list(rows)
+    O = np.zeros((len(rows), D), dtype=np.float64)
+    LSE = np.zeros(len(rows), dtype=np.float64)
+    for n, (b, hq, i) in enumerate(rows):
+        h = hq // G
+        vis = tok_visible[b, h].copy()
+        if causal:
+            vis[i + q_offset + 1:] = False
+        q = bf16_to_f64(Q_bits[b, hq, i])
+        s = (Kd[b, h][vis] @ q) * scale
+        O[n], LSE[n] = _softmax_av(s, Vd[b, h][vis])
+    return O, LSE
+
+
+def attention_decode(q_bits, pk, pv, scale=None):
+    """One new query token per (b, hq) against the whole cache.  q_bits [B, Hq, D].
+    Returns (O [B, Hq, D] fp64, LSE [B, Hq] fp64)."""
+    q_bits = np.asarray(q_bits, dtype=np.uint16)
+    B, Hq, D = q_bits.shape
+    rows = [(b, h, 0) for b in range(B) for h in range(Hq)]
+    O, LSE = attention_rows(q_bits[:, :, None, :], pk, pv, rows, causal=False, scale=scale)
+    return O.reshape(B, Hq, D), LSE.reshape(B, Hq)
+
+
+# ----------------------------------------------------------------------------
+# analytical model (Sec. III-D)
+# ----------------------------------------------------------------------------
+def compression_ratio(S_K, S_V, Bt=None, D=None):
+    """r_comp of Sec. III-D; the 1/(B*D) index term is included when Bt, D are given."""
+    idx = 0.0 if Bt is None else 1.0 / (Bt * D)
+    return 1.0 / (1.0 - 0.21875 * (S_K + S_V) + idx)
+
+
+def ideal_prefill_speedup(S_K, S_V):
+    return 4.0 / (4.0 - (S_K + S_V))
+
+
+def ideal_decode_speedup(S_K, S_V):
+    return compression_ratio(S_K, S_V)

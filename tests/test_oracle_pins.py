@@ -1,0 +1,331 @@
+"""Pins for the CPU oracle against things other than itself: exhaustive
+invariants, closed forms the paper prints (Sec. III-D), an independent library
+attention routine, exact rational arithmetic and brute force in Python floats."""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hs_oracle as orc
+from paper_2604_16864_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _bits(vals):
+    return wl.f32_to_bf16_bits(np.asarray(vals, dtype=np.float32))
+
+
+# ---------------------------------------------------------------- element mask
+def test_top2_exhaustive_small_alphabet():
+    """Every 4-tuple over an alphabet with ties, signed zeros and sign flips:
+    exactly two kept; no dropped magnitude exceeds a kept one; among equal
+    magnitudes the kept ones are the leftmost (Eq. 2a-b with a strict count)."""
+    alphabet = _bits([0.0, -0.0, 0.5, -0.5, 1.0, -2.0, 3.0])
+    groups = np.array(list(itertools.product(alphabet, repeat=4)), dtype=np.uint16)
+    keep = orc._top2_of_4(groups)
+    mag = np.abs(wl.bf16_bits_to_f32(groups))
+    assert (keep.sum(axis=-1) == 2).all()
+    for g in range(groups.shape[0]):
+        k = keep[g]
+        kept_min = mag[g][k].min()
+        assert mag[g][~k].max() <= kept_min
+        # ties at the boundary: every dropped element equal to the smallest kept
+        # magnitude sits to the right of every kept element of that magnitude
+        tied_drop = [i for i in range(4) if not k[i] and mag[g][i] == kept_min]
+        tied_keep = [i for i in range(4) if k[i] and mag[g][i] == kept_min]
+        if tied_drop:
+            assert max(tied_keep) < min(tied_drop)
+
+
+def test_top2_all_bit_patterns_pairs():
+    """Magnitude order equals integer order of bits & 0x7fff for every finite bf16:
+    check the mask on groups built from random finite patterns against float abs."""
+    rng = np.random.default_rng(5)
+    bits = rng.integers(0, 1 << 16, size=(200000, 4), dtype=np.uint32).astype(np.uint16)
+    finite = ((bits >> 7) & 0xFF) != 0xFF
+    bits = bits[finite.all(axis=-1)]
+    keep = orc._top2_of_4(bits)
+    mag = np.abs(wl.bf16_bits_to_f32(bits).astype(np.float64))
+    assert (keep.sum(-1) == 2).all()
+    kept_min = np.where(keep, mag, np.inf).min(-1)
+    drop_max = np.where(~keep, mag, -np.inf).max(-1)
+    assert (drop_max <= kept_min).all()
+
+
+def test_mask_axes():
+    """K groups run along channels, V groups along tokens (Table II, Trans-Both)."""
+    K = _bits(np.arange(1, 1 + 8 * 8, dtype=np.float32).reshape(1, 1, 8, 8))
+    mk = orc.element_mask_k(K)
+    mv = orc.element_mask_v(K)
+    # increasing values: the last two of each group survive
+    assert (mk.reshape(8, 2, 4) == np.array([False, False, True, True])).all()
+    assert (mv.reshape(2, 4, 8).transpose(0, 2, 1) == np.array([False, False, True, True])).all()
+
+
+# ---------------------------------------------------------------- pack / unpack
+def _rand_kv(seed, B=2, H=2, L=32, D=16):
+    rng = np.random.default_rng(seed)
+    K = wl.normal_bf16(rng, (B, H, L, D))
+    V = wl.normal_bf16(rng, (B, H, L, D))
+    return K, V
+
+
+def test_roundtrip_bit_exact_and_nibbles():
+    K, V = _rand_kv(1, L=64, D=32)
+    # plant ties, zeros and negative zeros
+    K[0, 0, 3, :8] = _bits([1, 1, 1, 1, 0, -0.0, 0, 0])
+    V[0, 1, 4:8, 5] = _bits([-2, 2, 2, -2])
+    pk, pv, info = orc.compress_kv(K, V, Bt=16)
+    assert (orc.unpack_tensor(pk) == np.where(info["mask_k"], K, 0)).all()
+    assert (orc.unpack_tensor(pv) == np.where(info["mask_v"], V, 0)).all()
+    legal = {0x4, 0x8, 0xC, 0x9, 0xD, 0xE}
+    for p in (pk, pv):
+        nib = orc._words_to_nibbles(p.meta)
+        assert set(np.unique(nib).tolist()) <= legal
+    # ties keep the leftmost two, all-zero groups keep positions 0, 1
+    assert (info["mask_k"][0, 0, 3, :8] == [True, True, False, False, True, True, False, False]).all()
+    # the sign bit of a kept negative zero survives the round trip
+    assert orc.unpack_tensor(pk)[0, 0, 3, 5] == 0x8000
+
+
+def test_mixed_states_roundtrip_and_map():
+    K, V = _rand_kv(2, B=1, H=2, L=16 * 9, D=16)
+    S, Dn, Sp = orc.SKIP, orc.DENSE, orc.SPARSE24
+    sk = np.array([[[Dn, Sp, S, Sp, Dn, Dn, S, Sp, Sp], [Sp, Sp, Sp, S, S, Dn, Dn, Dn, Sp]]], dtype=np.int8)
+    sv = np.array([[[Sp, Sp, S, Dn, Dn, Sp, S, Dn, Sp], [Dn, Sp, Dn, S, S, Sp, Dn, Sp, Dn]]], dtype=np.int8)
+    pk, pv, info = orc.compress_kv(K, V, Bt=16, state_k=sk, state_v=sv)
+    for p, st, X, m in ((pk, sk, K, info["mask_k"]), (pv, sv, V, info["mask_v"])):
+        for h in range(2):
+            mp = p.map[0, h]
+            assert ((mp == 0) == (st[0, h] == S)).all()
+            assert (mp[st[0, h] == Dn] == np.arange(1, 1 + (st[0, h] == Dn).sum())).all()
+            assert (mp[st[0, h] == Sp] == -np.arange(1, 1 + (st[0, h] == Sp).sum())).all()
+        tile_state = np.repeat(st, 16, axis=-1)[..., None]
+        want = np.where(tile_state == Dn, X, np.where(tile_state == Sp, np.where(m, X, 0), 0))
+        assert (orc.unpack_tensor(p) == want).all()
+
+
+# ---------------------------------------------------------------- byte accounting
+def _golden_ratios():
+    rows, fr = [], {}
+    for line in open(os.path.join(GOLD, "paper_sec3d_ratios.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        if len(f) == 5:
+            rows.append(tuple(float(x) for x in f))
+        else:
+            fr[f[0]] = float(f[1])
+    return rows, fr
+
+
+def test_sizes_match_paper_sec3d():
+    rows, fr = _golden_ratios()
+    K, V = _rand_kv(3, B=1, H=1, L=64 * 4, D=128)
+    pk, pv, _ = orc.compress_kv(K, V, Bt=64)           # all tiles 2:4
+    dense_bytes = K.nbytes
+    assert pk.nnz.nbytes == fr["nnz"] * dense_bytes
+    assert pk.meta.nbytes == fr["meta"] * dense_bytes
+    assert pv.nnz.nbytes == fr["nnz"] * dense_bytes
+    assert pv.meta.nbytes == fr["meta"] * dense_bytes
+    assert pk.nnz[0, 0, 0].nbytes + pk.meta[0, 0, 0].nbytes == 9216
+    for S_K, S_V, r, sp, sd in rows:
+        assert round(orc.compression_ratio(S_K, S_V), 2) == r
+        assert round(orc.ideal_prefill_speedup(S_K, S_V), 2) == sp
+        assert round(orc.ideal_decode_speedup(S_K, S_V), 2) == sd
+    # measured bytes equal the model with the index term (Sec. V-B: achieves theory exactly);
+    # the map here is int32 per tile per tensor = 2 elements, the paper counts one
+    T = 4
+    total = pk.nbytes() + pv.nbytes()
+    assert total == 2 * T * 9216 + 2 * T * 4
+    model = 1.0 / (1.0 - 0.21875 * 2 + 2.0 / (64 * 128))
+    assert abs((2 * dense_bytes) / total - model) < 1e-12
+    # half the tiles sparse in K, all in V
+    sk = np.array([[[1, 2, 1, 2]]], dtype=np.int8)
+    sv = np.full((1, 1, 4), 2, dtype=np.int8)
+    pk, pv, _ = orc.compress_kv(K, V, Bt=64, state_k=sk, state_v=sv)
+    r = (2 * dense_bytes) / (pk.nbytes() + pv.nbytes() - 2 * T * 4)
+    assert round(r, 2) == 1.49
+
+
+# ---------------------------------------------------------------- tile selection
+def test_skip_selection_exact_rational():
+    """The skipped set is the n lowest-energy tiles, checked in exact arithmetic."""
+    K, V = _rand_kv(4, B=1, H=2, L=16 * 12, D=16)
+    # two tiles with identical content -> identical energy -> tie goes to the lower index
+    K[0, 0, 16 * 7:16 * 8] = K[0, 0, 16 * 2:16 * 3]
+    V[0, 0, 16 * 7:16 * 8] = V[0, 0, 16 * 2:16 * 3]
+    for frac in (0.0, 0.25, 0.5, 0.75):
+        pk, pv, info = orc.compress_kv(K, V, Bt=16, skip_frac=frac)
+        n = int(math.floor(frac * 12))
+        for h in range(2):
+            e = []
+            for t in range(12):
+                acc = Fraction(0)
+                for X in (K, V):
+                    for x in wl.bf16_bits_to_f32(X[0, h, 16 * t:16 * (t + 1)]).ravel():
+                        acc += Fraction(float(x)) ** 2
+                e.append(acc)
+            order = sorted(range(12), key=lambda t: (e[t], t))
+            assert set(np.nonzero(pk.map[0, h] == 0)[0].tolist()) == set(order[:n])
+            assert ((pk.map[0, h] == 0) == (pv.map[0, h] == 0)).all()
+    # force the tie to straddle the cut: make tiles 2 and 7 the lowest-energy ones
+    K[0, 0, 16 * 2:16 * 3] = 0
+    K[0, 0, 16 * 7:16 * 8] = 0
+    V[0, 0, 16 * 2:16 * 3] = 0
+    V[0, 0, 16 * 7:16 * 8] = 0
+    pk, _, _ = orc.compress_kv(K, V, Bt=16, skip_frac=1 / 12 + 1e-9)
+    assert np.nonzero(pk.map[0, 0] == 0)[0].tolist() == [2]
+
+
+def test_block_sparsity_by_pruning_loss_exact():
+    """Eq. 2c-d: the S fraction of kept blocks with the lowest L1 pruning loss go sparse."""
+    K, V = _rand_kv(6, B=1, H=1, L=16 * 8, D=16)
+    pk, pv, info = orc.compress_kv(K, V, Bt=16, skip_frac=0.25, sparse_frac_k=0.5, sparse_frac_v=1.0)
+    kept = np.nonzero(pk.map[0, 0] != 0)[0].tolist()
+    assert len(kept) == 6
+    loss = {}
+    for t in kept:
+        tile = wl.bf16_bits_to_f32(K[0, 0, 16 * t:16 * (t + 1)]).reshape(16, 4, 4)
+        acc = Fraction(0)
+        for row in tile.reshape(-1, 4):
+            a = sorted((abs(float(x)) for x in row))
+            acc += Fraction(a[0]) + Fraction(a[1])      # the two smallest magnitudes are removed
+        loss[t] = acc
+    want_sparse = set(sorted(kept, key=lambda t: (loss[t], t))[:3])
+    assert set(np.nonzero(pk.map[0, 0] < 0)[0].tolist()) == want_sparse
+    assert (pv.map[0, 0][kept] < 0).all()
+
+
+# ---------------------------------------------------------------- attention
+def _sdpa(Qf, Kf, Vf, mask=None, causal=False):
+    """Independent library routine: torch CPU scaled_dot_product_attention in fp64."""
+    q = torch.from_numpy(Qf).double()
+    k = torch.from_numpy(Kf).double()
+    v = torch.from_numpy(Vf).double()
+    G = q.shape[1] // k.shape[1]
+    k = k.repeat_interleave(G, dim=1)
+    v = v.repeat_interleave(G, dim=1)
+    m = None if mask is None else torch.from_numpy(mask)
+    return torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=m, is_causal=causal and m is None).numpy()
+
+
+def _f(bits):
+    return wl.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+@pytest.mark.parametrize("G", [1, 4])
+def test_attention_all_dense_equals_library_sdpa(G):
+    B, Hkv, L, D, Bt = 2, 2, 64, 32, 16
+    Q, K, V = wl.make_qkv(B, Hkv * G, Hkv, L, D, L, seed=11)
+    st = np.full((B, Hkv, L // Bt), orc.DENSE, dtype=np.int8)
+    pk, pv, _ = orc.compress_kv(K, V, Bt=Bt, state_k=st, state_v=st)
+    rows = [(b, h, i) for b in range(B) for h in range(Hkv * G) for i in range(L)]
+    O, LSE = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    ref = _sdpa(_f(Q), _f(K), _f(V), causal=True)
+    assert np.allclose(O.reshape(B, Hkv * G, L, D), ref, rtol=1e-10, atol=1e-12)
+    O2, _ = orc.attention_rows(Q, pk, pv, rows, causal=False)
+    ref2 = _sdpa(_f(Q), _f(K), _f(V), causal=False)
+    assert np.allclose(O2.reshape(B, Hkv * G, L, D), ref2, rtol=1e-10, atol=1e-12)
+    # LSE against a direct logsumexp of the score matrix
+    s = np.einsum("bhid,bhjd->bhij", _f(Q), np.repeat(_f(K), G, axis=1)) / math.sqrt(D)
+    lse_ref = torch.logsumexp(torch.from_numpy(s), dim=-1).numpy()
+    _, LSE2 = orc.attention_rows(Q, pk, pv, rows, causal=False)
+    assert np.allclose(LSE2.reshape(B, Hkv * G, L), lse_ref, rtol=1e-12)
+
+
+def test_attention_sparse24_equals_sdpa_on_masked_kv():
+    B, Hkv, G, L, D, Bt = 1, 2, 4, 64, 32, 16
+    Q, K, V = wl.make_qkv(B, Hkv * G, Hkv, L, D, L, seed=12)
+    pk, pv, info = orc.compress_kv(K, V, Bt=Bt)
+    rows = [(b, h, i) for b in range(B) for h in range(Hkv * G) for i in range(L)]
+    O, _ = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    ref = _sdpa(_f(Q), _f(K) * info["mask_k"], _f(V) * info["mask_v"], causal=True)
+    assert np.allclose(O.reshape(B, Hkv * G, L, D), ref, rtol=1e-10, atol=1e-12)
+
+
+def test_skipped_tiles_contribute_nothing():
+    """Decode: deleting the skipped tiles' tokens from K, V gives the same output.
+    Prefill: same with an additive -inf mask; rows that see nothing are zero."""
+    B, Hkv, G, L, D, Bt = 1, 2, 2, 96, 32, 16
+    Q, K, V = wl.make_qkv(B, Hkv * G, Hkv, L, D, L, seed=13)
+    st = np.full((B, Hkv, L // Bt), orc.SPARSE24, dtype=np.int8)
+    st[0, 0, [0, 3]] = orc.SKIP
+    st[0, 1, [1, 2, 5]] = orc.SKIP
+    pk, pv, info = orc.compress_kv(K, V, Bt=Bt, state_k=st, state_v=st)
+    Km, Vm = _f(K) * info["mask_k"], _f(V) * info["mask_v"]
+    q = Q[:, :, -1, :]
+    Od, LSEd = orc.attention_decode(q, pk, pv)
+    for h in range(Hkv):
+        keep = np.repeat(st[0, h] != orc.SKIP, Bt)
+        ref = _sdpa(_f(q)[:, h * G:(h + 1) * G, None, :], Km[:, h:h + 1][:, :, keep], Vm[:, h:h + 1][:, :, keep])
+        assert np.allclose(Od[:, h * G:(h + 1) * G], ref[:, :, 0], rtol=1e-10, atol=1e-12)
+    # prefill with boolean mask
+    rows = [(0, h, i) for h in range(Hkv * G) for i in range(L)]
+    O, LSE = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    O = O.reshape(Hkv * G, L, D)
+    LSE = LSE.reshape(Hkv * G, L)
+    for hq in range(Hkv * G):
+        h = hq // G
+        vis = np.repeat(st[0, h] != orc.SKIP, Bt)[None, :] & np.tril(np.ones((L, L), dtype=bool))
+        empty = ~vis.any(axis=-1)
+        ref = _sdpa(_f(Q)[:, hq:hq + 1], Km[:, h:h + 1], Vm[:, h:h + 1], mask=vis[None, None] | empty[None, None, :, None])
+        assert np.allclose(O[hq][~empty], ref[0, 0][~empty], rtol=1e-10, atol=1e-12)
+        assert (O[hq][empty] == 0).all() and np.isneginf(LSE[hq][empty]).all()
+        if h == 0:
+            assert empty[:Bt].all() and not empty[Bt:].any()
+
+
+def test_decode_equals_last_causal_row():
+    B, Hkv, G, L, D, Bt = 2, 1, 4, 64, 32, 16
+    Q, K, V = wl.make_qkv(B, Hkv * G, Hkv, L, D, L, seed=14)
+    pk, pv, _ = orc.compress_kv(K, V, Bt=Bt, skip_frac=0.25)
+    rows = [(b, h, L - 1) for b in range(B) for h in range(Hkv * G)]
+    O, LSE = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    Od, LSEd = orc.attention_decode(Q[:, :, -1, :], pk, pv)
+    assert np.allclose(O.reshape(B, Hkv * G, D), Od, rtol=1e-12, atol=1e-14)
+    assert np.allclose(LSE.reshape(B, Hkv * G), LSEd, rtol=1e-12)
+
+
+def test_brute_force_python_floats_tiny():
+    """Whole path (prune, skip, attention) redone with Python lists and math.exp."""
+    B, Hkv, G, L, D, Bt = 1, 1, 2, 16, 8, 4
+    Q, K, V = wl.make_qkv(B, Hkv * G, Hkv, L, D, L, seed=15)
+    st = np.array([[[2, 0, 1, 2]]], dtype=np.int8)
+    pk, pv, _ = orc.compress_kv(K, V, Bt=Bt, state_k=st, state_v=st)
+    Kf = wl.bf16_bits_to_f32(K)[0, 0].tolist()
+    Vf = wl.bf16_bits_to_f32(V)[0, 0].tolist()
+    Qf = wl.bf16_bits_to_f32(Q)[0].tolist()
+
+    def top2(vals):
+        order = sorted(range(4), key=lambda i: (-abs(vals[i]), i))[:2]
+        return [vals[i] if i in order else 0.0 for i in range(4)]
+
+    Kp = [row[:] for row in Kf]
+    Vp = [row[:] for row in Vf]
+    for t in range(4):
+        if st[0, 0, t] != 2:
+            continue
+        for tok in range(4 * t, 4 * t + 4):
+            for g in range(D // 4):
+                Kp[tok][4 * g:4 * g + 4] = top2(Kf[tok][4 * g:4 * g + 4])
+        for c in range(D):
+            col = top2([Vf[4 * t + j][c] for j in range(4)])
+            for j in range(4):
+                Vp[4 * t + j][c] = col[j]
+    rows = [(0, h, i) for h in range(2) for i in range(L)]
+    O, LSE = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    for n, (_, h, i) in enumerate(rows):
+        toks = [j for j in range(i + 1) if st[0, 0, j // Bt] != 0]
+        s = [sum(Qf[h][i][c] * Kp[j][c] for c in range(D)) / math.sqrt(D) for j in toks]
+        m = max(s)
+        p = [math.exp(x - m) for x in s]
+        l = sum(p)
+        o = [sum(p[a] * Vp[j][c] for a, j in enumerate(toks)) / l for c in range(D)]
+        assert np.allclose(O[n], o, rtol=1e-12, atol=1e-14)
+        assert abs(LSE[n] - (m + math.log(l))) < 1e-12
