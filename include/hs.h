@@ -26,6 +26,12 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#ifdef HS_BUILD
+#define HS_API __attribute__((visibility("default")))
+#else
+#define HS_API
+#endif
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -80,9 +86,11 @@ typedef struct {
  *   x_map    [B, Hkv, T] int32: +(slot+1) dense, -(slot+1) sparse, 0 skipped;
  *            slots are handed out in ascending tile order per pool (the two
  *            running counters of Sec. III-B).
- * Inside a tile the bytes are in matrix-core operand order (documented in
- * DESIGN notes of the repository and mirrored by hs_unpack_kv); the pools of a
- * capacity-0 kind may be NULL. */
+ * Inside a tile slot the bytes are in the order in which the lanes of the gfx950
+ * matrix instructions consume them (64 lanes x 16 B per chunk; the exact index
+ * formulas are in csrc/hs_common.h); hs_unpack_kv returns the logical content.
+ * The pools of a capacity-0 kind may be NULL.  All pool pointers must be 16-byte
+ * aligned. */
 typedef struct {
   void* k_dense; void* k_nnz; void* k_meta; int32_t* k_map;
   void* v_dense; void* v_nnz; void* v_meta; int32_t* v_map;
@@ -90,31 +98,31 @@ typedef struct {
 } hs_kv;
 
 /* Library version (major * 100 + minor). [host, pure] */
-int hs_version(void);
+HS_API int hs_version(void);
 
 /* Text for a status code. [host, pure] */
-const char* hs_strerror(int status);
+HS_API const char* hs_strerror(int status);
 
 /* Text of the last HIP error this thread saw inside the library. [host] */
-const char* hs_last_hip_error(void);
+HS_API const char* hs_last_hip_error(void);
 
 /* Tile counts a policy yields per (b, kv head): counts[0..4] = n_skip,
  * n_dense_k, n_sparse_k, n_dense_v, n_sparse_v.  With explicit states the
  * counts are the per-row maxima.  These are the pool capacities to allocate.
  * [host, pure] */
-int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_t counts[5]);
+HS_API int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_t counts[5]);
 
 /* Bytes of the packed cache for given capacities, whole batch:
  * bytes[0..7] = k_dense, k_nnz, k_meta, k_map, v_dense, v_nnz, v_meta, v_map.
  * (Sec. III-D byte accounting.) [host, pure] */
-int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t bytes[8]);
+HS_API int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t bytes[8]);
 
 /* Workspace bytes needed by each call.  [host, pure]
  *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto) */
-int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes);
+HS_API int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes);
 
 /* Number of KV splits hs_decode_attn uses when n_splits == 0. [host, pure] */
-int hs_decode_auto_splits(const hs_shape* shape);
+HS_API int hs_decode_auto_splits(const hs_shape* shape);
 
 /* Compress (Sec. III-A + III-B; fused top-2-of-4 compressor of Sec. IV-B).
  * K, V: bf16 [B, Hkv, L, D]; kv_strides = element strides of the b, head and
@@ -123,13 +131,13 @@ int hs_decode_auto_splits(const hs_shape* shape);
  * consecutive tokens of a channel (magnitude = bits & 0x7fff, ties to the lower
  * position).  Writes maps and pools of `out`; slots beyond the used count are
  * left untouched.  workspace: hs_workspace_bytes(op 0). */
-int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
+HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],
                    const hs_kv* out, void* workspace, void* stream);
 
 /* Inverse of the packing, for tests and debugging: dense bf16 [B, Hkv, L, D]
  * (contiguous) with zeros at pruned positions and in skipped tiles. */
-int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_out, void* stream);
+HS_API int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_out, void* stream);
 
 /* Prefill attention (Algorithm 1 with the mixed dense/sparse dispatch of
  * Sec. III-C-2).  Q: bf16 [B, Hq, Lq, D] contiguous, Lq % 64 == 0, Lq <= L.
@@ -137,7 +145,7 @@ int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_ou
  * j <= i + L - Lq).  scale == 0 selects 1/sqrt(D) (Eq. 1).
  * O: bf16 [B, Hq, Lq, D]; LSE: fp32 [B, Hq, Lq] or NULL.  A query that sees no
  * token gets O = 0, LSE = -inf. */
-int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal,
+HS_API int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal,
                     const void* Q, const hs_kv* kv, void* O, float* LSE,
                     void* workspace, void* stream);
 
@@ -145,7 +153,7 @@ int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal,
  * (b, query head) against all L cached tokens.  Q, O: bf16 [B, Hq, D];
  * LSE: fp32 [B, Hq] or NULL.  n_splits == 0 picks hs_decode_auto_splits.
  * workspace: hs_workspace_bytes(op 2, n_splits). */
-int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
+HS_API int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
                    const void* Q, const hs_kv* kv, void* O, float* LSE,
                    void* workspace, void* stream);
 

@@ -1,0 +1,220 @@
+"""ctypes binding over libhs.so: argument marshalling only.
+
+Every step of the hot path runs in the library's HIP kernels; PyTorch supplies
+device memory and the stream.  There is no fallback: if the library has not
+been built, `lib()` raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhs.so")
+_lib = None
+
+SKIP, DENSE, SPARSE24 = 0, 1, 2
+TILE = 64
+HEAD_DIM = 128
+TILE_DENSE_BYTES, TILE_NNZ_BYTES, TILE_META_BYTES = 16384, 8192, 1024
+
+
+class HsShape(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("L", C.c_int32), ("D", C.c_int32),
+                ("tile", C.c_int32)]
+
+
+class HsPolicy(C.Structure):
+    _fields_ = [("skip_frac", C.c_double), ("sparse_frac_k", C.c_double), ("sparse_frac_v", C.c_double),
+                ("state_k", C.c_void_p), ("state_v", C.c_void_p)]
+
+
+class HsKV(C.Structure):
+    _fields_ = [("k_dense", C.c_void_p), ("k_nnz", C.c_void_p), ("k_meta", C.c_void_p), ("k_map", C.c_void_p),
+                ("v_dense", C.c_void_p), ("v_nnz", C.c_void_p), ("v_meta", C.c_void_p), ("v_map", C.c_void_p),
+                ("cap_dense_k", C.c_int32), ("cap_sparse_k", C.c_int32), ("cap_dense_v", C.c_int32),
+                ("cap_sparse_v", C.c_int32)]
+
+
+EXPORTS = {
+    "hs_version": (C.c_int, []),
+    "hs_strerror": (C.c_char_p, [C.c_int]),
+    "hs_last_hip_error": (C.c_char_p, []),
+    "hs_tile_counts": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(C.c_int32)]),
+    "hs_kv_bytes": (C.c_int, [C.POINTER(HsShape), C.POINTER(C.c_int32), C.POINTER(C.c_size_t)]),
+    "hs_workspace_bytes": (C.c_int, [C.POINTER(HsShape), C.c_int, C.c_int32, C.POINTER(C.c_size_t)]),
+    "hs_decode_auto_splits": (C.c_int, [C.POINTER(HsShape)]),
+    "hs_compress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
+    "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_prefill_attn": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_float, C.c_int, C.c_void_p, C.POINTER(HsKV),
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p]),
+}
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if libhs.so is missing (no CPU fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is not built: run `python -m paper_2604_16864_amd.build` "
+                               "(or __graft_entry__.build()) first")
+        L = C.CDLL(_LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+class HsError(RuntimeError):
+    pass
+
+
+def _check(rc):
+    if rc != 0:
+        L = lib()
+        msg = L.hs_strerror(rc).decode()
+        if rc == -3:
+            msg += ": " + L.hs_last_hip_error().decode()
+        raise HsError(f"libhs error {rc}: {msg}")
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_shape(B, Hq, Hkv, L, D=HEAD_DIM, tile=TILE):
+    return HsShape(B, Hq, Hkv, L, D, tile)
+
+
+def make_policy(skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0, state_k=None, state_v=None):
+    """state_k/state_v: optional host int8 arrays [B, Hkv, T].  The returned object
+    keeps them alive."""
+    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None)
+    if state_k is not None:
+        sk = np.ascontiguousarray(state_k, dtype=np.int8)
+        sv = np.ascontiguousarray(state_v, dtype=np.int8)
+        p.state_k = sk.ctypes.data
+        p.state_v = sv.ctypes.data
+        p._keep = (sk, sv)
+    return p
+
+
+def tile_counts(shape, policy):
+    c = (C.c_int32 * 5)()
+    _check(lib().hs_tile_counts(C.byref(shape), C.byref(policy), c))
+    return list(c)
+
+
+def kv_bytes(shape, counts):
+    c = (C.c_int32 * 5)(*counts)
+    b = (C.c_size_t * 8)()
+    _check(lib().hs_kv_bytes(C.byref(shape), c, b))
+    return list(b)
+
+
+def workspace_bytes(shape, op, arg=0):
+    out = C.c_size_t(0)
+    _check(lib().hs_workspace_bytes(C.byref(shape), op, arg, C.byref(out)))
+    return out.value
+
+
+def decode_auto_splits(shape):
+    return lib().hs_decode_auto_splits(C.byref(shape))
+
+
+class PackedKV:
+    """Caller-owned device buffers of a packed cache (torch uint8 / int32 tensors)."""
+
+    def __init__(self, shape, counts, device="cuda"):
+        self.shape = shape
+        self.counts = list(counts)
+        nb = kv_bytes(shape, counts)
+        rows_T = (shape.B, shape.Hkv, shape.L // TILE)
+
+        def buf(n):
+            return torch.empty(n, dtype=torch.uint8, device=device) if n else None
+
+        self.k_dense, self.k_nnz, self.k_meta = buf(nb[0]), buf(nb[1]), buf(nb[2])
+        self.v_dense, self.v_nnz, self.v_meta = buf(nb[4]), buf(nb[5]), buf(nb[6])
+        self.k_map = torch.empty(rows_T, dtype=torch.int32, device=device)
+        self.v_map = torch.empty(rows_T, dtype=torch.int32, device=device)
+        self.nbytes = sum(nb)
+
+    def struct(self):
+        return HsKV(_ptr(self.k_dense), _ptr(self.k_nnz), _ptr(self.k_meta), _ptr(self.k_map),
+                    _ptr(self.v_dense), _ptr(self.v_nnz), _ptr(self.v_meta), _ptr(self.v_map),
+                    self.counts[1], self.counts[2], self.counts[3], self.counts[4])
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+
+
+def compress_kv(shape, policy, K, V, out=None, workspace=None):
+    """K, V: bf16 device tensors [B, Hkv, L, D] (last dim contiguous).  Returns PackedKV."""
+    assert K.dtype == torch.bfloat16 and V.dtype == torch.bfloat16 and K.is_cuda and V.is_cuda
+    assert K.stride(-1) == 1 and V.stride(-1) == 1 and K.stride() == V.stride()
+    if out is None:
+        out = PackedKV(shape, tile_counts(shape, policy), K.device)
+    if workspace is None:
+        workspace = _workspace(workspace_bytes(shape, 0), K.device)
+    strides = (C.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
+    kvs = out.struct()
+    _check(lib().hs_compress_kv(C.byref(shape), C.byref(policy), _ptr(K), _ptr(V), strides, C.byref(kvs),
+                                _ptr(workspace), _stream()))
+    return out
+
+
+def unpack_kv(shape, kv):
+    K = torch.empty((shape.B, shape.Hkv, shape.L, shape.D), dtype=torch.bfloat16, device=kv.k_map.device)
+    V = torch.empty_like(K)
+    kvs = kv.struct()
+    _check(lib().hs_unpack_kv(C.byref(shape), C.byref(kvs), _ptr(K), _ptr(V), _stream()))
+    return K, V
+
+
+def prefill_attn(shape, Q, kv, causal=True, scale=0.0, want_lse=True, out=None, lse=None):
+    """Q: bf16 [B, Hq, Lq, D] contiguous.  Returns (O bf16 [B, Hq, Lq, D], LSE fp32 [B, Hq, Lq] or None)."""
+    assert Q.dtype == torch.bfloat16 and Q.is_contiguous() and Q.is_cuda
+    Lq = Q.shape[2]
+    O = torch.empty_like(Q) if out is None else out
+    if lse is None and want_lse:
+        lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    kvs = kv.struct()
+    _check(lib().hs_prefill_attn(C.byref(shape), Lq, float(scale), int(bool(causal)), _ptr(Q), C.byref(kvs), _ptr(O),
+                                 _ptr(lse), None, _stream()))
+    return O, lse
+
+
+def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, lse=None, workspace=None):
+    """Q: bf16 [B, Hq, D] contiguous.  Returns (O bf16 [B, Hq, D], LSE fp32 [B, Hq] or None)."""
+    assert Q.dtype == torch.bfloat16 and Q.is_contiguous() and Q.is_cuda
+    O = torch.empty_like(Q) if out is None else out
+    if lse is None and want_lse:
+        lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
+    if workspace is None:
+        workspace = _workspace(workspace_bytes(shape, 2, n_splits), Q.device)
+    kvs = kv.struct()
+    _check(lib().hs_decode_attn(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(O),
+                                _ptr(lse), _ptr(workspace), _stream()))
+    return O, lse
+
+
+def bits_to_bf16_tensor(bits, device="cuda"):
+    """numpy uint16 bit patterns -> torch bf16 tensor on the device (same bits)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.to(device).view(torch.bfloat16)
+
+
+def bf16_tensor_to_bits(t):
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

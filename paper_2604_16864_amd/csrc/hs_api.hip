@@ -1,0 +1,280 @@
+// C ABI of libhs: host-side validation, capacity arithmetic and kernel dispatch.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "hs_common.h"
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e) {
+  snprintf(g_hip_err, sizeof(g_hip_err), "%s", hipGetErrorString(e));
+  return HS_EHIP;
+}
+
+int check_shape(const hs_shape* s) {
+  if (s == nullptr) return HS_EINVAL;
+  if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->L <= 0) return HS_EINVAL;
+  if (s->D != HS_D || s->tile != HS_BT) return HS_EUNSUPPORTED;
+  if (s->L % HS_BT != 0 || s->Hq % s->Hkv != 0) return HS_EUNSUPPORTED;
+  if (s->Hq / s->Hkv > 8) return HS_EUNSUPPORTED;
+  if (s->B > 65535 || s->Hkv > 65535) return HS_EUNSUPPORTED;
+  return HS_OK;
+}
+
+bool frac_ok(double f) { return f >= 0.0 && f <= 1.0; }
+
+// Tile counts of a fraction policy (same for every row).
+void policy_counts(int T, const hs_policy* p, int32_t c[5]) {
+  const int n_skip = (int)floor(p->skip_frac * T);
+  const int n_keep = T - n_skip;
+  const int nsk = (int)floor(p->sparse_frac_k * n_keep);
+  const int nsv = (int)floor(p->sparse_frac_v * n_keep);
+  c[0] = n_skip; c[1] = n_keep - nsk; c[2] = nsk; c[3] = n_keep - nsv; c[4] = nsv;
+}
+
+int check_policy(const hs_policy* p) {
+  if (p == nullptr) return HS_EINVAL;
+  if ((p->state_k == nullptr) != (p->state_v == nullptr)) return HS_EINVAL;
+  if (p->state_k == nullptr) {
+    if (!(p->skip_frac >= 0.0 && p->skip_frac < 1.0)) return HS_EINVAL;
+    if (!frac_ok(p->sparse_frac_k) || !frac_ok(p->sparse_frac_v)) return HS_EINVAL;
+  }
+  return HS_OK;
+}
+
+// Explicit states: validate and count (per-row maxima).
+int explicit_counts(const hs_shape* s, const hs_policy* p, int32_t c[5]) {
+  const int T = s->L / HS_BT;
+  const int64_t rows = (int64_t)s->B * s->Hkv;
+  for (int i = 0; i < 5; i++) c[i] = 0;
+  for (int64_t r = 0; r < rows; r++) {
+    int n[5] = {0, 0, 0, 0, 0};
+    for (int t = 0; t < T; t++) {
+      const int sk = p->state_k[r * T + t], sv = p->state_v[r * T + t];
+      if (sk < 0 || sk > 2 || sv < 0 || sv > 2) return HS_EINVAL;
+      if ((sk == HS_SKIP) != (sv == HS_SKIP)) return HS_EINVAL;
+      n[0] += sk == HS_SKIP;
+      n[1] += sk == HS_DENSE; n[2] += sk == HS_SPARSE24;
+      n[3] += sv == HS_DENSE; n[4] += sv == HS_SPARSE24;
+    }
+    for (int i = 0; i < 5; i++) c[i] = n[i] > c[i] ? n[i] : c[i];
+  }
+  return HS_OK;
+}
+
+int check_kv(const hs_shape* s, const hs_kv* kv) {
+  if (kv == nullptr || kv->k_map == nullptr || kv->v_map == nullptr) return HS_EINVAL;
+  if (kv->cap_dense_k < 0 || kv->cap_sparse_k < 0 || kv->cap_dense_v < 0 || kv->cap_sparse_v < 0) return HS_EINVAL;
+  if (kv->cap_dense_k > 0 && kv->k_dense == nullptr) return HS_EINVAL;
+  if (kv->cap_sparse_k > 0 && (kv->k_nnz == nullptr || kv->k_meta == nullptr)) return HS_EINVAL;
+  if (kv->cap_dense_v > 0 && kv->v_dense == nullptr) return HS_EINVAL;
+  if (kv->cap_sparse_v > 0 && (kv->v_nnz == nullptr || kv->v_meta == nullptr)) return HS_EINVAL;
+  const uintptr_t align = (uintptr_t)kv->k_dense | (uintptr_t)kv->k_nnz | (uintptr_t)kv->k_meta |
+                          (uintptr_t)kv->v_dense | (uintptr_t)kv->v_nnz | (uintptr_t)kv->v_meta;
+  if (align & 15u) return HS_EINVAL;
+  (void)s;
+  return HS_OK;
+}
+
+constexpr int kSelectMaxTiles = 65536;  // O(T^2) ranking: 4M tokens per row
+
+}  // namespace
+
+extern "C" {
+
+int hs_version(void) { return 100; }
+
+const char* hs_strerror(int status) {
+  switch (status) {
+    case HS_OK: return "ok";
+    case HS_EINVAL: return "invalid argument";
+    case HS_EUNSUPPORTED: return "unsupported shape or option";
+    case HS_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* hs_last_hip_error(void) { return g_hip_err; }
+
+int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_t counts[5]) {
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_policy(policy);
+  if (rc != HS_OK) return rc;
+  if (counts == nullptr) return HS_EINVAL;
+  if (policy->state_k != nullptr) return explicit_counts(shape, policy, counts);
+  policy_counts(shape->L / HS_BT, policy, counts);
+  return HS_OK;
+}
+
+int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t bytes[8]) {
+  const int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  if (counts == nullptr || bytes == nullptr) return HS_EINVAL;
+  const size_t rows = (size_t)shape->B * shape->Hkv;
+  const size_t T = (size_t)(shape->L / HS_BT);
+  bytes[0] = rows * (size_t)counts[1] * HS_TILE_DENSE_BYTES;
+  bytes[1] = rows * (size_t)counts[2] * HS_TILE_NNZ_BYTES;
+  bytes[2] = rows * (size_t)counts[2] * HS_TILE_META_BYTES;
+  bytes[3] = rows * T * sizeof(int32_t);
+  bytes[4] = rows * (size_t)counts[3] * HS_TILE_DENSE_BYTES;
+  bytes[5] = rows * (size_t)counts[4] * HS_TILE_NNZ_BYTES;
+  bytes[6] = rows * (size_t)counts[4] * HS_TILE_META_BYTES;
+  bytes[7] = rows * T * sizeof(int32_t);
+  return HS_OK;
+}
+
+int hs_decode_auto_splits(const hs_shape* shape) {
+  if (check_shape(shape) != HS_OK) return 0;
+  const int T = shape->L / HS_BT;
+  const int rows = shape->B * shape->Hkv;
+  // about 3 workgroups per compute unit, each wave of a workgroup getting >= 1 tile
+  int n = (768 + rows - 1) / rows;
+  const int max_n = (T + 3) / 4;
+  if (n > max_n) n = max_n;
+  if (n < 1) n = 1;
+  return n;
+}
+
+int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes) {
+  const int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  if (bytes == nullptr) return HS_EINVAL;
+  const size_t rows = (size_t)shape->B * shape->Hkv;
+  const size_t T = (size_t)(shape->L / HS_BT);
+  switch (op) {
+    case 0: *bytes = 3 * rows * T * sizeof(double); return HS_OK;
+    case 1: *bytes = 0; return HS_OK;
+    case 2: {
+      int n = arg == 0 ? hs_decode_auto_splits(shape) : arg;
+      if (n < 1) return HS_EINVAL;
+      *bytes = (size_t)shape->B * shape->Hq * (size_t)n * (HS_D + 1) * sizeof(float);
+      return HS_OK;
+    }
+    default: return HS_EINVAL;
+  }
+}
+
+int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K, const void* V,
+                   const int64_t kv_strides[3], const hs_kv* out, void* workspace, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_policy(policy);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, out);
+  if (rc != HS_OK) return rc;
+  if (K == nullptr || V == nullptr) return HS_EINVAL;
+  if (((uintptr_t)K | (uintptr_t)V) & 15u) return HS_EINVAL;
+  const int T = shape->L / HS_BT;
+  const int rows = shape->B * shape->Hkv;
+  int64_t sb = (int64_t)shape->Hkv * shape->L * HS_D, sh = (int64_t)shape->L * HS_D, st = HS_D;
+  if (kv_strides != nullptr) { sb = kv_strides[0]; sh = kv_strides[1]; st = kv_strides[2]; }
+  if (st < HS_D || sb < 0 || sh < 0 || (sb | sh | st) % 8 != 0) return HS_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  int32_t c[5];
+  hipError_t e;
+  if (policy->state_k != nullptr) {
+    // explicit states [host]: walk the tiles in order with one counter per pool (Sec. III-B)
+    rc = explicit_counts(shape, policy, c);
+    if (rc != HS_OK) return rc;
+    if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
+      return HS_EINVAL;
+    std::vector<int32_t> mk((size_t)rows * T), mv((size_t)rows * T);
+    for (int r = 0; r < rows; r++) {
+      int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
+      for (int t = 0; t < T; t++) {
+        const size_t i = (size_t)r * T + t;
+        const int sk = policy->state_k[i], sv = policy->state_v[i];
+        mk[i] = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
+        mv[i] = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
+      }
+    }
+    // synchronous copies: the host vectors die at return
+    e = hipMemcpyAsync(out->k_map, mk.data(), mk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipMemcpyAsync(out->v_map, mv.data(), mv.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e);
+  } else {
+    policy_counts(T, policy, c);
+    if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
+      return HS_EINVAL;
+    const bool uniform_k = c[1] == 0 || c[2] == 0, uniform_v = c[3] == 0 || c[4] == 0;
+    if (c[0] == 0 && uniform_k && uniform_v) {
+      // no ranking needed: every tile in one state
+      e = hs_launch_fill_maps(out->k_map, out->v_map, rows, T, c[2] ? HS_SPARSE24 : HS_DENSE,
+                              c[4] ? HS_SPARSE24 : HS_DENSE, s);
+      if (e != hipSuccess) return hip_fail(e);
+    } else {
+      if (workspace == nullptr || ((uintptr_t)workspace & 7u)) return HS_EINVAL;
+      if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
+      e = hs_launch_score((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
+                          (double*)workspace, s);
+      if (e != hipSuccess) return hip_fail(e);
+      e = hs_launch_select((const double*)workspace, rows, T, c[0], c[2], c[4], out->k_map, out->v_map, s);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+  }
+  e = hs_launch_pack((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
+                     hs_make_kv_dev(out), s);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
+int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, kv);
+  if (rc != HS_OK) return rc;
+  if (K_out == nullptr || V_out == nullptr || (((uintptr_t)K_out | (uintptr_t)V_out) & 15u)) return HS_EINVAL;
+  const hipError_t e = hs_launch_unpack(shape->B, shape->Hkv, shape->L / HS_BT, hs_make_kv_dev(kv),
+                                        (uint16_t*)K_out, (uint16_t*)V_out, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
+int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal, const void* Q, const hs_kv* kv,
+                    void* O, float* LSE, void* workspace, void* stream) {
+  (void)workspace;
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, kv);
+  if (rc != HS_OK) return rc;
+  if (Q == nullptr || O == nullptr || (((uintptr_t)Q | (uintptr_t)O) & 15u)) return HS_EINVAL;
+  if (Lq <= 0 || Lq > shape->L) return HS_EINVAL;
+  if (Lq % HS_BT != 0) return HS_EUNSUPPORTED;
+  if (!(scale >= 0.f)) return HS_EINVAL;
+  if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
+  const hipError_t e = hs_launch_prefill(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, Lq / HS_BT, scale,
+                                         causal != 0, (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
+                                         (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
+int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
+                   float* LSE, void* workspace, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, kv);
+  if (rc != HS_OK) return rc;
+  if (Q == nullptr || O == nullptr || workspace == nullptr) return HS_EINVAL;
+  if (((uintptr_t)Q | (uintptr_t)workspace) & 15u) return HS_EINVAL;
+  if (n_splits < 0 || n_splits > 65535) return HS_EINVAL;
+  if (!(scale >= 0.f)) return HS_EINVAL;
+  if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
+  if (n_splits == 0) n_splits = hs_decode_auto_splits(shape);
+  const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
+                                        (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
+                                        (float*)workspace, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
+}  // extern "C"

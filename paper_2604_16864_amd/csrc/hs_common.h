@@ -1,0 +1,85 @@
+// Internal definitions shared by the HIP translation units of libhs (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "hs.h"
+
+// ---------------------------------------------------------------------------------
+// Matrix-core operand layouts on gfx950 (measured with one-hot operands):
+//
+//  v_mfma_f32_16x16x32_bf16   A: lane l holds row l%16,  k = 8*(l/16) + e, e = 0..7
+//                             B: lane l holds col l%16,  k = 8*(l/16) + e
+//                             D: lane l holds col l%16,  rows 4*(l/16) + i, i = 0..3
+//  v_smfmac_f32_16x16x64_bf16 A: lane l holds row l%16 and the 8 kept values of the
+//                                16 uncompressed k = 16*(l/16) .. +15 (4 groups of 4,
+//                                2 kept each, ascending position)
+//                             B: lane l holds col l%16,  k = 32*(e/8) + 8*(l/16) + e%8,
+//                                e = 0..15  (= the B operands of two consecutive dense
+//                                16x16x32 steps, so dense and sparse tiles share Q/P
+//                                registers; cf. the shared P^T fragment of Sec. IV-A)
+//                             idx: 2 bits per kept value (its position in the group),
+//                                value e at bits 2e..2e+1 of the 16-bit half selected
+//                                by ABID bit 0 (CBSZ = 0)
+//                             D: as the dense instruction.
+//
+// Physical order inside a tile slot = the order the lanes consume it ("chunks" of
+// 64 lanes x 16 B, lane l at byte 16*l of its chunk; a = l/16, r = l%16):
+//
+//  K 2:4  nnz : chunk m*2+kb (m = 0..3, kb = 0..1): token 16m+r, kept values of channel
+//               groups 16kb+4a+q, q = 0..3 (channels 4*group .. +3), lower position first.
+//         meta: word [m][l] (u32): bits 0..15 idx for kb = 0, bits 16..31 for kb = 1;
+//               nibble q (bits 4q..4q+3 of the half) = i0 | i1<<2 of group 16kb+4a+q.
+//  V 2:4  nnz : chunk mb (0..7): channel 16mb+r, kept values of token groups
+//               g(a,q) = 4*(2*(a/2) + q%2) + 2*(a%2) + q/2, q = 0..3 (tokens 4g..4g+3).
+//         meta: word [mb/2][l]: low half mb even, high half mb odd; nibble q as above.
+//  K dense    : chunk m*4+s (s = 0..3): token 16m+r, channels 32s+8a+e, e = 0..7.
+//  V dense    : chunk mb*2+h (h = 0..1): channel 16mb+r, tokens 16*(2h+e/4)+4a+e%4.
+//
+// The token order of V is the one in which GEMM1's accumulator registers (lane holds
+// tokens 16m+4a+i of its query column) line up, after conversion to bf16, as GEMM2's B
+// operand with no cross-lane movement (the problem Sec. IV-C-2 solves with movmatrix).
+// ---------------------------------------------------------------------------------
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+#define HS_D 128
+#define HS_BT 64
+
+struct hs_kv_dev {  // device-side view of hs_kv (passed by value to kernels)
+  const uint8_t* k_dense; const uint8_t* k_nnz; const uint8_t* k_meta; const int32_t* k_map;
+  const uint8_t* v_dense; const uint8_t* v_nnz; const uint8_t* v_meta; const int32_t* v_map;
+  int32_t cap_dense_k, cap_sparse_k, cap_dense_v, cap_sparse_v;
+};
+
+static inline hs_kv_dev hs_make_kv_dev(const hs_kv* kv) {
+  hs_kv_dev d;
+  d.k_dense = (const uint8_t*)kv->k_dense; d.k_nnz = (const uint8_t*)kv->k_nnz;
+  d.k_meta = (const uint8_t*)kv->k_meta;   d.k_map = kv->k_map;
+  d.v_dense = (const uint8_t*)kv->v_dense; d.v_nnz = (const uint8_t*)kv->v_nnz;
+  d.v_meta = (const uint8_t*)kv->v_meta;   d.v_map = kv->v_map;
+  d.cap_dense_k = kv->cap_dense_k; d.cap_sparse_k = kv->cap_sparse_k;
+  d.cap_dense_v = kv->cap_dense_v; d.cap_sparse_v = kv->cap_sparse_v;
+  return d;
+}
+
+// token group of V held at pair q of lane group a (see layout note above)
+__host__ __device__ static inline int hs_v_group(int a, int q) {
+  return 4 * (2 * (a >> 1) + (q & 1)) + 2 * (a & 1) + (q >> 1);
+}
+
+// launchers implemented in the kernel translation units; all return a hipError_t
+hipError_t hs_launch_fill_maps(int32_t* k_map, int32_t* v_map, int rows, int T, int state_k, int state_v,
+                               hipStream_t st);
+hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
+                           int B, int Hkv, int T, double* scores, hipStream_t st);
+hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
+                            int32_t* k_map, int32_t* v_map, hipStream_t st);
+hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
+                          int B, int Hkv, int T, hs_kv_dev kv, hipStream_t st);
+hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
+hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
+                            hs_kv_dev kv, uint16_t* O, float* LSE, float* ws, hipStream_t st);
+hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
+                             hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st);

@@ -1,0 +1,426 @@
+// Compress path: tile scoring, tile selection, fused 2:4 prune + pack, and unpack.
+// Paper: hierarchical pruner Sec. III-A (Eq. 2a-d), cache compressor Sec. III-B,
+// fused magnitude compressor Sec. IV-B.
+#include "hs_common.h"
+
+namespace {
+
+constexpr int kVStride = 132;  // LDS row stride (elements) of a staged V tile: 8-byte aligned rows, shifted banks
+
+// Top-2-of-4 by magnitude (Eq. 2a-b with an exact count of two): x0..x3 are bf16 bit
+// patterns; element j outranks element i if |x_j| > |x_i|, or |x_j| == |x_i| and j < i.
+// Returns the 4-bit keep mask (exactly two bits set).
+__device__ __forceinline__ uint32_t top2_mask(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3) {
+  const uint32_t k0 = x0 & 0x7fffu, k1 = x1 & 0x7fffu, k2 = x2 & 0x7fffu, k3 = x3 & 0x7fffu;
+  const uint32_t g01 = k0 >= k1, g02 = k0 >= k2, g03 = k0 >= k3, g12 = k1 >= k2, g13 = k1 >= k3, g23 = k2 >= k3;
+  const uint32_t c0 = 3u - g01 - g02 - g03;        // how many outrank element 0
+  const uint32_t c1 = g01 + 2u - g12 - g13;
+  const uint32_t c2 = g02 + g12 + 1u - g23;
+  const uint32_t c3 = g03 + g13 + g23;
+  return (c0 < 2u) | ((c1 < 2u) << 1) | ((c2 < 2u) << 2) | ((c3 < 2u) << 3);
+}
+
+// From the keep mask: the two kept values packed (lower position in the low half) and
+// the metadata nibble i0 | i1 << 2 (Sec. IV-B: 2-bit position of each kept element).
+__device__ __forceinline__ void top2_emit(uint32_t mask, uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3,
+                                          uint32_t& vals, uint32_t& nib) {
+  const uint32_t i0 = (uint32_t)__builtin_ctz(mask);
+  const uint32_t i1 = 31u - (uint32_t)__builtin_clz(mask);
+  const uint32_t v0 = (mask & 1u) ? x0 : ((mask & 2u) ? x1 : x2);
+  const uint32_t v1 = (mask & 8u) ? x3 : ((mask & 4u) ? x2 : x1);
+  vals = (v0 & 0xffffu) | (v1 << 16);
+  nib = i0 | (i1 << 2);
+}
+
+__device__ __forceinline__ double bf16_val(uint32_t bits) { return (double)__uint_as_float(bits << 16); }
+
+// ----------------------------------------------------------------------------------
+// uniform maps: every tile of every row in the same state
+// ----------------------------------------------------------------------------------
+__global__ void fill_maps_kernel(int32_t* k_map, int32_t* v_map, int rows, int T, int state_k, int state_v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)rows * T) return;
+  const int t = (int)(i % T);
+  k_map[i] = state_k == HS_DENSE ? t + 1 : (state_k == HS_SPARSE24 ? -(t + 1) : 0);
+  v_map[i] = state_v == HS_DENSE ? t + 1 : (state_v == HS_SPARSE24 ? -(t + 1) : 0);
+}
+
+// ----------------------------------------------------------------------------------
+// Staging of one V tile [64 tokens][128 ch] into LDS with coalesced 16-byte loads.
+// ----------------------------------------------------------------------------------
+__device__ __forceinline__ void stage_v_tile(const uint16_t* vt, int64_t tok_stride, uint16_t* lds) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int q = tid + 256 * i;
+    const int tok = q >> 4, c8 = q & 15;
+    const uint4 d = *reinterpret_cast<const uint4*>(vt + tok * tok_stride + 8 * c8);
+    uint2* dst = reinterpret_cast<uint2*>(lds + tok * kVStride + 8 * c8);
+    dst[0] = make_uint2(d.x, d.y);
+    dst[1] = make_uint2(d.z, d.w);
+  }
+}
+
+// ----------------------------------------------------------------------------------
+// Tile scores: energy = sum K^2 + sum V^2 (skip ranking), loss_x = L1 norm of what the
+// 2:4 mask removes (Eq. 2c).  fp64, fixed reduction order.  scores = [3][rows][T].
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T,
+                                                    double* __restrict__ scores) {
+  __shared__ uint16_t vl[HS_BT * kVStride];
+  __shared__ double red[3][4];
+  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
+  const uint16_t* kt = K + b * sb + h * sh + (int64_t)t * HS_BT * st;
+  const uint16_t* vt = V + b * sb + h * sh + (int64_t)t * HS_BT * st;
+  stage_v_tile(vt, st, vl);
+  double e = 0.0, lk = 0.0, lv = 0.0;
+  {  // K: this thread owns token 16w+r, channels 64kb+16a .. +15
+    const uint16_t* row = kt + (int64_t)(16 * w + r) * st;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      const uint4 d0 = *reinterpret_cast<const uint4*>(row + 64 * kb + 16 * a);
+      const uint4 d1 = *reinterpret_cast<const uint4*>(row + 64 * kb + 16 * a + 8);
+      const uint32_t wds[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
+        const uint32_t m = top2_mask(x0, x1, x2, x3);
+        const double f0 = bf16_val(x0), f1 = bf16_val(x1), f2 = bf16_val(x2), f3 = bf16_val(x3);
+        e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
+        lk += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
+      }
+    }
+  }
+  __syncthreads();
+  {  // V: channel 16mb+r for mb = 2w, 2w+1; token groups of lane group a
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int c = 16 * (2 * w + j) + r;
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int g = hs_v_group(a, q);
+        const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
+        const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
+        const uint32_t m = top2_mask(x0, x1, x2, x3);
+        const double f0 = bf16_val(x0), f1 = bf16_val(x1), f2 = bf16_val(x2), f3 = bf16_val(x3);
+        e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
+        lv += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
+      }
+    }
+  }
+  // wave reduction (fixed butterfly), then 4 partials in LDS
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    e += __shfl_xor(e, off);
+    lk += __shfl_xor(lk, off);
+    lv += __shfl_xor(lv, off);
+  }
+  if (l == 0) { red[0][w] = e; red[1][w] = lk; red[2][w] = lv; }
+  __syncthreads();
+  if (tid < 3) {
+    const int64_t rows = (int64_t)gridDim.z * Hkv;
+    const int64_t row = (int64_t)b * Hkv + h;
+    scores[(tid * rows + row) * T + t] = (red[tid][0] + red[tid][1]) + (red[tid][2] + red[tid][3]);
+  }
+}
+
+// ----------------------------------------------------------------------------------
+// Tile selection per (b, kv head) row (Eq. 2d + the skip extension) and slot assignment
+// (the two sequential counters of Sec. III-B, done as an exclusive prefix count).
+// One workgroup per row; ranks by counting, O(T^2) compares.
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ scores, int rows, int T, int n_skip,
+                                                     int n_sparse_k, int n_sparse_v, int32_t* __restrict__ k_map,
+                                                     int32_t* __restrict__ v_map) {
+  __shared__ int cnt[3][256];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const double* en = scores + ((int64_t)0 * rows + row) * T;
+  const double* lk = scores + ((int64_t)1 * rows + row) * T;
+  const double* lv = scores + ((int64_t)2 * rows + row) * T;
+  int32_t* km = k_map + (int64_t)row * T;
+  int32_t* vm = v_map + (int64_t)row * T;
+  // pass 1: skip flags, parked in the maps as 0 (skip) / 1 (kept)
+  for (int t = tid; t < T; t += 256) {
+    const double e = en[t];
+    int rank = 0;
+    for (int u = 0; u < T; u++) {
+      const double eu = en[u];
+      rank += (eu < e) || (eu == e && u < t);
+    }
+    km[t] = rank >= n_skip;
+  }
+  __syncthreads();
+  // pass 2: among kept tiles, rank by pruning loss; state: 0 skip, 1 dense, 2 sparse
+  for (int t = tid; t < T; t += 256) {
+    int sk = 0, sv = 0;
+    if (km[t] != 0) {
+      const double a = lk[t], c = lv[t];
+      int rk = 0, rv = 0;
+      for (int u = 0; u < T; u++) {
+        if (km[u] == 0) continue;
+        const double au = lk[u], cu = lv[u];
+        rk += (au < a) || (au == a && u < t);
+        rv += (cu < c) || (cu == c && u < t);
+      }
+      sk = rk < n_sparse_k ? HS_SPARSE24 : HS_DENSE;
+      sv = rv < n_sparse_v ? HS_SPARSE24 : HS_DENSE;
+    }
+    vm[t] = sk | (sv << 8);
+  }
+  __syncthreads();
+  // pass 3: slots in ascending tile order; each thread owns a contiguous chunk
+  const int per = (T + 255) / 256;
+  const int t0 = min(tid * per, T), t1 = min(t0 + per, T);
+  int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
+  for (int t = t0; t < t1; t++) {
+    const int s = vm[t], sk = s & 0xff, sv = s >> 8;
+    ndk += sk == HS_DENSE; nsk += sk == HS_SPARSE24; ndv += sv == HS_DENSE; nsv += sv == HS_SPARSE24;
+  }
+  // exclusive scan of the four counters over threads (thread 0 walks the 256 partials)
+  __shared__ int part[4][256];
+  part[0][tid] = ndk; part[1][tid] = nsk; part[2][tid] = ndv; part[3][tid] = nsv;
+  __syncthreads();
+  if (tid < 4) {
+    int acc = 0;
+    for (int i = 0; i < 256; i++) { const int v = part[tid][i]; part[tid][i] = acc; acc += v; }
+  }
+  __syncthreads();
+  ndk = part[0][tid]; nsk = part[1][tid]; ndv = part[2][tid]; nsv = part[3][tid];
+  for (int t = t0; t < t1; t++) {
+    const int s = vm[t], sk = s & 0xff, sv = s >> 8;
+    km[t] = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
+    vm[t] = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
+  }
+  (void)cnt;
+}
+
+// ----------------------------------------------------------------------------------
+// Fused prune + pack (Sec. IV-B): one workgroup per tile, K then V.
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                                                   int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv) {
+  __shared__ uint16_t vl[HS_BT * kVStride];
+  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
+  const int64_t row = (int64_t)b * Hkv + h;
+  const int mk = kv.k_map[row * T + t], mv = kv.v_map[row * T + t];
+  const uint16_t* kt = K + b * sb + h * sh + (int64_t)t * HS_BT * st;
+  const uint16_t* vt = V + b * sb + h * sh + (int64_t)t * HS_BT * st;
+  if (mv != 0) stage_v_tile(vt, st, vl);
+
+  // ---- K ----
+  if (mk > 0) {  // dense: permuted copy into operand order
+    uint8_t* dst = const_cast<uint8_t*>(kv.k_dense) + (row * kv.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+    const uint16_t* src = kt + (int64_t)(16 * w + r) * st + 8 * a;
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+      const uint4 d = *reinterpret_cast<const uint4*>(src + 32 * s);
+      *reinterpret_cast<uint4*>(dst + ((w * 4 + s) * 64 + l) * 16) = d;
+    }
+  } else if (mk < 0) {
+    const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
+    uint8_t* nnz = const_cast<uint8_t*>(kv.k_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    uint8_t* meta = const_cast<uint8_t*>(kv.k_meta) + slot * (int64_t)HS_TILE_META_BYTES;
+    const uint16_t* src = kt + (int64_t)(16 * w + r) * st + 16 * a;
+    uint32_t idx = 0;
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      const uint4 d0 = *reinterpret_cast<const uint4*>(src + 64 * kb);
+      const uint4 d1 = *reinterpret_cast<const uint4*>(src + 64 * kb + 8);
+      const uint32_t wds[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+      uint32_t out[4];
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
+        uint32_t nib;
+        top2_emit(top2_mask(x0, x1, x2, x3), x0, x1, x2, x3, out[q], nib);
+        idx |= nib << (16 * kb + 4 * q);
+      }
+      *reinterpret_cast<uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+    *reinterpret_cast<uint32_t*>(meta + (w * 64 + l) * 4) = idx;
+  }
+
+  // ---- V ----
+  if (mv == 0) return;
+  __syncthreads();
+  if (mv > 0) {
+    uint8_t* dst = const_cast<uint8_t*>(kv.v_dense) + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1;
+      const int c = 16 * mb + r;
+      uint32_t o[4];
+#pragma unroll
+      for (int p = 0; p < 4; p++) {
+        const int e0 = 2 * p, e1 = 2 * p + 1;
+        const int tok0 = 16 * (2 * hh + (e0 >> 2)) + 4 * a + (e0 & 3);
+        const int tok1 = 16 * (2 * hh + (e1 >> 2)) + 4 * a + (e1 & 3);
+        o[p] = (uint32_t)vl[tok0 * kVStride + c] | ((uint32_t)vl[tok1 * kVStride + c] << 16);
+      }
+      *reinterpret_cast<uint4*>(dst + (ch * 64 + l) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  } else {
+    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+    uint8_t* nnz = const_cast<uint8_t*>(kv.v_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    uint8_t* meta = const_cast<uint8_t*>(kv.v_meta) + slot * (int64_t)HS_TILE_META_BYTES;
+    uint32_t idx = 0;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int mb = 2 * w + j, c = 16 * mb + r;
+      uint32_t out[4];
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int g = hs_v_group(a, q);
+        const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
+        const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
+        uint32_t nib;
+        top2_emit(top2_mask(x0, x1, x2, x3), x0, x1, x2, x3, out[q], nib);
+        idx |= nib << (16 * j + 4 * q);
+      }
+      *reinterpret_cast<uint4*>(nnz + (mb * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+    *reinterpret_cast<uint32_t*>(meta + (w * 64 + l) * 4) = idx;
+  }
+}
+
+// ----------------------------------------------------------------------------------
+// Unpack (tests / debugging): packed -> dense bf16 [B, Hkv, L, D], zeros where pruned
+// or skipped.
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev kv, uint16_t* __restrict__ K_out,
+                                                     uint16_t* __restrict__ V_out) {
+  __shared__ uint16_t vl[HS_BT * kVStride];
+  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
+  const int64_t row = (int64_t)b * Hkv + h;
+  const int mk = kv.k_map[row * T + t], mv = kv.v_map[row * T + t];
+  uint16_t* ko = K_out + (row * T + t) * (int64_t)(HS_BT * HS_D);
+  uint16_t* vo = V_out + (row * T + t) * (int64_t)(HS_BT * HS_D);
+  {  // K: token 16w+r
+    uint16_t* dst = ko + (16 * w + r) * HS_D;
+    if (mk > 0) {
+      const uint8_t* src = kv.k_dense + (row * kv.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+#pragma unroll
+      for (int s = 0; s < 4; s++)
+        *reinterpret_cast<uint4*>(dst + 32 * s + 8 * a) = *reinterpret_cast<const uint4*>(src + ((w * 4 + s) * 64 + l) * 16);
+    } else if (mk < 0) {
+      const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
+      const uint8_t* nnz = kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
+      const uint32_t idx = *reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES + (w * 64 + l) * 4);
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) {
+        const uint4 d = *reinterpret_cast<const uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16);
+        const uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+        uint16_t o[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) o[i] = 0;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const uint32_t nib = (idx >> (16 * kb + 4 * q)) & 0xfu;
+          const uint32_t i0 = nib & 3u, i1 = nib >> 2;
+#pragma unroll
+          for (int p = 0; p < 4; p++) {
+            if (i0 == (uint32_t)p) o[4 * q + p] = (uint16_t)(vals[q] & 0xffffu);
+            if (i1 == (uint32_t)p) o[4 * q + p] = (uint16_t)(vals[q] >> 16);
+          }
+        }
+        uint32_t pk[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) pk[i] = (uint32_t)o[2 * i] | ((uint32_t)o[2 * i + 1] << 16);
+        uint4* d4 = reinterpret_cast<uint4*>(dst + 64 * kb + 16 * a);
+        d4[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        d4[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < 4; s++) *reinterpret_cast<uint4*>(dst + 32 * s + 8 * a) = make_uint4(0, 0, 0, 0);
+    }
+  }
+  // V: rebuild the tile in LDS in [token][channel] order, then store it coalesced
+  if (mv > 0) {
+    const uint8_t* src = kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1, c = 16 * mb + r;
+      const uint4 d = *reinterpret_cast<const uint4*>(src + (ch * 64 + l) * 16);
+      const uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const int tok = 16 * (2 * hh + (e >> 2)) + 4 * a + (e & 3);
+        vl[tok * kVStride + c] = (uint16_t)((vals[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+      }
+    }
+  } else if (mv < 0) {
+    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+    const uint8_t* nnz = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    const uint32_t idx = *reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES + (w * 64 + l) * 4);
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int mb = 2 * w + j, c = 16 * mb + r;
+      const uint4 d = *reinterpret_cast<const uint4*>(nnz + (mb * 64 + l) * 16);
+      const uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int g = hs_v_group(a, q);
+        const uint32_t nib = (idx >> (16 * j + 4 * q)) & 0xfu;
+        const uint32_t i0 = nib & 3u, i1 = nib >> 2;
+#pragma unroll
+        for (int p = 0; p < 4; p++) {
+          uint16_t v = 0;
+          if (i0 == (uint32_t)p) v = (uint16_t)(vals[q] & 0xffffu);
+          if (i1 == (uint32_t)p) v = (uint16_t)(vals[q] >> 16);
+          vl[(4 * g + p) * kVStride + c] = v;
+        }
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int q = tid + 256 * i, tok = q >> 4, c8 = q & 15;
+    uint4 d = make_uint4(0, 0, 0, 0);
+    if (mv != 0) {
+      const uint2* s2 = reinterpret_cast<const uint2*>(vl + tok * kVStride + 8 * c8);
+      const uint2 lo = s2[0], hi = s2[1];
+      d = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+    *reinterpret_cast<uint4*>(vo + tok * HS_D + 8 * c8) = d;
+  }
+}
+
+}  // namespace
+
+hipError_t hs_launch_fill_maps(int32_t* k_map, int32_t* v_map, int rows, int T, int state_k, int state_v,
+                               hipStream_t st) {
+  const int64_t n = (int64_t)rows * T;
+  hipLaunchKernelGGL(fill_maps_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, k_map, v_map, rows, T,
+                     state_k, state_v);
+  return hipGetLastError();
+}
+
+hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
+                           int T, double* scores, hipStream_t st) {
+  hipLaunchKernelGGL(score_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, scores);
+  return hipGetLastError();
+}
+
+hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
+                            int32_t* k_map, int32_t* v_map, hipStream_t st) {
+  hipLaunchKernelGGL(select_kernel, dim3(rows), dim3(256), 0, st, scores, rows, T, n_skip, n_sparse_k, n_sparse_v,
+                     k_map, v_map);
+  return hipGetLastError();
+}
+
+hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
+                          int T, hs_kv_dev kv, hipStream_t st) {
+  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv);
+  return hipGetLastError();
+}
+
+hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st) {
+  hipLaunchKernelGGL(unpack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, Hkv, T, kv, K_out, V_out);
+  return hipGetLastError();
+}

@@ -1,0 +1,272 @@
+// Decode attention: split-KV kernel + merge kernel (Sec. IV-C: each workgroup handles a
+// subset of the KV blocks and emits a partial output with its log-sum-exp; a light
+// post-processing kernel combines them; the query heads that share a KV head are folded
+// into the N dimension of the matrix instruction).
+//
+// The kernel is HBM-bound: every byte of the packed cache is read exactly once, straight
+// from global memory into matrix-core operand registers (the pools are stored in operand
+// order), so there is no LDS staging and no cross-lane shuffle in the main loop.  The
+// sparse matrix instruction is used as the decompressor: it consumes the 2-bit metadata
+// natively, so no vector-ALU work is spent on selecting operands.
+#include "hs_common.h"
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
+
+// streaming (non-temporal) 16-byte load: the packed cache is read once per call
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream(const uint4* p) {
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p)));
+}
+
+struct u4x2 { uint4 lo, hi; };
+__device__ __forceinline__ bf16x16_t as_bf16x16(uint4 lo, uint4 hi) {
+  u4x2 t{lo, hi};
+  return __builtin_bit_cast(bf16x16_t, t);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  bf2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float bf16_lo_f(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi_f(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+
+// Workspace layout: partial O (normalised) [B*Hq][n_splits][128] fp32, then partial LSE
+// [B*Hq][n_splits] fp32 (natural log; -inf for an empty split).
+template <int MODE>  // 0: every tile 2:4 or skipped; 1: every tile dense or skipped; 2: any mix
+__global__ __launch_bounds__(256, 2) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2, int n_splits,
+                                                              const uint16_t* __restrict__ Q, hs_kv_dev kv,
+                                                              float* __restrict__ ws) {
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, c = l & 15;
+  const int G = Hq / Hkv;
+  const int64_t row = (int64_t)b * Hkv + hkv;
+  const int per = (T + n_splits - 1) / n_splits;
+  const int t_begin = split * per, t_end = min(T, t_begin + per);
+
+  // Q^T as the B operand: columns 0..G-1 and 8..8+G-1 both hold head (hkv*G + column%8);
+  // the second copy carries the low-order half of P in GEMM2 (see below).
+  uint4 qb[4];  // dense k-steps s = 0..3 (channels 32s + 8a + e); sparse kb uses steps 2kb, 2kb+1
+  {
+    const int head = c & 7;
+    const bool valid = head < G;
+    const uint16_t* q = Q + ((int64_t)b * Hq + hkv * G + (valid ? head : 0)) * HS_D + 8 * a;
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+      qb[s] = valid ? *reinterpret_cast<const uint4*>(q + 32 * s) : make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  f32x4_t o[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++) o[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int t = t_begin + w; t < t_end; t += 4) {
+    const int mk = kv.k_map[row * T + t];
+    const int mv = kv.v_map[row * T + t];
+    if (mk == 0) continue;  // skipped tile (both maps are 0 there)
+
+    // ---------------- issue all loads of the tile ----------------
+    uint4 kd[16];  // sparse uses 8 (+ kmeta), dense 16
+    uint32_t kmeta[4];
+    uint4 vd[16];
+    uint32_t vmeta[4];
+    const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
+    const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+    if (k_sparse) {
+      const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
+      const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
+      const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
+#pragma unroll
+      for (int i = 0; i < 8; i++) kd[i] = ld_stream(p + 64 * i);
+#pragma unroll
+      for (int i = 0; i < 4; i++) kmeta[i] = __builtin_nontemporal_load(pm + 64 * i);
+    } else {
+      const int64_t slot = row * kv.cap_dense_k + (mk - 1);
+      const uint4* p = reinterpret_cast<const uint4*>(kv.k_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
+#pragma unroll
+      for (int i = 0; i < 16; i++) kd[i] = ld_stream(p + 64 * i);
+    }
+    if (v_sparse) {
+      const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+      const uint4* p = reinterpret_cast<const uint4*>(kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
+      const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
+#pragma unroll
+      for (int i = 0; i < 8; i++) vd[i] = ld_stream(p + 64 * i);
+#pragma unroll
+      for (int i = 0; i < 4; i++) vmeta[i] = __builtin_nontemporal_load(pm + 64 * i);
+    } else {
+      const int64_t slot = row * kv.cap_dense_v + (mv - 1);
+      const uint4* p = reinterpret_cast<const uint4*>(kv.v_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
+#pragma unroll
+      for (int i = 0; i < 16; i++) vd[i] = ld_stream(p + 64 * i);
+    }
+
+    // ---------------- GEMM1: S^T[64 tokens x 16 cols] = K_tile . Q^T ----------------
+    f32x4_t s[4];
+#pragma unroll
+    for (int m = 0; m < 4; m++) {
+      s[m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (k_sparse) {
+        s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(kd[2 * m]), as_bf16x16(qb[0], qb[1]), s[m], (int)kmeta[m], 0, 0);
+        s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(kd[2 * m + 1]), as_bf16x16(qb[2], qb[3]), s[m], (int)kmeta[m], 0, 1);
+      } else {
+#pragma unroll
+        for (int st = 0; st < 4; st++)
+          s[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kd[4 * m + st]), as_bf16x8(qb[st]), s[m], 0, 0, 0);
+      }
+    }
+
+    // ---------------- online softmax for column c (log2 domain) ----------------
+    float mx = -INFINITY;
+#pragma unroll
+    for (int m = 0; m < 4; m++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        s[m][i] *= scale_log2;
+        mx = fmaxf(mx, s[m][i]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
+    m_run = m_new;
+    float psum = 0.f;
+    // P^T as the B operand: element 8h+4u+i of lane group a <- token 16(2h+u)+4a+i.
+    // Columns < 8 carry bf16(p), columns >= 8 carry bf16(p - bf16(p)), so that the sum of
+    // the two accumulator columns sees p to ~16 bits although the operand type is bf16.
+    uint32_t pb[8];
+#pragma unroll
+    for (int m = 0; m < 4; m++) {
+      float p[4], rsd[4];
+      uint32_t hi[2];
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        p[i] = __builtin_amdgcn_exp2f(s[m][i] - m_new);
+        psum += p[i];
+      }
+      hi[0] = pack_bf16(p[0], p[1]);
+      hi[1] = pack_bf16(p[2], p[3]);
+      rsd[0] = p[0] - bf16_lo_f(hi[0]);
+      rsd[1] = p[1] - bf16_hi_f(hi[0]);
+      rsd[2] = p[2] - bf16_lo_f(hi[1]);
+      rsd[3] = p[3] - bf16_hi_f(hi[1]);
+      const uint32_t lo0 = pack_bf16(rsd[0], rsd[1]), lo1 = pack_bf16(rsd[2], rsd[3]);
+      pb[2 * m] = c < 8 ? hi[0] : lo0;
+      pb[2 * m + 1] = c < 8 ? hi[1] : lo1;
+    }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int i = 0; i < 8; i++) o[i] *= alpha;
+
+    // ---------------- GEMM2: O^T[128 ch x 16 cols] += V_tile^T . P^T ----------------
+    const uint4 pb_lo = make_uint4(pb[0], pb[1], pb[2], pb[3]);  // dense step h = 0 (tokens 0..31)
+    const uint4 pb_hi = make_uint4(pb[4], pb[5], pb[6], pb[7]);  // dense step h = 1
+#pragma unroll
+    for (int mb = 0; mb < 8; mb++) {
+      if (v_sparse) {
+        if (mb & 1)
+          o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(vd[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)vmeta[mb >> 1], 0, 1);
+        else
+          o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(vd[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)vmeta[mb >> 1], 0, 0);
+      } else {
+        o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vd[2 * mb]), as_bf16x8(pb_lo), o[mb], 0, 0, 0);
+        o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vd[2 * mb + 1]), as_bf16x8(pb_hi), o[mb], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---------------- combine: lane groups, hi/lo columns, then the 4 waves ----------------
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) o[i][j] += __shfl_xor(o[i][j], 8);  // column c + column c^8
+
+  __shared__ float sm_m[4][8], sm_l[4][8];
+  __shared__ float sm_o[4][8][HS_D];
+  if (c < 8) {
+    if (a == 0) { sm_m[w][c] = m_run; sm_l[w][c] = l_run; }
+#pragma unroll
+    for (int mb = 0; mb < 8; mb++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) sm_o[w][c][16 * mb + 4 * a + i] = o[mb][i];
+  }
+  __syncthreads();
+  // thread -> (head g = tid / 32, 4 channels)
+  const int g = tid >> 5, ch = (tid & 31) * 4;
+  if (g < G) {
+    float mstar = fmaxf(fmaxf(sm_m[0][g], sm_m[1][g]), fmaxf(sm_m[2][g], sm_m[3][g]));
+    float lsum = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (mstar > -INFINITY) {
+#pragma unroll
+      for (int ww = 0; ww < 4; ww++) {
+        const float f = __builtin_amdgcn_exp2f(sm_m[ww][g] - mstar);
+        lsum += f * sm_l[ww][g];
+#pragma unroll
+        for (int i = 0; i < 4; i++) acc[i] += f * sm_o[ww][g][ch + i];
+      }
+    }
+    const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+    const int64_t hq = (int64_t)b * Hq + hkv * G + g;
+    float* po = ws + (hq * n_splits + split) * HS_D + ch;
+    *reinterpret_cast<float4*>(po) = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    if ((tid & 31) == 0) {
+      float* pl = ws + (int64_t)gridDim.z * Hq * n_splits * HS_D;
+      pl[hq * n_splits + split] = lsum > 0.f ? (mstar + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
+    }
+  }
+}
+
+// Merge of the split partials (Sec. IV-C "lightweight post-processing kernel"):
+// M = max LSE_s, O = sum e^{LSE_s - M} O_s / sum e^{LSE_s - M}.  One workgroup of 128
+// threads (one per channel) per (b, query head).
+__global__ __launch_bounds__(128) void decode_merge_kernel(int n_rows, int n_splits, const float* __restrict__ ws,
+                                                           uint16_t* __restrict__ O, float* __restrict__ LSE) {
+  const int hq = blockIdx.x, ch = threadIdx.x;
+  const float* po = ws + (int64_t)hq * n_splits * HS_D;
+  const float* pl = ws + (int64_t)n_rows * n_splits * HS_D + (int64_t)hq * n_splits;
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; s++) M = fmaxf(M, pl[s]);
+  float den = 0.f, acc = 0.f;
+  if (M > -INFINITY) {
+    for (int s = 0; s < n_splits; s++) {
+      const float f = __expf(pl[s] - M);
+      den += f;
+      acc += f * po[(int64_t)s * HS_D + ch];
+    }
+  }
+  const float out = den > 0.f ? acc / den : 0.f;
+  O[(int64_t)hq * HS_D + ch] = (uint16_t)(pack_bf16(out, 0.f) & 0xffffu);
+  if (LSE != nullptr && ch == 0) LSE[hq] = den > 0.f ? M + __logf(den) : -INFINITY;
+}
+
+}  // namespace
+
+hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q, hs_kv_dev kv,
+                            uint16_t* O, float* LSE, float* ws, hipStream_t st) {
+  const dim3 grid(n_splits, Hkv, B), block(256);
+  const float sl2 = scale * kLog2e;
+  const bool no_dense = kv.cap_dense_k == 0 && kv.cap_dense_v == 0;
+  const bool no_sparse = kv.cap_sparse_k == 0 && kv.cap_sparse_v == 0;
+  if (no_dense)
+    hipLaunchKernelGGL(decode_split_kernel<0>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, Q, kv, ws);
+  else if (no_sparse)
+    hipLaunchKernelGGL(decode_split_kernel<1>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, Q, kv, ws);
+  else
+    hipLaunchKernelGGL(decode_split_kernel<2>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, Q, kv, ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(128), 0, st, B * Hq, n_splits, ws, O, LSE);
+  return hipGetLastError();
+}

@@ -1,0 +1,305 @@
+// Prefill attention: Algorithm 1 (Trans-Both: S^T = K Q^T, O^T = V^T P^T with K and V^T as
+// the first, possibly 2:4-sparse, operand of the matrix instruction) with the mixed
+// dense/sparse dispatch of Sec. III-C-2, online softmax, and tile skipping.
+//
+// Work decomposition: a "slab" is 64 consecutive query positions of one query head; a wave
+// owns one slab (4 column blocks of 16 queries), keeps Q^T (B operand of GEMM1), the
+// running softmax state and O^T (128 x 64 fp32) in registers for the whole kernel.  The 4
+// waves of a workgroup take 4 consecutive slabs in (position-tile, head-in-group) order, so
+// for a GQA group of 4 they are the 4 query heads of one 64-position tile and share every
+// KV tile, which is staged once per workgroup in LDS (double buffered, prefetched through
+// registers one tile ahead).  Pools are stored in operand order, so LDS reads are
+// conflict-free 16-byte-per-lane reads and GEMM1's accumulators become GEMM2's B operand
+// in place (no re-layout step).
+#include "hs_common.h"
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
+struct u4x2 { uint4 lo, hi; };
+__device__ __forceinline__ bf16x16_t as_bf16x16(uint4 lo, uint4 hi) {
+  u4x2 t{lo, hi};
+  return __builtin_bit_cast(bf16x16_t, t);
+}
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  bf2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+constexpr int kBufBytes = 32768;  // one stage: K region 16 KiB + V region 16 KiB
+
+// Registers that carry the next tile from global memory to LDS.
+struct Stage {
+  uint4 k[4];
+  uint4 v[4];
+};
+
+template <int MODE>
+__device__ __forceinline__ void stage_load(Stage& sg, const hs_kv_dev& kv, int64_t row, int mk, int mv, int tid) {
+  const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
+  const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+  if (k_sparse) {
+    const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES);
+    sg.k[0] = p[tid];
+    sg.k[1] = p[tid + 256];
+    if (tid < 64) sg.k[2] = reinterpret_cast<const uint4*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES)[tid];
+  } else {
+    const int64_t slot = row * kv.cap_dense_k + (mk - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.k_dense + slot * (int64_t)HS_TILE_DENSE_BYTES);
+#pragma unroll
+    for (int i = 0; i < 4; i++) sg.k[i] = p[tid + 256 * i];
+  }
+  if (v_sparse) {
+    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES);
+    sg.v[0] = p[tid];
+    sg.v[1] = p[tid + 256];
+    if (tid < 64) sg.v[2] = reinterpret_cast<const uint4*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES)[tid];
+  } else {
+    const int64_t slot = row * kv.cap_dense_v + (mv - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.v_dense + slot * (int64_t)HS_TILE_DENSE_BYTES);
+#pragma unroll
+    for (int i = 0; i < 4; i++) sg.v[i] = p[tid + 256 * i];
+  }
+}
+
+template <int MODE>
+__device__ __forceinline__ void stage_store(const Stage& sg, uint8_t* buf, int mk, int mv, int tid) {
+  const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
+  const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+  uint4* kd = reinterpret_cast<uint4*>(buf);
+  uint4* vd = reinterpret_cast<uint4*>(buf + 16384);
+  if (k_sparse) {
+    kd[tid] = sg.k[0];
+    kd[tid + 256] = sg.k[1];
+    if (tid < 64) kd[512 + tid] = sg.k[2];
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; i++) kd[tid + 256 * i] = sg.k[i];
+  }
+  if (v_sparse) {
+    vd[tid] = sg.v[0];
+    vd[tid + 256] = sg.v[1];
+    if (tid < 64) vd[512 + tid] = sg.v[2];
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; i++) vd[tid + 256 * i] = sg.v[i];
+  }
+}
+
+// next tile index > j (and <= jmax) whose map entry is not 0, or -1
+__device__ __forceinline__ int next_active(const int32_t* km, int j, int jmax) {
+  for (int t = j + 1; t <= jmax; t++)
+    if (km[t] != 0) return t;
+  return -1;
+}
+
+template <int MODE>  // 0: every tile 2:4 or skipped; 1: every tile dense or skipped; 2: any mix
+__global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T, int Tq, int q_off, float scale_log2,
+                                                         int causal, const uint16_t* __restrict__ Q, hs_kv_dev kv,
+                                                         uint16_t* __restrict__ O, float* __restrict__ LSE) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kBufBytes];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, c = l & 15;
+  const int G = Hq / Hkv;
+  const int hkv = blockIdx.y, b = blockIdx.z;
+  const int n_slabs = Tq * G;
+  // heavy (late) query tiles first: causal work grows with the position
+  const int grp = (int)gridDim.x - 1 - (int)blockIdx.x;
+  const int slab = 4 * grp + w;
+  const bool valid = slab < n_slabs;
+  const int qt = valid ? slab / G : 0, hg = valid ? slab % G : 0;
+  const int hq = hkv * G + hg;
+  const int64_t row = (int64_t)b * Hkv + hkv;
+  const int32_t* km = kv.k_map + row * T;
+  const int32_t* vm = kv.v_map + row * T;
+  // last KV tile each wave / the workgroup may look at
+  const int jdiag = qt + q_off;
+  const int jmax_w = causal ? jdiag : T - 1;
+  const int last_slab = min(4 * grp + 3, n_slabs - 1);
+  const int jmax_wg = causal ? min(T - 1, last_slab / G + q_off) : T - 1;
+
+  // Q^T (B operand): column block nb, dense k-step s: query 64qt+16nb+c, channels 32s+8a+e
+  uint4 qb[4][4];
+  {
+    const uint16_t* qp = Q + (((int64_t)b * Hq + hq) * Tq * HS_BT + (int64_t)qt * HS_BT + c) * HS_D + 8 * a;
+#pragma unroll
+    for (int nb = 0; nb < 4; nb++)
+#pragma unroll
+      for (int s = 0; s < 4; s++)
+        qb[nb][s] = valid ? *reinterpret_cast<const uint4*>(qp + (int64_t)(16 * nb) * HS_D + 32 * s) : make_uint4(0, 0, 0, 0);
+  }
+
+  f32x4_t o[8][4];
+#pragma unroll
+  for (int mb = 0; mb < 8; mb++)
+#pragma unroll
+    for (int nb = 0; nb < 4; nb++) o[mb][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run[4], l_run[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; nb++) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
+
+  Stage sg;
+  int j = next_active(km, -1, jmax_wg);
+  int mk = 0, mv = 0;
+  if (j >= 0) {
+    mk = km[j]; mv = vm[j];
+    stage_load<MODE>(sg, kv, row, mk, mv, tid);
+    stage_store<MODE>(sg, lds, mk, mv, tid);
+  }
+  __syncthreads();
+  int buf = 0;
+  while (j >= 0) {
+    const int jn = next_active(km, j, jmax_wg);
+    int mkn = 0, mvn = 0;
+    if (jn >= 0) {
+      mkn = km[jn]; mvn = vm[jn];
+      stage_load<MODE>(sg, kv, row, mkn, mvn, tid);
+    }
+    if (valid && j <= jmax_w) {
+      const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
+      const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+      const uint4* kl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes);
+      const uint4* vl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes + 16384);
+      // ---------------- GEMM1: S^T[64 tokens x 64 queries] ----------------
+      f32x4_t s[4][4];
+#pragma unroll
+      for (int m = 0; m < 4; m++) {
+#pragma unroll
+        for (int nb = 0; nb < 4; nb++) s[m][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (k_sparse) {
+          const int idx = (int)reinterpret_cast<const uint32_t*>(kl + 512)[m * 64 + l];
+          const bf16x8_t a0 = as_bf16x8(kl[(2 * m) * 64 + l]);
+          const bf16x8_t a1 = as_bf16x8(kl[(2 * m + 1) * 64 + l]);
+#pragma unroll
+          for (int nb = 0; nb < 4; nb++)
+            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, as_bf16x16(qb[nb][0], qb[nb][1]), s[m][nb], idx, 0, 0);
+#pragma unroll
+          for (int nb = 0; nb < 4; nb++)
+            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, as_bf16x16(qb[nb][2], qb[nb][3]), s[m][nb], idx, 0, 1);
+        } else {
+#pragma unroll
+          for (int st = 0; st < 4; st++) {
+            const bf16x8_t av = as_bf16x8(kl[(4 * m + st) * 64 + l]);
+#pragma unroll
+            for (int nb = 0; nb < 4; nb++)
+              s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(qb[nb][st]), s[m][nb], 0, 0, 0);
+          }
+        }
+      }
+      // ---------------- online softmax per query column (log2 domain) ----------------
+      const bool diag = causal && j == jdiag;
+      uint32_t pb[4][8];
+#pragma unroll
+      for (int nb = 0; nb < 4; nb++) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int m = 0; m < 4; m++)
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            float x = s[m][nb][i] * scale_log2;
+            if (diag && (16 * m + 4 * a + i) > (16 * nb + c)) x = -INFINITY;
+            s[m][nb][i] = x;
+            mx = fmaxf(mx, x);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[nb], mx);  // finite: every processed tile shows >= 1 token to each query
+        const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+        m_run[nb] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int m = 0; m < 4; m++) {
+          float p[4];
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            p[i] = __builtin_amdgcn_exp2f(s[m][nb][i] - m_new);
+            psum += p[i];
+          }
+          pb[nb][2 * m] = pack_bf16(p[0], p[1]);
+          pb[nb][2 * m + 1] = pack_bf16(p[2], p[3]);
+        }
+        l_run[nb] = l_run[nb] * alpha + psum;
+#pragma unroll
+        for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
+      }
+      // ---------------- GEMM2: O^T[128 ch x 64 queries] += V^T . P^T ----------------
+#pragma unroll
+      for (int mb = 0; mb < 8; mb++) {
+        if (v_sparse) {
+          const int idx = (int)reinterpret_cast<const uint32_t*>(vl + 512)[(mb >> 1) * 64 + l];
+          const bf16x8_t av = as_bf16x8(vl[mb * 64 + l]);
+#pragma unroll
+          for (int nb = 0; nb < 4; nb++) {
+            const bf16x16_t bp = as_bf16x16(make_uint4(pb[nb][0], pb[nb][1], pb[nb][2], pb[nb][3]),
+                                            make_uint4(pb[nb][4], pb[nb][5], pb[nb][6], pb[nb][7]));
+            if (mb & 1)
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bp, o[mb][nb], idx, 0, 1);
+            else
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bp, o[mb][nb], idx, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int h = 0; h < 2; h++) {
+            const bf16x8_t av = as_bf16x8(vl[(2 * mb + h) * 64 + l]);
+#pragma unroll
+            for (int nb = 0; nb < 4; nb++) {
+              const bf16x8_t bp = as_bf16x8(make_uint4(pb[nb][4 * h], pb[nb][4 * h + 1], pb[nb][4 * h + 2], pb[nb][4 * h + 3]));
+              o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bp, o[mb][nb], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    if (jn >= 0) stage_store<MODE>(sg, lds + (buf ^ 1) * kBufBytes, mkn, mvn, tid);
+    __syncthreads();
+    j = jn; mk = mkn; mv = mvn;
+    buf ^= 1;
+  }
+
+  // ---------------- epilogue: O = O^T / l, LSE ----------------
+  if (!valid) return;
+#pragma unroll
+  for (int nb = 0; nb < 4; nb++) {
+    float lt = l_run[nb];
+    lt += __shfl_xor(lt, 16);
+    lt += __shfl_xor(lt, 32);
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const int64_t qrow = ((int64_t)b * Hq + hq) * Tq * HS_BT + (int64_t)qt * HS_BT + 16 * nb + c;
+    uint16_t* op = O + qrow * HS_D + 4 * a;
+#pragma unroll
+    for (int mb = 0; mb < 8; mb++) {
+      const uint2 v = make_uint2(pack_bf16(o[mb][nb][0] * inv, o[mb][nb][1] * inv),
+                                 pack_bf16(o[mb][nb][2] * inv, o[mb][nb][3] * inv));
+      *reinterpret_cast<uint2*>(op + 16 * mb) = v;
+    }
+    if (LSE != nullptr && a == 0)
+      LSE[qrow] = lt > 0.f ? (m_run[nb] + __builtin_amdgcn_logf(lt)) * kLn2 : -INFINITY;
+  }
+}
+
+}  // namespace
+
+hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
+                             hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st) {
+  const int G = Hq / Hkv;
+  const int n_groups = (Tq * G + 3) / 4;
+  const dim3 grid(n_groups, Hkv, B), block(256);
+  const float sl2 = scale * kLog2e;
+  const int q_off = T - Tq;
+  const bool no_dense = kv.cap_dense_k == 0 && kv.cap_dense_v == 0;
+  const bool no_sparse = kv.cap_sparse_k == 0 && kv.cap_sparse_v == 0;
+  if (no_dense)
+    hipLaunchKernelGGL(prefill_kernel<0>, grid, block, 0, st, Hq, Hkv, T, Tq, q_off, sl2, causal, Q, kv, O, LSE);
+  else if (no_sparse)
+    hipLaunchKernelGGL(prefill_kernel<1>, grid, block, 0, st, Hq, Hkv, T, Tq, q_off, sl2, causal, Q, kv, O, LSE);
+  else
+    hipLaunchKernelGGL(prefill_kernel<2>, grid, block, 0, st, Hq, Hkv, T, Tq, q_off, sl2, causal, Q, kv, O, LSE);
+  return hipGetLastError();
+}

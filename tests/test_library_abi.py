@@ -1,0 +1,73 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and its host-only size arithmetic reproduces the byte accounting of
+Sec. III-D.  No compute call is made."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_16864_amd import binding as hb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(hb._LIB_PATH):
+        from paper_2604_16864_amd.build import build_lib
+        build_lib(verbose=False)
+    return hb.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    hdr = open(os.path.join(ROOT, "include", "hs.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(hs_[a-z_0-9]+)\s*\(", hdr))
+    assert {"hs_compress_kv", "hs_prefill_attn", "hs_decode_attn", "hs_unpack_kv"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(hb.EXPORTS)
+
+
+def test_size_arithmetic_matches_paper(L):
+    sh = hb.make_shape(1, 32, 8, 32768)
+    T = 32768 // 64
+    c = hb.tile_counts(sh, hb.make_policy())
+    assert c == [0, 0, T, 0, T]
+    nb = hb.kv_bytes(sh, c)
+    dense_total = 2 * 8 * 32768 * 128 * 2
+    pools = nb[0] + nb[1] + nb[2] + nb[4] + nb[5] + nb[6]
+    assert nb[1] + nb[2] == 8 * T * 9216
+    assert round(dense_total / pools, 2) == 1.78                 # Sec. III-D: S_K = S_V = 1
+    c = hb.tile_counts(sh, hb.make_policy(sparse_frac_k=0.5))
+    nb = hb.kv_bytes(sh, c)
+    pools = nb[0] + nb[1] + nb[2] + nb[4] + nb[5] + nb[6]
+    assert round(dense_total / pools, 2) == 1.49                 # Sec. III-D: S_K = 0.5, S_V = 1
+    c = hb.tile_counts(sh, hb.make_policy(skip_frac=0.75))
+    assert c == [384, 0, 128, 0, 128]
+    c = hb.tile_counts(sh, hb.make_policy(skip_frac=0.25, sparse_frac_k=0.0, sparse_frac_v=0.5))
+    assert c == [128, 384, 0, 192, 192]
+
+
+def test_argument_errors(L):
+    bad = hb.make_shape(1, 32, 8, 32768, D=64)
+    c = (C.c_int32 * 5)()
+    pol = hb.make_policy()
+    assert L.hs_tile_counts(C.byref(bad), C.byref(pol), c) == -2
+    odd = hb.make_shape(1, 32, 8, 1000)
+    assert L.hs_tile_counts(C.byref(odd), C.byref(pol), c) == -2
+    big_g = hb.make_shape(1, 32, 2, 1024)
+    assert L.hs_tile_counts(C.byref(big_g), C.byref(pol), c) == -2
+    ok = hb.make_shape(1, 4, 1, 1024)
+    assert L.hs_tile_counts(C.byref(ok), C.byref(hb.make_policy(skip_frac=1.0)), c) == -1
+    assert L.hs_tile_counts(C.byref(ok), C.byref(hb.make_policy(sparse_frac_k=1.5)), c) == -1
+    assert L.hs_tile_counts(C.byref(ok), None, c) == -1
+    # null buffers are rejected before anything is launched
+    kv = hb.HsKV()
+    assert L.hs_decode_attn(C.byref(ok), 0.0, 0, None, C.byref(kv), None, None, None, None) == -1
+    assert L.hs_prefill_attn(C.byref(ok), 64, 0.0, 1, None, C.byref(kv), None, None, None, None) == -1
+    assert L.hs_compress_kv(C.byref(ok), C.byref(pol), None, None, None, C.byref(kv), None, None) == -1
+    assert L.hs_strerror(-2).decode().startswith("unsupported")
+    assert hb.workspace_bytes(ok, 2, 4) == 1 * 4 * 4 * 129 * 4
+    assert hb.decode_auto_splits(ok) == 4
