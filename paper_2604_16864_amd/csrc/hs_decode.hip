@@ -41,28 +41,153 @@ __device__ __forceinline__ float bf16_hi_f(uint32_t p) { return __uint_as_float(
 
 // Workspace layout: partial O (normalised) [B*Hq][n_splits][128] fp32, then partial LSE
 // [B*Hq][n_splits] fp32 (natural log; -inf for an empty split).
+
+// Operand registers of one tile (K and V), filled by tile_load and consumed by tile_compute.
+template <int MODE>
+struct TileRegs {
+  static constexpr int kN = MODE == 0 ? 8 : 16;  // 16-byte chunks per lane: 2:4 tile 8, dense tile 16
+  uint4 k[kN];
+  uint4 v[kN];
+  uint32_t km[4];
+  uint32_t vm[4];
+  int mk, mv;
+};
+
+template <int MODE>
+__device__ __forceinline__ void tile_load(TileRegs<MODE>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {
+  r.mk = mk;
+  r.mv = mv;
+  const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
+  const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+  if (k_sparse) {
+    const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
+    const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
+#pragma unroll
+    for (int i = 0; i < 8; i++) r.k[i] = ld_stream(p + 64 * i);
+#pragma unroll
+    for (int i = 0; i < 4; i++) r.km[i] = __builtin_nontemporal_load(pm + 64 * i);
+  } else {
+    const int64_t slot = row * kv.cap_dense_k + (mk - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.k_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
+#pragma unroll
+    for (int i = 0; i < 16; i++) r.k[i % TileRegs<MODE>::kN] = ld_stream(p + 64 * i);
+  }
+  if (v_sparse) {
+    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
+    const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
+#pragma unroll
+    for (int i = 0; i < 8; i++) r.v[i] = ld_stream(p + 64 * i);
+#pragma unroll
+    for (int i = 0; i < 4; i++) r.vm[i] = __builtin_nontemporal_load(pm + 64 * i);
+  } else {
+    const int64_t slot = row * kv.cap_dense_v + (mv - 1);
+    const uint4* p = reinterpret_cast<const uint4*>(kv.v_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
+#pragma unroll
+    for (int i = 0; i < 16; i++) r.v[i % TileRegs<MODE>::kN] = ld_stream(p + 64 * i);
+  }
+}
+
+// One tile: GEMM1 (S^T = K Q^T), online softmax, GEMM2 (O^T += V^T P^T).
+template <int MODE>
+__device__ __forceinline__ void tile_compute(const TileRegs<MODE>& r, const uint4 (&qb)[4], float scale_log2, int c,
+                                             f32x4_t (&o)[8], float& m_run, float& l_run) {
+  const bool k_sparse = MODE == 0 || (MODE == 2 && r.mk < 0);
+  const bool v_sparse = MODE == 0 || (MODE == 2 && r.mv < 0);
+  constexpr int kN = TileRegs<MODE>::kN;
+  f32x4_t s[4];
+#pragma unroll
+  for (int m = 0; m < 4; m++) {
+    s[m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (k_sparse) {
+      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m]), as_bf16x16(qb[0], qb[1]), s[m], (int)r.km[m], 0, 0);
+      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m + 1]), as_bf16x16(qb[2], qb[3]), s[m], (int)r.km[m], 0, 1);
+    } else {
+#pragma unroll
+      for (int st = 0; st < 4; st++)
+        s[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[(4 * m + st) % kN]), as_bf16x8(qb[st]), s[m], 0, 0, 0);
+    }
+  }
+  // online softmax for column c (log2 domain)
+  float mx = -INFINITY;
+#pragma unroll
+  for (int m = 0; m < 4; m++)
+#pragma unroll
+    for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][i]);
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m_run, mx * scale_log2);
+  const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
+  m_run = m_new;
+  float psum = 0.f;
+  // P^T as the B operand: element 8h+4u+i of lane group a <- token 16(2h+u)+4a+i.
+  // Columns < 8 carry bf16(p), columns >= 8 carry bf16(p - bf16(p)), so that the sum of
+  // the two accumulator columns sees p to ~16 bits although the operand type is bf16.
+  uint32_t pb[8];
+#pragma unroll
+  for (int m = 0; m < 4; m++) {
+    float p[4], rsd[4];
+    uint32_t hi[2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][i], scale_log2, -m_new));
+      psum += p[i];
+    }
+    hi[0] = pack_bf16(p[0], p[1]);
+    hi[1] = pack_bf16(p[2], p[3]);
+    rsd[0] = p[0] - bf16_lo_f(hi[0]);
+    rsd[1] = p[1] - bf16_hi_f(hi[0]);
+    rsd[2] = p[2] - bf16_lo_f(hi[1]);
+    rsd[3] = p[3] - bf16_hi_f(hi[1]);
+    const uint32_t lo0 = pack_bf16(rsd[0], rsd[1]), lo1 = pack_bf16(rsd[2], rsd[3]);
+    pb[2 * m] = c < 8 ? hi[0] : lo0;
+    pb[2 * m + 1] = c < 8 ? hi[1] : lo1;
+  }
+  l_run = l_run * alpha + psum;
+#pragma unroll
+  for (int i = 0; i < 8; i++) o[i] *= alpha;
+  const uint4 pb_lo = make_uint4(pb[0], pb[1], pb[2], pb[3]);  // dense step h = 0
+  const uint4 pb_hi = make_uint4(pb[4], pb[5], pb[6], pb[7]);  // dense step h = 1
+#pragma unroll
+  for (int mb = 0; mb < 8; mb++) {
+    if (v_sparse) {
+      if (mb & 1)
+        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)r.vm[mb >> 1], 0, 1);
+      else
+        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)r.vm[mb >> 1], 0, 0);
+    } else {
+      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb) % kN]), as_bf16x8(pb_lo), o[mb], 0, 0, 0);
+      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb + 1) % kN]), as_bf16x8(pb_hi), o[mb], 0, 0, 0);
+    }
+  }
+}
+
+// Split-KV kernel.  grid = (n_splits, Hkv, B); workgroup = 4 waves; split s owns tiles
+// [s*per, (s+1)*per); wave w takes every 4th tile of them.  Each wave preloads the map
+// entries of its tiles with one vector load, drops the skipped ones, and streams the rest
+// with a two-deep register pipeline (the loads of tile i+1 are in flight while tile i is
+// being multiplied).
 template <int MODE>  // 0: every tile 2:4 or skipped; 1: every tile dense or skipped; 2: any mix
-__global__ __launch_bounds__(256, 2) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2, int n_splits,
-                                                              const uint16_t* __restrict__ Q, hs_kv_dev kv,
-                                                              float* __restrict__ ws) {
+__global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2,
+                                                                             int n_splits, int per,
+                                                                             const uint16_t* __restrict__ Q,
+                                                                             hs_kv_dev kv, float* __restrict__ ws) {
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, c = l & 15;
   const int G = Hq / Hkv;
   const int64_t row = (int64_t)b * Hkv + hkv;
-  const int per = (T + n_splits - 1) / n_splits;
   const int t_begin = split * per, t_end = min(T, t_begin + per);
 
   // Q^T as the B operand: columns 0..G-1 and 8..8+G-1 both hold head (hkv*G + column%8);
-  // the second copy carries the low-order half of P in GEMM2 (see below).
+  // the second copy carries the low-order half of P in GEMM2.
   uint4 qb[4];  // dense k-steps s = 0..3 (channels 32s + 8a + e); sparse kb uses steps 2kb, 2kb+1
   {
     const int head = c & 7;
     const bool valid = head < G;
     const uint16_t* q = Q + ((int64_t)b * Hq + hkv * G + (valid ? head : 0)) * HS_D + 8 * a;
 #pragma unroll
-    for (int s = 0; s < 4; s++) {
-      qb[s] = valid ? *reinterpret_cast<const uint4*>(q + 32 * s) : make_uint4(0, 0, 0, 0);
-    }
+    for (int s = 0; s < 4; s++) qb[s] = valid ? *reinterpret_cast<const uint4*>(q + 32 * s) : make_uint4(0, 0, 0, 0);
   }
 
   f32x4_t o[8];
@@ -70,118 +195,36 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(int Hq, int Hkv, i
   for (int i = 0; i < 8; i++) o[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
 
-  for (int t = t_begin + w; t < t_end; t += 4) {
-    const int mk = kv.k_map[row * T + t];
-    const int mv = kv.v_map[row * T + t];
-    if (mk == 0) continue;  // skipped tile (both maps are 0 there)
-
-    // ---------------- issue all loads of the tile ----------------
-    uint4 kd[16];  // sparse uses 8 (+ kmeta), dense 16
-    uint32_t kmeta[4];
-    uint4 vd[16];
-    uint32_t vmeta[4];
-    const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
-    const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
-    if (k_sparse) {
-      const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
-      const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
-      const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
-#pragma unroll
-      for (int i = 0; i < 8; i++) kd[i] = ld_stream(p + 64 * i);
-#pragma unroll
-      for (int i = 0; i < 4; i++) kmeta[i] = __builtin_nontemporal_load(pm + 64 * i);
-    } else {
-      const int64_t slot = row * kv.cap_dense_k + (mk - 1);
-      const uint4* p = reinterpret_cast<const uint4*>(kv.k_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
-#pragma unroll
-      for (int i = 0; i < 16; i++) kd[i] = ld_stream(p + 64 * i);
+  TileRegs<MODE> ra, rb;
+  for (int base = t_begin + w; base < t_end; base += 256) {  // up to 64 tiles of this wave per round
+    const int t_mine = base + 4 * l;
+    int mk_v = 0, mv_v = 0;
+    if (t_mine < t_end) {
+      mk_v = kv.k_map[row * T + t_mine];
+      mv_v = kv.v_map[row * T + t_mine];
     }
-    if (v_sparse) {
-      const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
-      const uint4* p = reinterpret_cast<const uint4*>(kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
-      const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
-#pragma unroll
-      for (int i = 0; i < 8; i++) vd[i] = ld_stream(p + 64 * i);
-#pragma unroll
-      for (int i = 0; i < 4; i++) vmeta[i] = __builtin_nontemporal_load(pm + 64 * i);
-    } else {
-      const int64_t slot = row * kv.cap_dense_v + (mv - 1);
-      const uint4* p = reinterpret_cast<const uint4*>(kv.v_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
-#pragma unroll
-      for (int i = 0; i < 16; i++) vd[i] = ld_stream(p + 64 * i);
-    }
-
-    // ---------------- GEMM1: S^T[64 tokens x 16 cols] = K_tile . Q^T ----------------
-    f32x4_t s[4];
-#pragma unroll
-    for (int m = 0; m < 4; m++) {
-      s[m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      if (k_sparse) {
-        s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(kd[2 * m]), as_bf16x16(qb[0], qb[1]), s[m], (int)kmeta[m], 0, 0);
-        s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(kd[2 * m + 1]), as_bf16x16(qb[2], qb[3]), s[m], (int)kmeta[m], 0, 1);
-      } else {
-#pragma unroll
-        for (int st = 0; st < 4; st++)
-          s[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kd[4 * m + st]), as_bf16x8(qb[st]), s[m], 0, 0, 0);
+    unsigned long long act = __ballot(mk_v != 0);
+    if (act == 0ull) continue;
+    int i0 = __builtin_ctzll(act);
+    act &= act - 1;
+    tile_load<MODE>(ra, kv, row, __shfl(mk_v, i0), __shfl(mv_v, i0), l);
+    while (true) {
+      const bool more_b = act != 0ull;
+      if (more_b) {
+        const int i1 = __builtin_ctzll(act);
+        act &= act - 1;
+        tile_load<MODE>(rb, kv, row, __shfl(mk_v, i1), __shfl(mv_v, i1), l);
       }
-    }
-
-    // ---------------- online softmax for column c (log2 domain) ----------------
-    float mx = -INFINITY;
-#pragma unroll
-    for (int m = 0; m < 4; m++)
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        s[m][i] *= scale_log2;
-        mx = fmaxf(mx, s[m][i]);
+      tile_compute<MODE>(ra, qb, scale_log2, c, o, m_run, l_run);
+      if (!more_b) break;
+      const bool more_a = act != 0ull;
+      if (more_a) {
+        const int i2 = __builtin_ctzll(act);
+        act &= act - 1;
+        tile_load<MODE>(ra, kv, row, __shfl(mk_v, i2), __shfl(mv_v, i2), l);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
-    m_run = m_new;
-    float psum = 0.f;
-    // P^T as the B operand: element 8h+4u+i of lane group a <- token 16(2h+u)+4a+i.
-    // Columns < 8 carry bf16(p), columns >= 8 carry bf16(p - bf16(p)), so that the sum of
-    // the two accumulator columns sees p to ~16 bits although the operand type is bf16.
-    uint32_t pb[8];
-#pragma unroll
-    for (int m = 0; m < 4; m++) {
-      float p[4], rsd[4];
-      uint32_t hi[2];
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        p[i] = __builtin_amdgcn_exp2f(s[m][i] - m_new);
-        psum += p[i];
-      }
-      hi[0] = pack_bf16(p[0], p[1]);
-      hi[1] = pack_bf16(p[2], p[3]);
-      rsd[0] = p[0] - bf16_lo_f(hi[0]);
-      rsd[1] = p[1] - bf16_hi_f(hi[0]);
-      rsd[2] = p[2] - bf16_lo_f(hi[1]);
-      rsd[3] = p[3] - bf16_hi_f(hi[1]);
-      const uint32_t lo0 = pack_bf16(rsd[0], rsd[1]), lo1 = pack_bf16(rsd[2], rsd[3]);
-      pb[2 * m] = c < 8 ? hi[0] : lo0;
-      pb[2 * m + 1] = c < 8 ? hi[1] : lo1;
-    }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int i = 0; i < 8; i++) o[i] *= alpha;
-
-    // ---------------- GEMM2: O^T[128 ch x 16 cols] += V_tile^T . P^T ----------------
-    const uint4 pb_lo = make_uint4(pb[0], pb[1], pb[2], pb[3]);  // dense step h = 0 (tokens 0..31)
-    const uint4 pb_hi = make_uint4(pb[4], pb[5], pb[6], pb[7]);  // dense step h = 1
-#pragma unroll
-    for (int mb = 0; mb < 8; mb++) {
-      if (v_sparse) {
-        if (mb & 1)
-          o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(vd[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)vmeta[mb >> 1], 0, 1);
-        else
-          o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(vd[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)vmeta[mb >> 1], 0, 0);
-      } else {
-        o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vd[2 * mb]), as_bf16x8(pb_lo), o[mb], 0, 0, 0);
-        o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vd[2 * mb + 1]), as_bf16x8(pb_hi), o[mb], 0, 0, 0);
-      }
+      tile_compute<MODE>(rb, qb, scale_log2, c, o, m_run, l_run);
+      if (!more_a) break;
     }
   }
 
@@ -229,26 +272,43 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(int Hq, int Hkv, i
 }
 
 // Merge of the split partials (Sec. IV-C "lightweight post-processing kernel"):
-// M = max LSE_s, O = sum e^{LSE_s - M} O_s / sum e^{LSE_s - M}.  One workgroup of 128
-// threads (one per channel) per (b, query head).
-__global__ __launch_bounds__(128) void decode_merge_kernel(int n_rows, int n_splits, const float* __restrict__ ws,
+// M = max LSE_s, O = sum e^{LSE_s - M} O_s / sum e^{LSE_s - M}.  One workgroup of 256
+// threads per (b, query head): thread = (split lane tid/32 of 8, 4 channels).
+__global__ __launch_bounds__(256) void decode_merge_kernel(int n_rows, int n_splits, const float* __restrict__ ws,
                                                            uint16_t* __restrict__ O, float* __restrict__ LSE) {
-  const int hq = blockIdx.x, ch = threadIdx.x;
+  __shared__ float red[8];
+  __shared__ float sacc[8][HS_D + 1];
+  const int hq = blockIdx.x, tid = threadIdx.x, sl = tid >> 5, ch = (tid & 31) * 4;
   const float* po = ws + (int64_t)hq * n_splits * HS_D;
   const float* pl = ws + (int64_t)n_rows * n_splits * HS_D + (int64_t)hq * n_splits;
   float M = -INFINITY;
-  for (int s = 0; s < n_splits; s++) M = fmaxf(M, pl[s]);
-  float den = 0.f, acc = 0.f;
+  for (int s = tid; s < n_splits; s += 256) M = fmaxf(M, pl[s]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  if ((tid & 63) == 0) red[tid >> 6] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float den = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (M > -INFINITY) {
-    for (int s = 0; s < n_splits; s++) {
+    for (int s = sl; s < n_splits; s += 8) {
       const float f = __expf(pl[s] - M);
+      const float4 v = *reinterpret_cast<const float4*>(po + (int64_t)s * HS_D + ch);
       den += f;
-      acc += f * po[(int64_t)s * HS_D + ch];
+      acc[0] += f * v.x; acc[1] += f * v.y; acc[2] += f * v.z; acc[3] += f * v.w;
     }
   }
-  const float out = den > 0.f ? acc / den : 0.f;
-  O[(int64_t)hq * HS_D + ch] = (uint16_t)(pack_bf16(out, 0.f) & 0xffffu);
-  if (LSE != nullptr && ch == 0) LSE[hq] = den > 0.f ? M + __logf(den) : -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; i++) sacc[sl][ch + i] = acc[i];
+  if ((tid & 31) == 0) sacc[sl][HS_D] = den;
+  __syncthreads();
+  if (tid < HS_D) {
+    float num = 0.f, d = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; k++) { num += sacc[k][tid]; d += sacc[k][HS_D]; }
+    const float out = d > 0.f ? num / d : 0.f;
+    O[(int64_t)hq * HS_D + tid] = (uint16_t)(pack_bf16(out, 0.f) & 0xffffu);
+    if (LSE != nullptr && tid == 0) LSE[hq] = d > 0.f ? M + __logf(d) : -INFINITY;
+  }
 }
 
 }  // namespace
@@ -257,16 +317,17 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_sp
                             uint16_t* O, float* LSE, float* ws, hipStream_t st) {
   const dim3 grid(n_splits, Hkv, B), block(256);
   const float sl2 = scale * kLog2e;
+  const int per = (T + n_splits - 1) / n_splits;
   const bool no_dense = kv.cap_dense_k == 0 && kv.cap_dense_v == 0;
   const bool no_sparse = kv.cap_sparse_k == 0 && kv.cap_sparse_v == 0;
   if (no_dense)
-    hipLaunchKernelGGL(decode_split_kernel<0>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, Q, kv, ws);
+    hipLaunchKernelGGL(decode_split_kernel<0>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, ws);
   else if (no_sparse)
-    hipLaunchKernelGGL(decode_split_kernel<1>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, Q, kv, ws);
+    hipLaunchKernelGGL(decode_split_kernel<1>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, ws);
   else
-    hipLaunchKernelGGL(decode_split_kernel<2>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, Q, kv, ws);
+    hipLaunchKernelGGL(decode_split_kernel<2>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(128), 0, st, B * Hq, n_splits, ws, O, LSE);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, B * Hq, n_splits, ws, O, LSE);
   return hipGetLastError();
 }

@@ -170,89 +170,133 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T,
       // ---------------- GEMM1: S^T[64 tokens x 64 queries] ----------------
       f32x4_t s[4][4];
 #pragma unroll
-      for (int m = 0; m < 4; m++) {
+      for (int m = 0; m < 4; m++)
 #pragma unroll
         for (int nb = 0; nb < 4; nb++) s[m][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        if (k_sparse) {
-          const int idx = (int)reinterpret_cast<const uint32_t*>(kl + 512)[m * 64 + l];
-          const bf16x8_t a0 = as_bf16x8(kl[(2 * m) * 64 + l]);
-          const bf16x8_t a1 = as_bf16x8(kl[(2 * m + 1) * 64 + l]);
+      if (k_sparse) {
+        uint4 ak[8];
+        int kidx[4];
 #pragma unroll
-          for (int nb = 0; nb < 4; nb++)
-            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, as_bf16x16(qb[nb][0], qb[nb][1]), s[m][nb], idx, 0, 0);
+        for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];
 #pragma unroll
-          for (int nb = 0; nb < 4; nb++)
-            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, as_bf16x16(qb[nb][2], qb[nb][3]), s[m][nb], idx, 0, 1);
-        } else {
+        for (int m = 0; m < 4; m++) kidx[m] = (int)reinterpret_cast<const uint32_t*>(kl + 512)[m * 64 + l];
 #pragma unroll
-          for (int st = 0; st < 4; st++) {
-            const bf16x8_t av = as_bf16x8(kl[(4 * m + st) * 64 + l]);
+        for (int nb = 0; nb < 4; nb++)
 #pragma unroll
-            for (int nb = 0; nb < 4; nb++)
-              s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(qb[nb][st]), s[m][nb], 0, 0, 0);
+          for (int m = 0; m < 4; m++) {
+            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ak[2 * m]), as_bf16x16(qb[nb][0], qb[nb][1]), s[m][nb], kidx[m], 0, 0);
+            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ak[2 * m + 1]), as_bf16x16(qb[nb][2], qb[nb][3]), s[m][nb], kidx[m], 0, 1);
           }
+      } else {
+#pragma unroll
+        for (int m = 0; m < 4; m++) {
+          uint4 ak[4];
+#pragma unroll
+          for (int st = 0; st < 4; st++) ak[st] = kl[(4 * m + st) * 64 + l];
+#pragma unroll
+          for (int nb = 0; nb < 4; nb++)
+#pragma unroll
+            for (int st = 0; st < 4; st++)
+              s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[st]), as_bf16x8(qb[nb][st]), s[m][nb], 0, 0, 0);
         }
       }
-      // ---------------- online softmax per query column (log2 domain) ----------------
-      const bool diag = causal && j == jdiag;
-      uint32_t pb[4][8];
+      // causal mask inside the diagonal tile: token 16m+4a+i is hidden from query 16nb+c if larger
+      if (causal && j == jdiag) {
+#pragma unroll
+        for (int nb = 0; nb < 4; nb++)
+#pragma unroll
+          for (int m = 0; m < 4; m++)
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+              if ((16 * m + 4 * a + i) > (16 * nb + c)) s[m][nb][i] = -INFINITY;
+      }
+      // ---------------- running max, updated lazily ----------------
+      // The reference point m_run of a column only moves when the tile's maximum exceeds it
+      // by more than 2^8; until then P is computed against the stale reference (values up
+      // to 256, harmless in fp32/bf16) and neither O nor l needs rescaling.  The final
+      // O / l and LSE = m_run + log2(l) do not depend on which reference was used.
+      float mxl[4];
+      bool need = false;
 #pragma unroll
       for (int nb = 0; nb < 4; nb++) {
-        float mx = -INFINITY;
+        float mx = s[0][nb][0];
 #pragma unroll
         for (int m = 0; m < 4; m++)
 #pragma unroll
-          for (int i = 0; i < 4; i++) {
-            float x = s[m][nb][i] * scale_log2;
-            if (diag && (16 * m + 4 * a + i) > (16 * nb + c)) x = -INFINITY;
-            s[m][nb][i] = x;
-            mx = fmaxf(mx, x);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[nb], mx);  // finite: every processed tile shows >= 1 token to each query
-        const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-        m_run[nb] = m_new;
+          for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][nb][i]);
+        mxl[nb] = mx * scale_log2;
+        need = need || (mxl[nb] > m_run[nb] + 8.0f);
+      }
+      if (__any(need)) {
+#pragma unroll
+        for (int nb = 0; nb < 4; nb++) {
+          float mx = mxl[nb];
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run[nb], mx);  // finite: a processed tile shows >= 1 token to every query
+          const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+          m_run[nb] = m_new;
+          l_run[nb] *= alpha;
+#pragma unroll
+          for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
+        }
+      }
+      // ---------------- V operands (A of GEMM2) ----------------
+      uint4 av[16];
+      int vidx[4];
+      if (v_sparse) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
+#pragma unroll
+        for (int i = 0; i < 4; i++) vidx[i] = (int)reinterpret_cast<const uint32_t*>(vl + 512)[i * 64 + l];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; i++) av[i] = vl[i * 64 + l];
+      }
+      // ---------------- per column block: P = exp2(S*scale - m), then O^T += V^T P^T ----------------
+      // P goes through the matrix unit as bf16(p) + bf16(p - bf16(p)): two instructions per
+      // block, so the product sees p to ~16 bits (a single bf16 P alone costs ~1.3e-3 mean
+      // relative error on the output, on top of the bf16 rounding of O itself).
+#pragma unroll
+      for (int nb = 0; nb < 4; nb++) {
+        uint32_t ph[8], pl[8];
         float psum = 0.f;
+        const float mref = m_run[nb];
 #pragma unroll
         for (int m = 0; m < 4; m++) {
           float p[4];
 #pragma unroll
           for (int i = 0; i < 4; i++) {
-            p[i] = __builtin_amdgcn_exp2f(s[m][nb][i] - m_new);
+            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
             psum += p[i];
           }
-          pb[nb][2 * m] = pack_bf16(p[0], p[1]);
-          pb[nb][2 * m + 1] = pack_bf16(p[2], p[3]);
+          ph[2 * m] = pack_bf16(p[0], p[1]);
+          ph[2 * m + 1] = pack_bf16(p[2], p[3]);
+          pl[2 * m] = pack_bf16(p[0] - __uint_as_float(ph[2 * m] << 16), p[1] - __uint_as_float(ph[2 * m] & 0xffff0000u));
+          pl[2 * m + 1] = pack_bf16(p[2] - __uint_as_float(ph[2 * m + 1] << 16), p[3] - __uint_as_float(ph[2 * m + 1] & 0xffff0000u));
         }
-        l_run[nb] = l_run[nb] * alpha + psum;
-#pragma unroll
-        for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
-      }
-      // ---------------- GEMM2: O^T[128 ch x 64 queries] += V^T . P^T ----------------
-#pragma unroll
-      for (int mb = 0; mb < 8; mb++) {
+        l_run[nb] += psum;
+        const uint4 h0 = make_uint4(ph[0], ph[1], ph[2], ph[3]), h1 = make_uint4(ph[4], ph[5], ph[6], ph[7]);
+        const uint4 l0 = make_uint4(pl[0], pl[1], pl[2], pl[3]), l1 = make_uint4(pl[4], pl[5], pl[6], pl[7]);
         if (v_sparse) {
-          const int idx = (int)reinterpret_cast<const uint32_t*>(vl + 512)[(mb >> 1) * 64 + l];
-          const bf16x8_t av = as_bf16x8(vl[mb * 64 + l]);
+          const bf16x16_t bh = as_bf16x16(h0, h1), bl = as_bf16x16(l0, l1);
 #pragma unroll
-          for (int nb = 0; nb < 4; nb++) {
-            const bf16x16_t bp = as_bf16x16(make_uint4(pb[nb][0], pb[nb][1], pb[nb][2], pb[nb][3]),
-                                            make_uint4(pb[nb][4], pb[nb][5], pb[nb][6], pb[nb][7]));
-            if (mb & 1)
-              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bp, o[mb][nb], idx, 0, 1);
-            else
-              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bp, o[mb][nb], idx, 0, 0);
+          for (int mb = 0; mb < 8; mb++) {
+            if (mb & 1) {
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bh, o[mb][nb], vidx[mb >> 1], 0, 1);
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bl, o[mb][nb], vidx[mb >> 1], 0, 1);
+            } else {
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bh, o[mb][nb], vidx[mb >> 1], 0, 0);
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bl, o[mb][nb], vidx[mb >> 1], 0, 0);
+            }
           }
         } else {
 #pragma unroll
-          for (int h = 0; h < 2; h++) {
-            const bf16x8_t av = as_bf16x8(vl[(2 * mb + h) * 64 + l]);
-#pragma unroll
-            for (int nb = 0; nb < 4; nb++) {
-              const bf16x8_t bp = as_bf16x8(make_uint4(pb[nb][4 * h], pb[nb][4 * h + 1], pb[nb][4 * h + 2], pb[nb][4 * h + 3]));
-              o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bp, o[mb][nb], 0, 0, 0);
-            }
+          for (int mb = 0; mb < 8; mb++) {
+            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb]), as_bf16x8(h0), o[mb][nb], 0, 0, 0);
+            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb + 1]), as_bf16x8(h1), o[mb][nb], 0, 0, 0);
+            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb]), as_bf16x8(l0), o[mb][nb], 0, 0, 0);
+            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb + 1]), as_bf16x8(l1), o[mb][nb], 0, 0, 0);
           }
         }
       }
