@@ -97,7 +97,7 @@ def main():
     kvs = [hb.PackedKV(sh, counts) for _ in range(args.copies)]
     ws_c = torch.empty(max(16, hb.workspace_bytes(sh, 0)), dtype=torch.uint8, device="cuda")
     n_splits = hb.decode_auto_splits(sh)
-    ws_d = torch.empty(hb.workspace_bytes(sh, 2, n_splits), dtype=torch.uint8, device="cuda")
+    ws_d = torch.zeros(hb.workspace_bytes(sh, 2, n_splits), dtype=torch.uint8, device="cuda")
     O = torch.empty_like(Q)
     Od = torch.empty_like(qd)
     lse_d = torch.empty((B, Hq), dtype=torch.float32, device="cuda")

@@ -95,6 +95,10 @@ typedef struct {
   void* k_dense; void* k_nnz; void* k_meta; int32_t* k_map;
   void* v_dense; void* v_nnz; void* v_meta; int32_t* v_map;
   int32_t cap_dense_k, cap_sparse_k, cap_dense_v, cap_sparse_v;
+  int32_t uniform; /* nonzero = the caller promises that no tile is skipped and that each
+                      tensor's tiles are all of one kind, i.e. slot == tile index (what
+                      skip_frac 0 with sparse fractions in {0, 1} produces); attention
+                      kernels then skip the map lookup.  Needs the used capacities >= T. */
 } hs_kv;
 
 /* Library version (major * 100 + minor). [host, pure] */
@@ -152,7 +156,8 @@ HS_API int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int c
 /* Decode attention (split-KV kernel + merge, Sec. IV-C): one query token per
  * (b, query head) against all L cached tokens.  Q, O: bf16 [B, Hq, D];
  * LSE: fp32 [B, Hq] or NULL.  n_splits == 0 picks hs_decode_auto_splits.
- * workspace: hs_workspace_bytes(op 2, n_splits). */
+ * workspace: hs_workspace_bytes(op 2, n_splits), 16-byte aligned (split partials;
+ * no initial content needed).  Two calls in flight at once must not share one. */
 HS_API int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
                    const void* Q, const hs_kv* kv, void* O, float* LSE,
                    void* workspace, void* stream);

@@ -34,7 +34,7 @@ class HsKV(C.Structure):
     _fields_ = [("k_dense", C.c_void_p), ("k_nnz", C.c_void_p), ("k_meta", C.c_void_p), ("k_map", C.c_void_p),
                 ("v_dense", C.c_void_p), ("v_nnz", C.c_void_p), ("v_meta", C.c_void_p), ("v_map", C.c_void_p),
                 ("cap_dense_k", C.c_int32), ("cap_sparse_k", C.c_int32), ("cap_dense_v", C.c_int32),
-                ("cap_sparse_v", C.c_int32)]
+                ("cap_sparse_v", C.c_int32), ("uniform", C.c_int32)]
 
 
 EXPORTS = {
@@ -149,11 +149,15 @@ class PackedKV:
         self.k_map = torch.empty(rows_T, dtype=torch.int32, device=device)
         self.v_map = torch.empty(rows_T, dtype=torch.int32, device=device)
         self.nbytes = sum(nb)
+        T = shape.L // TILE
+        # slot == tile index: nothing skipped, one kind of tile per tensor, same kind in K and V
+        self.uniform = int(counts[0] == 0 and (counts[1] == 0 or counts[2] == 0) and (counts[3] == 0 or counts[4] == 0)
+                           and (counts[1] == 0) == (counts[3] == 0) and max(counts[1], counts[2]) == T)
 
     def struct(self):
         return HsKV(_ptr(self.k_dense), _ptr(self.k_nnz), _ptr(self.k_meta), _ptr(self.k_map),
                     _ptr(self.v_dense), _ptr(self.v_nnz), _ptr(self.v_meta), _ptr(self.v_map),
-                    self.counts[1], self.counts[2], self.counts[3], self.counts[4])
+                    self.counts[1], self.counts[2], self.counts[3], self.counts[4], self.uniform)
 
 
 def _workspace(nbytes, device):

@@ -272,6 +272,13 @@ int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const v
   if (!(scale >= 0.f)) return HS_EINVAL;
   if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
   if (n_splits == 0) n_splits = hs_decode_auto_splits(shape);
+  if (kv->uniform) {
+    const int T = shape->L / HS_BT;
+    const bool k_ok = (kv->cap_dense_k == 0 && kv->cap_sparse_k >= T) || (kv->cap_sparse_k == 0 && kv->cap_dense_k >= T);
+    const bool v_ok = (kv->cap_dense_v == 0 && kv->cap_sparse_v >= T) || (kv->cap_sparse_v == 0 && kv->cap_dense_v >= T);
+    const bool same = (kv->cap_dense_k == 0) == (kv->cap_dense_v == 0);
+    if (!k_ok || !v_ok || !same) return HS_EINVAL;
+  }
   const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
                                         (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
                                         (float*)workspace, (hipStream_t)stream);

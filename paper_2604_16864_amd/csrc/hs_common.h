@@ -51,6 +51,7 @@ struct hs_kv_dev {  // device-side view of hs_kv (passed by value to kernels)
   const uint8_t* k_dense; const uint8_t* k_nnz; const uint8_t* k_meta; const int32_t* k_map;
   const uint8_t* v_dense; const uint8_t* v_nnz; const uint8_t* v_meta; const int32_t* v_map;
   int32_t cap_dense_k, cap_sparse_k, cap_dense_v, cap_sparse_v;
+  int32_t uniform;
 };
 
 static inline hs_kv_dev hs_make_kv_dev(const hs_kv* kv) {
@@ -61,6 +62,7 @@ static inline hs_kv_dev hs_make_kv_dev(const hs_kv* kv) {
   d.v_meta = (const uint8_t*)kv->v_meta;   d.v_map = kv->v_map;
   d.cap_dense_k = kv->cap_dense_k; d.cap_sparse_k = kv->cap_sparse_k;
   d.cap_dense_v = kv->cap_dense_v; d.cap_sparse_v = kv->cap_sparse_v;
+  d.uniform = kv->uniform;
   return d;
 }
 

@@ -39,8 +39,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 __device__ __forceinline__ float bf16_lo_f(uint32_t p) { return __uint_as_float(p << 16); }
 __device__ __forceinline__ float bf16_hi_f(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
 
-// Workspace layout: partial O (normalised) [B*Hq][n_splits][128] fp32, then partial LSE
-// [B*Hq][n_splits] fp32 (natural log; -inf for an empty split).
 
 // Operand registers of one tile (K and V), filled by tile_load and consumed by tile_compute.
 template <int MODE>
@@ -168,11 +166,13 @@ __device__ __forceinline__ void tile_compute(const TileRegs<MODE>& r, const uint
 // entries of its tiles with one vector load, drops the skipped ones, and streams the rest
 // with a two-deep register pipeline (the loads of tile i+1 are in flight while tile i is
 // being multiplied).
-template <int MODE>  // 0: every tile 2:4 or skipped; 1: every tile dense or skipped; 2: any mix
+// Each workgroup emits a normalised partial output and its log-sum-exp per query head.
+template <int MODE, bool UNIFORM>  // MODE 0: every tile 2:4 or skipped; 1: dense or skipped; 2: any mix
 __global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2,
                                                                              int n_splits, int per,
                                                                              const uint16_t* __restrict__ Q,
-                                                                             hs_kv_dev kv, float* __restrict__ ws) {
+                                                                             hs_kv_dev kv, float* __restrict__ ws_o,
+                                                                             float* __restrict__ ws_l) {
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, c = l & 15;
   const int G = Hq / Hkv;
@@ -200,8 +200,13 @@ __global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(in
     const int t_mine = base + 4 * l;
     int mk_v = 0, mv_v = 0;
     if (t_mine < t_end) {
-      mk_v = kv.k_map[row * T + t_mine];
-      mv_v = kv.v_map[row * T + t_mine];
+      if (UNIFORM) {  // promised by the caller: no tile skipped, one kind per tensor, slot == tile
+        mk_v = MODE == 0 ? -(t_mine + 1) : t_mine + 1;
+        mv_v = mk_v;
+      } else {
+        mk_v = kv.k_map[row * T + t_mine];
+        mv_v = kv.v_map[row * T + t_mine];
+      }
     }
     unsigned long long act = __ballot(mk_v != 0);
     if (act == 0ull) continue;
@@ -234,7 +239,10 @@ __global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(in
 #pragma unroll
   for (int i = 0; i < 8; i++)
 #pragma unroll
-    for (int j = 0; j < 4; j++) o[i][j] += __shfl_xor(o[i][j], 8);  // column c + column c^8
+    for (int j = 0; j < 4; j++) {  // column c + column c^8 (rotate by 8 inside the 16-lane row)
+      const int other = __builtin_amdgcn_mov_dpp(__float_as_int(o[i][j]), 0x128, 0xf, 0xf, true);
+      o[i][j] += __int_as_float(other);
+    }
 
   __shared__ float sm_m[4][8], sm_l[4][8];
   __shared__ float sm_o[4][8][HS_D];
@@ -248,6 +256,7 @@ __global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(in
   __syncthreads();
   // thread -> (head g = tid / 32, 4 channels)
   const int g = tid >> 5, ch = (tid & 31) * 4;
+  const int64_t hq = (int64_t)b * Hq + hkv * G + (g < G ? g : 0);
   if (g < G) {
     float mstar = fmaxf(fmaxf(sm_m[0][g], sm_m[1][g]), fmaxf(sm_m[2][g], sm_m[3][g]));
     float lsum = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -261,73 +270,96 @@ __global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(in
       }
     }
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-    const int64_t hq = (int64_t)b * Hq + hkv * G + g;
-    float* po = ws + (hq * n_splits + split) * HS_D + ch;
+    float* po = ws_o + (hq * n_splits + split) * HS_D + ch;
     *reinterpret_cast<float4*>(po) = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-    if ((tid & 31) == 0) {
-      float* pl = ws + (int64_t)gridDim.z * Hq * n_splits * HS_D;
-      pl[hq * n_splits + split] = lsum > 0.f ? (mstar + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
-    }
+    if ((tid & 31) == 0)
+      ws_l[hq * n_splits + split] = lsum > 0.f ? (mstar + __builtin_amdgcn_logf(lsum)) * kLn2 : -INFINITY;
   }
 }
 
 // Merge of the split partials (Sec. IV-C "lightweight post-processing kernel"):
-// M = max LSE_s, O = sum e^{LSE_s - M} O_s / sum e^{LSE_s - M}.  One workgroup of 256
-// threads per (b, query head): thread = (split lane tid/32 of 8, 4 channels).
-__global__ __launch_bounds__(256) void decode_merge_kernel(int n_rows, int n_splits, const float* __restrict__ ws,
-                                                           uint16_t* __restrict__ O, float* __restrict__ LSE) {
-  __shared__ float red[8];
-  __shared__ float sacc[8][HS_D + 1];
+// O = sum_s e^{LSE_s - M} O_s / sum_s e^{LSE_s - M}, M = max_s LSE_s, done in one pass with a
+// running reference per thread.  One workgroup of 256 threads per (b, query head):
+// thread = (split lane tid/32 of 8, 4 channels); the 8 split lanes are combined in LDS.
+// A separate launch on purpose: folding it into the split kernel ("last workgroup to arrive
+// merges") needs device-scope visibility between workgroups on different XCDs, and both ways
+// of getting it (a device-wide fence per workgroup, or write-through stores and L2-bypassing
+// loads) measured slower than this launch.
+__global__ __launch_bounds__(256) void decode_merge_kernel(int n_splits, const float* __restrict__ ws_o,
+                                                           const float* __restrict__ ws_l, uint16_t* __restrict__ O,
+                                                           float* __restrict__ LSE) {
+  __shared__ float sm_acc[8][HS_D];
+  __shared__ float sm_ml[8][2];
   const int hq = blockIdx.x, tid = threadIdx.x, sl = tid >> 5, ch = (tid & 31) * 4;
-  const float* po = ws + (int64_t)hq * n_splits * HS_D;
-  const float* pl = ws + (int64_t)n_rows * n_splits * HS_D + (int64_t)hq * n_splits;
-  float M = -INFINITY;
-  for (int s = tid; s < n_splits; s += 256) M = fmaxf(M, pl[s]);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-  if ((tid & 63) == 0) red[tid >> 6] = M;
-  __syncthreads();
-  M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float den = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
-  if (M > -INFINITY) {
-    for (int s = sl; s < n_splits; s += 8) {
-      const float f = __expf(pl[s] - M);
-      const float4 v = *reinterpret_cast<const float4*>(po + (int64_t)s * HS_D + ch);
-      den += f;
-      acc[0] += f * v.x; acc[1] += f * v.y; acc[2] += f * v.z; acc[3] += f * v.w;
+  const float* po = ws_o + (int64_t)hq * n_splits * HS_D + ch;
+  const float* pl = ws_l + (int64_t)hq * n_splits;
+  float M = -INFINITY, den = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int s = sl; s < n_splits; s += 8) {
+    const float lse = pl[s];
+    const float4 v = *reinterpret_cast<const float4*>(po + (int64_t)s * HS_D);
+    if (lse > -INFINITY) {
+      const float Mn = fmaxf(M, lse);
+      const float fo = __expf(M - Mn), fn = __expf(lse - Mn);  // fo = 0 while M is still -inf
+      den = den * fo + fn;
+      acc[0] = acc[0] * fo + fn * v.x; acc[1] = acc[1] * fo + fn * v.y;
+      acc[2] = acc[2] * fo + fn * v.z; acc[3] = acc[3] * fo + fn * v.w;
+      M = Mn;
     }
   }
+  if ((tid & 31) == 0) { sm_ml[sl][0] = M; sm_ml[sl][1] = den; }
 #pragma unroll
-  for (int i = 0; i < 4; i++) sacc[sl][ch + i] = acc[i];
-  if ((tid & 31) == 0) sacc[sl][HS_D] = den;
+  for (int i = 0; i < 4; i++) sm_acc[sl][ch + i] = acc[i];
   __syncthreads();
   if (tid < HS_D) {
-    float num = 0.f, d = 0.f;
+    float Mt = -INFINITY;
 #pragma unroll
-    for (int k = 0; k < 8; k++) { num += sacc[k][tid]; d += sacc[k][HS_D]; }
+    for (int k = 0; k < 8; k++) Mt = fmaxf(Mt, sm_ml[k][0]);
+    float num = 0.f, d = 0.f;
+    if (Mt > -INFINITY) {
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        const float f = __expf(sm_ml[k][0] - Mt);  // 0 for a split lane that saw nothing
+        num += f * sm_acc[k][tid];
+        d += f * sm_ml[k][1];
+      }
+    }
     const float out = d > 0.f ? num / d : 0.f;
     O[(int64_t)hq * HS_D + tid] = (uint16_t)(pack_bf16(out, 0.f) & 0xffffu);
-    if (LSE != nullptr && tid == 0) LSE[hq] = d > 0.f ? M + __logf(d) : -INFINITY;
+    if (LSE != nullptr && tid == 0) LSE[hq] = d > 0.f ? Mt + __logf(d) : -INFINITY;
   }
 }
 
 }  // namespace
 
+// Workspace: [partial O (normalised) [B*Hq][n_splits][128] fp32][partial LSE [B*Hq][n_splits] fp32].
+template <int MODE, bool UNIFORM>
+static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T, float sl2, int n_splits, int per,
+                               const uint16_t* Q, const hs_kv_dev& kv, float* wo, float* wl) {
+  hipLaunchKernelGGL((decode_split_kernel<MODE, UNIFORM>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits, per, Q,
+                     kv, wo, wl);
+  return hipGetLastError();
+}
+
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q, hs_kv_dev kv,
                             uint16_t* O, float* LSE, float* ws, hipStream_t st) {
-  const dim3 grid(n_splits, Hkv, B), block(256);
+  const dim3 grid(n_splits, Hkv, B);
   const float sl2 = scale * kLog2e;
   const int per = (T + n_splits - 1) / n_splits;
+  float* wo = ws;
+  float* wl = wo + (size_t)B * Hq * n_splits * HS_D;
   const bool no_dense = kv.cap_dense_k == 0 && kv.cap_dense_v == 0;
   const bool no_sparse = kv.cap_sparse_k == 0 && kv.cap_sparse_v == 0;
+  hipError_t e;
   if (no_dense)
-    hipLaunchKernelGGL(decode_split_kernel<0>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, ws);
+    e = kv.uniform ? launch_split<0, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)
+                   : launch_split<0, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);
   else if (no_sparse)
-    hipLaunchKernelGGL(decode_split_kernel<1>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, ws);
+    e = kv.uniform ? launch_split<1, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)
+                   : launch_split<1, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);
   else
-    hipLaunchKernelGGL(decode_split_kernel<2>, grid, block, 0, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, ws);
-  hipError_t e = hipGetLastError();
+    e = launch_split<2, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, B * Hq, n_splits, ws, O, LSE);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);
   return hipGetLastError();
 }
