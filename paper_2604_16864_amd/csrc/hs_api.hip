@@ -133,10 +133,10 @@ int hs_decode_auto_splits(const hs_shape* shape) {
   if (check_shape(shape) != HS_OK) return 0;
   const int T = shape->L / HS_BT;
   const int rows = shape->B * shape->Hkv;
-  // about 2048 waves (8 per compute unit); every wave of a split gets the same number of
-  // tiles: per = 4 * ceil(total tiles / 2048)
+  // about 1024 waves (one workgroup per compute unit, measured best on the 32K-context
+  // shape); every wave of a split gets the same number of tiles: per = 4 * ceil(tiles / 1024)
   const int64_t total = (int64_t)rows * T;
-  const int per_wave = (int)((total + 2047) / 2048);
+  const int per_wave = (int)((total + 1023) / 1024);
   const int per = 4 * (per_wave < 1 ? 1 : per_wave);
   int n = (T + per - 1) / per;
   if (n < 1) n = 1;

@@ -32,67 +32,61 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// p0, p1 -> packed bf16 pair of their upper halves (truncation) and packed bf16 pair of the
+// remainders: hi + lo reproduces p to ~16 bits.
+__device__ __forceinline__ void split_hi_lo(float p0, float p1, uint32_t& hi, uint32_t& lo) {
+  const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
+  hi = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+  lo = pack_bf16(p0 - __uint_as_float(b0 & 0xffff0000u), p1 - __uint_as_float(b1 & 0xffff0000u));
+}
+
 constexpr int kBufBytes = 32768;  // one stage: K region 16 KiB + V region 16 KiB
 
-// Registers that carry the next tile from global memory to LDS.
-struct Stage {
-  uint4 k[4];
-  uint4 v[4];
-};
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
+// Copy one tile (K and V operands) from its pool slots into an LDS stage with direct
+// global->LDS loads (no staging registers): a chunk is 64 lanes x 16 B = 1 KiB, lane l's
+// 16 bytes land at chunk base + 16 l, which is the order the pools are stored in.  The 4
+// waves share the chunks round-robin.  2:4 tile: 8 value chunks + 1 metadata chunk per
+// tensor (value chunks at 0..8 KiB, metadata at 8 KiB of the tensor's region); dense: 16.
 template <int MODE>
-__device__ __forceinline__ void stage_load(Stage& sg, const hs_kv_dev& kv, int64_t row, int mk, int mv, int tid) {
+__device__ __forceinline__ void stage_issue(uint8_t* buf, const hs_kv_dev& kv, int64_t row, int mk, int mv, int w,
+                                            int l) {
   const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
   const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+  const uint8_t *kd, *km = nullptr, *vd, *vm = nullptr;
+  int nk, nv;
   if (k_sparse) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
-    const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES);
-    sg.k[0] = p[tid];
-    sg.k[1] = p[tid + 256];
-    if (tid < 64) sg.k[2] = reinterpret_cast<const uint4*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES)[tid];
+    kd = kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    km = kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES;
+    nk = 8;
   } else {
-    const int64_t slot = row * kv.cap_dense_k + (mk - 1);
-    const uint4* p = reinterpret_cast<const uint4*>(kv.k_dense + slot * (int64_t)HS_TILE_DENSE_BYTES);
-#pragma unroll
-    for (int i = 0; i < 4; i++) sg.k[i] = p[tid + 256 * i];
+    kd = kv.k_dense + (row * kv.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+    nk = 16;
   }
   if (v_sparse) {
     const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
-    const uint4* p = reinterpret_cast<const uint4*>(kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES);
-    sg.v[0] = p[tid];
-    sg.v[1] = p[tid + 256];
-    if (tid < 64) sg.v[2] = reinterpret_cast<const uint4*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES)[tid];
+    vd = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    vm = kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES;
+    nv = 8;
   } else {
-    const int64_t slot = row * kv.cap_dense_v + (mv - 1);
-    const uint4* p = reinterpret_cast<const uint4*>(kv.v_dense + slot * (int64_t)HS_TILE_DENSE_BYTES);
-#pragma unroll
-    for (int i = 0; i < 4; i++) sg.v[i] = p[tid + 256 * i];
+    vd = kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+    nv = 16;
   }
+  for (int ch = w; ch < nk; ch += 4)
+    __builtin_amdgcn_global_load_lds((gptr_t)(kd + ch * 1024 + l * 16), (lptr_t)(buf + ch * 1024), 16, 0, 0);
+  for (int ch = w; ch < nv; ch += 4)
+    __builtin_amdgcn_global_load_lds((gptr_t)(vd + ch * 1024 + l * 16), (lptr_t)(buf + 16384 + ch * 1024), 16, 0, 0);
+  if (k_sparse && w == 0)
+    __builtin_amdgcn_global_load_lds((gptr_t)(km + l * 16), (lptr_t)(buf + 8192), 16, 0, 0);
+  if (v_sparse && w == 1)
+    __builtin_amdgcn_global_load_lds((gptr_t)(vm + l * 16), (lptr_t)(buf + 16384 + 8192), 16, 0, 0);
 }
 
-template <int MODE>
-__device__ __forceinline__ void stage_store(const Stage& sg, uint8_t* buf, int mk, int mv, int tid) {
-  const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
-  const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
-  uint4* kd = reinterpret_cast<uint4*>(buf);
-  uint4* vd = reinterpret_cast<uint4*>(buf + 16384);
-  if (k_sparse) {
-    kd[tid] = sg.k[0];
-    kd[tid + 256] = sg.k[1];
-    if (tid < 64) kd[512 + tid] = sg.k[2];
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; i++) kd[tid + 256 * i] = sg.k[i];
-  }
-  if (v_sparse) {
-    vd[tid] = sg.v[0];
-    vd[tid + 256] = sg.v[1];
-    if (tid < 64) vd[512 + tid] = sg.v[2];
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; i++) vd[tid + 256 * i] = sg.v[i];
-  }
-}
+// all of this wave's direct-to-LDS loads have landed (vmcnt = 0; other counters untouched)
+__device__ __forceinline__ void stage_wait() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // next tile index > j (and <= jmax) whose map entry is not 0, or -1
 __device__ __forceinline__ int next_active(const int32_t* km, int j, int jmax) {
@@ -145,22 +139,23 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T,
 #pragma unroll
   for (int nb = 0; nb < 4; nb++) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
 
-  Stage sg;
   int j = next_active(km, -1, jmax_wg);
   int mk = 0, mv = 0;
   if (j >= 0) {
     mk = km[j]; mv = vm[j];
-    stage_load<MODE>(sg, kv, row, mk, mv, tid);
-    stage_store<MODE>(sg, lds, mk, mv, tid);
+    stage_issue<MODE>(lds, kv, row, mk, mv, w, l);
   }
+  stage_wait();
   __syncthreads();
   int buf = 0;
   while (j >= 0) {
+    // prefetch the next visible tile into the other stage; it is waited for at the end of
+    // this iteration, after the arithmetic on the current one
     const int jn = next_active(km, j, jmax_wg);
     int mkn = 0, mvn = 0;
     if (jn >= 0) {
       mkn = km[jn]; mvn = vm[jn];
-      stage_load<MODE>(sg, kv, row, mkn, mvn, tid);
+      stage_issue<MODE>(lds + (buf ^ 1) * kBufBytes, kv, row, mkn, mvn, w, l);
     }
     if (valid && j <= jmax_w) {
       const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
@@ -180,13 +175,17 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T,
         for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];
 #pragma unroll
         for (int m = 0; m < 4; m++) kidx[m] = (int)reinterpret_cast<const uint32_t*>(kl + 512)[m * 64 + l];
+        // 16 independent accumulators between the two instructions that share one
 #pragma unroll
         for (int nb = 0; nb < 4; nb++)
 #pragma unroll
-          for (int m = 0; m < 4; m++) {
+          for (int m = 0; m < 4; m++)
             s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ak[2 * m]), as_bf16x16(qb[nb][0], qb[nb][1]), s[m][nb], kidx[m], 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < 4; nb++)
+#pragma unroll
+          for (int m = 0; m < 4; m++)
             s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ak[2 * m + 1]), as_bf16x16(qb[nb][2], qb[nb][3]), s[m][nb], kidx[m], 0, 1);
-          }
       } else {
 #pragma unroll
         for (int m = 0; m < 4; m++) {
@@ -194,9 +193,9 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T,
 #pragma unroll
           for (int st = 0; st < 4; st++) ak[st] = kl[(4 * m + st) * 64 + l];
 #pragma unroll
-          for (int nb = 0; nb < 4; nb++)
+          for (int st = 0; st < 4; st++)
 #pragma unroll
-            for (int st = 0; st < 4; st++)
+            for (int nb = 0; nb < 4; nb++)
               s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[st]), as_bf16x8(qb[nb][st]), s[m][nb], 0, 0, 0);
         }
       }
@@ -241,7 +240,29 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T,
           for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
         }
       }
-      // ---------------- V operands (A of GEMM2) ----------------
+      // ---------------- P = exp2(S*scale - m) and O^T += V^T P^T, software-pipelined ----------------
+      // P goes through the matrix unit as two bf16 terms (upper half of p + remainder): a
+      // single bf16 P alone costs ~1.3e-3 mean relative error on the output, on top of the
+      // bf16 rounding of O itself.  The matrix instructions of column block nb are issued
+      // interleaved with the vector-ALU softmax of block nb+1.
+      uint32_t ph[2][8], pl[2][8];
+      auto softmax_block = [&](int nb, uint32_t (&h)[8], uint32_t (&lo)[8]) {
+        float psum = 0.f;
+        const float mref = m_run[nb];
+#pragma unroll
+        for (int m = 0; m < 4; m++) {
+          float p[4];
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
+            psum += p[i];
+          }
+          split_hi_lo(p[0], p[1], h[2 * m], lo[2 * m]);
+          split_hi_lo(p[2], p[3], h[2 * m + 1], lo[2 * m + 1]);
+        }
+        l_run[nb] += psum;
+      };
+      softmax_block(0, ph[0], pl[0]);
       uint4 av[16];
       int vidx[4];
       if (v_sparse) {
@@ -253,55 +274,51 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel(int Hq, int Hkv, int T,
 #pragma unroll
         for (int i = 0; i < 16; i++) av[i] = vl[i * 64 + l];
       }
-      // ---------------- per column block: P = exp2(S*scale - m), then O^T += V^T P^T ----------------
-      // P goes through the matrix unit as bf16(p) + bf16(p - bf16(p)): two instructions per
-      // block, so the product sees p to ~16 bits (a single bf16 P alone costs ~1.3e-3 mean
-      // relative error on the output, on top of the bf16 rounding of O itself).
 #pragma unroll
       for (int nb = 0; nb < 4; nb++) {
-        uint32_t ph[8], pl[8];
-        float psum = 0.f;
-        const float mref = m_run[nb];
-#pragma unroll
-        for (int m = 0; m < 4; m++) {
-          float p[4];
-#pragma unroll
-          for (int i = 0; i < 4; i++) {
-            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
-            psum += p[i];
-          }
-          ph[2 * m] = pack_bf16(p[0], p[1]);
-          ph[2 * m + 1] = pack_bf16(p[2], p[3]);
-          pl[2 * m] = pack_bf16(p[0] - __uint_as_float(ph[2 * m] << 16), p[1] - __uint_as_float(ph[2 * m] & 0xffff0000u));
-          pl[2 * m + 1] = pack_bf16(p[2] - __uint_as_float(ph[2 * m + 1] << 16), p[3] - __uint_as_float(ph[2 * m + 1] & 0xffff0000u));
-        }
-        l_run[nb] += psum;
-        const uint4 h0 = make_uint4(ph[0], ph[1], ph[2], ph[3]), h1 = make_uint4(ph[4], ph[5], ph[6], ph[7]);
-        const uint4 l0 = make_uint4(pl[0], pl[1], pl[2], pl[3]), l1 = make_uint4(pl[4], pl[5], pl[6], pl[7]);
+        const uint32_t(&h)[8] = ph[nb & 1];
+        const uint32_t(&lo)[8] = pl[nb & 1];
+        const uint4 h0 = make_uint4(h[0], h[1], h[2], h[3]), h1 = make_uint4(h[4], h[5], h[6], h[7]);
+        const uint4 l0 = make_uint4(lo[0], lo[1], lo[2], lo[3]), l1 = make_uint4(lo[4], lo[5], lo[6], lo[7]);
         if (v_sparse) {
           const bf16x16_t bh = as_bf16x16(h0, h1), bl = as_bf16x16(l0, l1);
 #pragma unroll
           for (int mb = 0; mb < 8; mb++) {
-            if (mb & 1) {
+            if (mb & 1)
               o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bh, o[mb][nb], vidx[mb >> 1], 0, 1);
-              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bl, o[mb][nb], vidx[mb >> 1], 0, 1);
-            } else {
+            else
               o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bh, o[mb][nb], vidx[mb >> 1], 0, 0);
+          }
+#pragma unroll
+          for (int mb = 0; mb < 8; mb++) {
+            if (mb & 1)
+              o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bl, o[mb][nb], vidx[mb >> 1], 0, 1);
+            else
               o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bl, o[mb][nb], vidx[mb >> 1], 0, 0);
-            }
           }
         } else {
 #pragma unroll
-          for (int mb = 0; mb < 8; mb++) {
-            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb]), as_bf16x8(h0), o[mb][nb], 0, 0, 0);
-            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb + 1]), as_bf16x8(h1), o[mb][nb], 0, 0, 0);
-            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb]), as_bf16x8(l0), o[mb][nb], 0, 0, 0);
-            o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb + 1]), as_bf16x8(l1), o[mb][nb], 0, 0, 0);
+          for (int mb = 0; mb < 8; mb++) o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb]), as_bf16x8(h0), o[mb][nb], 0, 0, 0);
+#pragma unroll
+          for (int mb = 0; mb < 8; mb++) o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb + 1]), as_bf16x8(h1), o[mb][nb], 0, 0, 0);
+#pragma unroll
+          for (int mb = 0; mb < 8; mb++) o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb]), as_bf16x8(l0), o[mb][nb], 0, 0, 0);
+#pragma unroll
+          for (int mb = 0; mb < 8; mb++) o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[2 * mb + 1]), as_bf16x8(l1), o[mb][nb], 0, 0, 0);
+        }
+        if (nb < 3) {
+          softmax_block(nb + 1, ph[(nb + 1) & 1], pl[(nb + 1) & 1]);
+          // one matrix instruction, then a slice of the next block's softmax
+          constexpr int kMfma = 16;  // per block: 2:4 -> 8 hi + 8 lo; dense issues 32, the rest trail
+#pragma unroll
+          for (int k = 0; k < kMfma; k++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
           }
         }
       }
     }
-    if (jn >= 0) stage_store<MODE>(sg, lds + (buf ^ 1) * kBufBytes, mkn, mvn, tid);
+    stage_wait();
     __syncthreads();
     j = jn; mk = mkn; mv = mvn;
     buf ^= 1;
