@@ -26,6 +26,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_DENSE_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE on this workload (summary, commands and
+# the copy-kernel calibration: profiles/bench_cfg1_hbm_traffic.md).  Only valid for cfg1 with 2:4 on all tiles.
+TRAFFIC_BYTES = {"decode": (36949.8 * 2.000 + 544.0) * 1024, "compress": (65851.7 * 2.000 + 73728.0) * 1024,
+                 "prefill": (823241.6 * 2.000 + 262144.0) * 1024}
 
 
 def packed_bytes(B, Hkv, T, counts):
@@ -67,6 +71,9 @@ def main():
     ap.add_argument("--copies", type=int, default=8, help="packed-cache buffers to rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-KV baseline legs")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (reference kernel of known traffic for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -115,6 +122,14 @@ def main():
         if ev: ev[2].record()
         hb.decode_attn(sh, qd, kv_r, n_splits=n_splits, out=Od, lse=lse_d, workspace=ws_d)
         if ev: ev[3].record()
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
@@ -195,14 +210,14 @@ def main():
         "stages": stages,
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0> (+ merge)", "achieved": decode_bytes / dec_s / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": decode_bytes / dec_s / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": None},
+                     "traffic": TRAFFIC_BYTES["decode"]},
         "roofline_prefill": {"bound": "mfma", "kernel": "prefill_kernel<0>", "achieved": prefill_flops / pre_s / 1e12,
                              "peak": MFMA_BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
-                             "frac": prefill_flops / pre_s / 1e12 / MFMA_BF16_DENSE_PEAK_TFLOPS, "traffic": None,
+                             "frac": prefill_flops / pre_s / 1e12 / MFMA_BF16_DENSE_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES["prefill"],
                              "note": "dense-equivalent causal FLOPs over the dense bf16 peak"},
         "roofline_compress": {"bound": "hbm", "kernel": "pack_kernel", "achieved": compress_bytes / cmp_s / 1e9,
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": compress_bytes / cmp_s / 1e9 / HBM_PEAK_GBPS,
-                              "traffic": None},
+                              "traffic": TRAFFIC_BYTES["compress"]},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, sample_heads=2)
