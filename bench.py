@@ -38,10 +38,11 @@ def packed_bytes(B, Hkv, T, counts):
     return B * Hkv * per_row
 
 
-def cpu_baseline(cfg, sample_heads):
-    """The oracle, as it stands, timed on the host on a bounded sample of the same
-    workload: decode attention (unpack + fp64 softmax attention) over `sample_heads`
-    of the KV heads.  Reported in the metric's unit (compressed GB/s)."""
+def cpu_baseline(cfg):
+    """The oracle, as it stands, timed on the host on the same workload (same seeded inputs):
+    prune + pack of the whole cache, decode attention over all heads, and causal prefill
+    attention for a bounded sample of query rows.  `value` is the decode leg in the metric's
+    unit (packed GB/s); the other legs are quoted in `sample`."""
     import numpy as np
     from oracle import hs_oracle as orc
     from paper_2604_16864_amd import workloads as wl
@@ -50,17 +51,111 @@ def cpu_baseline(cfg, sample_heads):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = 1
-    G = cfg["Hq"] // cfg["Hkv"]
-    Q, K, V = wl.make_qkv(cfg["B"], sample_heads * G, sample_heads, cfg["L"], cfg["D"], 1, cfg["seed"], cfg["k_outliers"])
-    q = Q[:, :, 0, :].copy()
+    n_rows = 48
+    Q, K, V = wl.make_qkv(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["D"], cfg["L"], cfg["seed"], cfg["k_outliers"])
+    q = Q[:, :, -1, :].copy()
+    t0 = time.perf_counter()
     pk, pv, _ = orc.compress_kv(K, V, Bt=64)
+    t_c = time.perf_counter() - t0
     t0 = time.perf_counter()
     orc.attention_decode(q, pk, pv)
-    dt = time.perf_counter() - t0
+    t_d = time.perf_counter() - t0
+    rows = wl.sample_rows(cfg["B"], cfg["Hq"], cfg["L"], n_rows, seed=cfg["seed"] + 4)
+    t0 = time.perf_counter()
+    orc.attention_rows(Q, pk, pv, rows, causal=True)
+    t_p = time.perf_counter() - t0
     nbytes = pk.nbytes() + pv.nbytes()
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"oracle decode attention (unpack + fp64 attention) over {sample_heads} of {cfg['Hkv']} KV heads "
-                      f"of the same workload, {nbytes / 1e6:.1f} MB packed, {dt:.2f} s"}
+    return {"value": nbytes / t_d / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"same workload and inputs: oracle decode attention over all {cfg['Hkv']} KV heads "
+                      f"({nbytes / 1e6:.1f} MB packed) {t_d:.2f} s; prune+pack of the whole cache {t_c:.2f} s; "
+                      f"causal prefill attention for {n_rows} sampled query rows {t_p:.2f} s "
+                      f"({t_p / n_rows * 1e3:.0f} ms per row incl. one unpack of the cache)",
+            "compress_s": t_c, "decode_s": t_d, "prefill_rows": n_rows, "prefill_rows_s": t_p}
+
+
+def _time(torch, fn, reps, warm=1):
+    for _ in range(warm):
+        fn(0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def extra_legs(hb, torch, Q, K, V, qd, sh, args):
+    """Context numbers beside the headline: other sparsity settings of the same path.  Inputs of the two
+    large shapes are N(0,1) drawn on the device (seeded torch generator); everything else as in the step."""
+    res = {}
+    B, Hq, Hkv, L = sh.B, sh.Hq, sh.Hkv, sh.L
+    T = L // 64
+    ws_c = torch.empty(max(16, hb.workspace_bytes(sh, 0)), dtype=torch.uint8, device="cuda")
+    # (1) the paper's quality-preserving point: keys dense, values 2:4 (S_K = 0, S_V = 1), same workload
+    pol = hb.make_policy(sparse_frac_k=0.0, sparse_frac_v=1.0)
+    cts = hb.tile_counts(sh, pol)
+    kvm = [hb.compress_kv(sh, pol, K, V, workspace=ws_c) for _ in range(6)]
+    O = torch.empty_like(Q)
+    t_p = _time(torch, lambda i: hb.prefill_attn(sh, Q, kvm[i % 6], causal=True, want_lse=False, out=O), 3)
+    n = hb.decode_auto_splits(sh)
+    ws_d = torch.empty(hb.workspace_bytes(sh, 2, n), dtype=torch.uint8, device="cuda")
+    Od = torch.empty_like(qd)
+    t_d = _time(torch, lambda i: hb.decode_attn(sh, qd, kvm[i % 6], n_splits=n, want_lse=False, out=Od, workspace=ws_d), 24, warm=6)
+    res["sk0_sv1_same_workload"] = {"prefill_ms": t_p * 1e3, "decode_us": t_d * 1e6,
+                                    "decode_GBps": packed_bytes(B, Hkv, T, cts) / t_d / 1e9,
+                                    "ideal_prefill_speedup": 4.0 / 3.0, "ideal_decode_speedup": 1.0 / (1.0 - 0.21875)}
+    del kvm, O
+    torch.cuda.empty_cache()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3000)
+    # (2) hierarchical decode sweep: B8, 32/8 heads, L131072; skip {0, .25, .5, .75} of the tiles + 2:4 in the rest
+    B3, L3 = 8, 131072
+    sh3 = hb.make_shape(B3, Hq, Hkv, L3)
+    K3 = torch.randn((B3, Hkv, L3, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    V3 = torch.randn((B3, Hkv, L3, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    q3 = torch.randn((B3, Hq, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    ws3 = torch.empty(hb.workspace_bytes(sh3, 0), dtype=torch.uint8, device="cuda")
+    n3 = hb.decode_auto_splits(sh3)
+    wsd3 = torch.empty(hb.workspace_bytes(sh3, 2, n3), dtype=torch.uint8, device="cuda")
+    O3 = torch.empty_like(q3)
+    sweep = []
+    for name3, kw in (("dense", dict(sparse_frac_k=0.0, sparse_frac_v=0.0)), ("skip0", dict(skip_frac=0.0)),
+                      ("skip0.25", dict(skip_frac=0.25)), ("skip0.5", dict(skip_frac=0.5)), ("skip0.75", dict(skip_frac=0.75))):
+        p3 = hb.make_policy(**kw)
+        c3 = hb.tile_counts(sh3, p3)
+        kv3 = hb.PackedKV(sh3, c3)
+        t_c = _time(torch, lambda i: hb.compress_kv(sh3, p3, K3, V3, out=kv3, workspace=ws3), 2)
+        t = _time(torch, lambda i: hb.decode_attn(sh3, q3, kv3, n_splits=n3, want_lse=False, out=O3, workspace=wsd3), 5)
+        nb = packed_bytes(B3, Hkv, L3 // 64, c3)
+        sweep.append({"case": name3, "decode_us": t * 1e6, "decode_GBps": nb / t / 1e9, "hbm_frac": nb / t / 1e9 / HBM_PEAK_GBPS,
+                      "packed_MB": nb / 1e6, "compress_us": t_c * 1e6,
+                      "compress_GBps": (2 * B3 * Hkv * L3 * 128 * 2 + nb) / t_c / 1e9})
+        del kv3
+    for r in sweep:
+        r["speedup_vs_dense"] = sweep[0]["decode_us"] / r["decode_us"]
+    res["decode_b8_128k"] = sweep
+    del K3, V3, ws3
+    torch.cuda.empty_cache()
+    # (3) long causal prefill with tile skipping: B1, 32/8 heads, L65536
+    L4 = 65536
+    sh4 = hb.make_shape(1, Hq, Hkv, L4)
+    K4 = torch.randn((1, Hkv, L4, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    V4 = torch.randn((1, Hkv, L4, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Q4 = torch.randn((1, Hq, L4, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    O4 = torch.empty_like(Q4)
+    ws4 = torch.empty(hb.workspace_bytes(sh4, 0), dtype=torch.uint8, device="cuda")
+    flops4 = 4.0 * 128 * Hq * (L4 * (L4 + 1) / 2.0)
+    pf = []
+    for name4, kw in (("dense", dict(sparse_frac_k=0.0, sparse_frac_v=0.0)), ("2:4", dict()), ("2:4+skip0.75", dict(skip_frac=0.75))):
+        kv4 = hb.compress_kv(sh4, hb.make_policy(**kw), K4, V4, workspace=ws4)
+        t = _time(torch, lambda i: hb.prefill_attn(sh4, Q4, kv4, causal=True, want_lse=False, out=O4), 2)
+        pf.append({"case": name4, "prefill_ms": t * 1e3, "dense_equiv_TFLOPs_of_full_causal": flops4 / t / 1e12})
+        del kv4
+    for r in pf:
+        r["speedup_vs_dense"] = pf[0]["prefill_ms"] / r["prefill_ms"]
+    res["prefill_64k"] = pf
+    return res
 
 
 def main():
@@ -71,6 +166,9 @@ def main():
     ap.add_argument("--copies", type=int, default=8, help="packed-cache buffers to rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-KV baseline legs")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the extra legs (hierarchical decode sweep at B8 x 128K, long prefill with tile "
+                         "skipping, the paper's S_K=0/S_V=1 point)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference kernel of known traffic for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -200,6 +298,14 @@ def main():
             "decode_speedup_vs_dense": dec_dense / dec_s,
         })
 
+    extra = None
+    if not args.no_extra:
+        del kvs
+        if not args.no_dense:
+            del kvd
+        torch.cuda.empty_cache()
+        extra = extra_legs(hb, torch, Q, K, V, qd, sh, args)
+
     out = {
         "metric": "decode_attn_hbm_GBps_on_packed_kv", "value": decode_bytes / dec_s / 1e9, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
@@ -219,8 +325,10 @@ def main():
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": compress_bytes / cmp_s / 1e9 / HBM_PEAK_GBPS,
                               "traffic": TRAFFIC_BYTES["compress"]},
     }
+    if extra is not None:
+        out["stages_extra"] = extra
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, sample_heads=2)
+        out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
 
 

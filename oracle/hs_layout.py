@@ -11,7 +11,8 @@ semantics alone, independently of the library's index arithmetic:
                    D lane l = col l%16, rows 4*(l//16) + i   (i = 0..3)
   sparse 16x16x64: A lane l = row l%16, the kept values of k in [16*(l//16), +16)
                    B lane l = col l%16, k = 32*(e//8) + 8*(l//16) + e%8  (e = 0..15)
-                   index: 2 bits per kept value, value e at bits 2e of a 16-bit half
+                   index: 2 bits per kept value, value e at bits 2e of a 16-bit half;
+                   a lane keeps the four 32-bit index words of a tile side by side (16 B)
 
 GEMM1 (S^T = K Q^T) has tokens as rows: its D registers hold, for lane group a,
 tokens 16m + 4a + i of row block m.  GEMM2 (O^T = V^T P^T) contracts over tokens
@@ -40,7 +41,7 @@ TOKEN_OF_K = _gemm2_token_of_k()
 def k_sparse_physical(nnz, meta):
     """Canonical K tile (nnz [64, 64] u16, meta [64, 4] u32) -> (nnz bytes [8192], meta bytes [1024])."""
     out = np.zeros((4, 2, 64, 8), dtype=np.uint16)
-    om = np.zeros((4, 64), dtype=np.uint32)
+    om = np.zeros((64, 4), dtype=np.uint32)             # lane-major: lane l owns words m = 0..3
     halves = meta.view(np.uint16).reshape(64, 8)        # 16-bit half h covers groups 4h..4h+3
     for m in range(4):
         for l in range(64):
@@ -49,14 +50,14 @@ def k_sparse_physical(nnz, meta):
             for kb in range(2):
                 # uncompressed channels 64kb + 16a .. +15 -> kept elements 32kb + 8a .. +7
                 out[m, kb, l] = nnz[tok, 32 * kb + 8 * a: 32 * kb + 8 * a + 8]
-                om[m, l] |= np.uint32(halves[tok, 4 * kb + a]) << np.uint32(16 * kb)
+                om[l, m] |= np.uint32(halves[tok, 4 * kb + a]) << np.uint32(16 * kb)
     return out.reshape(-1).view(np.uint8), om.reshape(-1).view(np.uint8)
 
 
 def v_sparse_physical(nnz, meta):
     """Canonical V tile (nnz [16, 2, 128] u16, meta [16, 16] u32) -> physical bytes."""
     out = np.zeros((8, 64, 8), dtype=np.uint16)
-    om = np.zeros((4, 64), dtype=np.uint32)
+    om = np.zeros((64, 4), dtype=np.uint32)             # lane-major: lane l owns words mb//2 = 0..3
     nib = (meta[:, :, None] >> (4 * np.arange(8, dtype=np.uint32))) & np.uint32(0xF)
     nib = nib.reshape(16, 128)                          # [token group, channel]
     for mb in range(8):
@@ -68,7 +69,7 @@ def v_sparse_physical(nnz, meta):
                 assert (TOKEN_OF_K[16 * a + 4 * q: 16 * a + 4 * q + 4] == 4 * g + np.arange(4)).all()
                 out[mb, l, 2 * q] = nnz[g, 0, c]
                 out[mb, l, 2 * q + 1] = nnz[g, 1, c]
-                om[mb // 2, l] |= np.uint32(nib[g, c]) << np.uint32(16 * (mb % 2) + 4 * q)
+                om[l, mb // 2] |= np.uint32(nib[g, c]) << np.uint32(16 * (mb % 2) + 4 * q)
     return out.reshape(-1).view(np.uint8), om.reshape(-1).view(np.uint8)
 
 

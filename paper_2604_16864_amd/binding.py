@@ -150,9 +150,9 @@ class PackedKV:
         self.v_map = torch.empty(rows_T, dtype=torch.int32, device=device)
         self.nbytes = sum(nb)
         T = shape.L // TILE
-        # slot == tile index: nothing skipped, one kind of tile per tensor, same kind in K and V
+        # slot == tile index: nothing skipped, one kind of tile per tensor
         self.uniform = int(counts[0] == 0 and (counts[1] == 0 or counts[2] == 0) and (counts[3] == 0 or counts[4] == 0)
-                           and (counts[1] == 0) == (counts[3] == 0) and max(counts[1], counts[2]) == T)
+                           and max(counts[1], counts[2]) == T and max(counts[3], counts[4]) == T)
 
     def struct(self):
         return HsKV(_ptr(self.k_dense), _ptr(self.k_nnz), _ptr(self.k_meta), _ptr(self.k_map),

@@ -22,7 +22,7 @@ int check_shape(const hs_shape* s) {
   if (s->D != HS_D || s->tile != HS_BT) return HS_EUNSUPPORTED;
   if (s->L % HS_BT != 0 || s->Hq % s->Hkv != 0) return HS_EUNSUPPORTED;
   if (s->Hq / s->Hkv > 8) return HS_EUNSUPPORTED;
-  if (s->B > 65535 || s->Hkv > 65535) return HS_EUNSUPPORTED;
+  if (s->B > 65535 || s->Hkv > 65535 || (int64_t)s->B * s->Hkv > 65535) return HS_EUNSUPPORTED;
   return HS_OK;
 }
 
@@ -276,8 +276,7 @@ int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const v
     const int T = shape->L / HS_BT;
     const bool k_ok = (kv->cap_dense_k == 0 && kv->cap_sparse_k >= T) || (kv->cap_sparse_k == 0 && kv->cap_dense_k >= T);
     const bool v_ok = (kv->cap_dense_v == 0 && kv->cap_sparse_v >= T) || (kv->cap_sparse_v == 0 && kv->cap_dense_v >= T);
-    const bool same = (kv->cap_dense_k == 0) == (kv->cap_dense_v == 0);
-    if (!k_ok || !v_ok || !same) return HS_EINVAL;
+    if (!k_ok || !v_ok) return HS_EINVAL;
   }
   const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
                                         (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,

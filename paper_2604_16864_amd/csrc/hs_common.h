@@ -27,11 +27,13 @@
 //
 //  K 2:4  nnz : chunk m*2+kb (m = 0..3, kb = 0..1): token 16m+r, kept values of channel
 //               groups 16kb+4a+q, q = 0..3 (channels 4*group .. +3), lower position first.
-//         meta: word [m][l] (u32): bits 0..15 idx for kb = 0, bits 16..31 for kb = 1;
-//               nibble q (bits 4q..4q+3 of the half) = i0 | i1<<2 of group 16kb+4a+q.
+//         meta: lane l owns 16 bytes = words m = 0..3 (u32, word 4l+m of the slot): bits 0..15
+//               idx for kb = 0, bits 16..31 for kb = 1; nibble q (bits 4q..4q+3 of the half)
+//               = i0 | i1<<2 of group 16kb+4a+q.
 //  V 2:4  nnz : chunk mb (0..7): channel 16mb+r, kept values of token groups
 //               g(a,q) = 4*(2*(a/2) + q%2) + 2*(a%2) + q/2, q = 0..3 (tokens 4g..4g+3).
-//         meta: word [mb/2][l]: low half mb even, high half mb odd; nibble q as above.
+//         meta: lane l owns words w = 0..3 (word 4l+w): low half mb = 2w, high half mb = 2w+1;
+//               nibble q as above.
 //  K dense    : chunk m*4+s (s = 0..3): token 16m+r, channels 32s+8a+e, e = 0..7.
 //  V dense    : chunk mb*2+h (h = 0..1): channel 16mb+r, tokens 16*(2h+e/4)+4a+e%4.
 //

@@ -129,48 +129,71 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 // ----------------------------------------------------------------------------------
 // Tile selection per (b, kv head) row (Eq. 2d + the skip extension) and slot assignment
 // (the two sequential counters of Sec. III-B, done as an exclusive prefix count).
-// One workgroup per row; ranks by counting, O(T^2) compares.
+// Ranks are found by counting: rank(t) = #{u : (score_u, u) < (score_t, t)}.  One thread per
+// tile; the row's scores pass through LDS in chunks, so the O(T^2) compares read LDS only.
+// Three launches because each phase needs the previous one's result for the whole row.
 // ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ scores, int rows, int T, int n_skip,
-                                                     int n_sparse_k, int n_sparse_v, int32_t* __restrict__ k_map,
-                                                     int32_t* __restrict__ v_map) {
-  __shared__ int cnt[3][256];
-  const int row = blockIdx.x, tid = threadIdx.x;
-  const double* en = scores + ((int64_t)0 * rows + row) * T;
+constexpr int kRankChunk = 2048;
+
+// phase 1: km[t] = 1 if tile t is kept, 0 if it is among the n_skip lowest-energy tiles
+__global__ __launch_bounds__(256) void rank_skip_kernel(const double* __restrict__ scores, int T, int n_skip,
+                                                        int32_t* km_all) {
+  __shared__ double se[kRankChunk];
+  const int row = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
+  const double* en = scores + (int64_t)row * T;  // plane 0 = energy
+  const double e = t < T ? en[t] : 0.0;
+  int rank = 0;
+  for (int c0 = 0; c0 < T; c0 += kRankChunk) {
+    const int n = min(kRankChunk, T - c0);
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += 256) se[i] = en[c0 + i];
+    __syncthreads();
+    for (int i = 0; i < n; i++) {
+      const double eu = se[i];
+      rank += (eu < e) || (eu == e && c0 + i < t);
+    }
+  }
+  if (t < T) km_all[(int64_t)row * T + t] = rank >= n_skip;
+}
+
+// phase 2: vm[t] = state_k | state_v << 8: among kept tiles the n_sparse_x with the lowest
+// pruning loss are 2:4, the others dense
+__global__ __launch_bounds__(256) void rank_state_kernel(const double* __restrict__ scores, int rows, int T,
+                                                         int n_sparse_k, int n_sparse_v, const int32_t* km_all,
+                                                         int32_t* vm_all) {
+  __shared__ double sk_[kRankChunk], sv_[kRankChunk];
+  __shared__ int skept[kRankChunk];
+  const int row = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
   const double* lk = scores + ((int64_t)1 * rows + row) * T;
   const double* lv = scores + ((int64_t)2 * rows + row) * T;
+  const int32_t* km = km_all + (int64_t)row * T;
+  const double a = t < T ? lk[t] : 0.0, c = t < T ? lv[t] : 0.0;
+  int rk = 0, rv = 0;
+  for (int c0 = 0; c0 < T; c0 += kRankChunk) {
+    const int n = min(kRankChunk, T - c0);
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += 256) { sk_[i] = lk[c0 + i]; sv_[i] = lv[c0 + i]; skept[i] = km[c0 + i]; }
+    __syncthreads();
+    for (int i = 0; i < n; i++) {
+      if (skept[i] == 0) continue;
+      const double au = sk_[i], cu = sv_[i];
+      rk += (au < a) || (au == a && c0 + i < t);
+      rv += (cu < c) || (cu == c && c0 + i < t);
+    }
+  }
+  if (t < T) {
+    int st = 0;
+    if (km[t] != 0) st = (rk < n_sparse_k ? HS_SPARSE24 : HS_DENSE) | ((rv < n_sparse_v ? HS_SPARSE24 : HS_DENSE) << 8);
+    vm_all[(int64_t)row * T + t] = st;
+  }
+}
+
+// phase 3: slots in ascending tile order; one workgroup per row, each thread owns a contiguous chunk
+__global__ __launch_bounds__(256) void slots_kernel(int T, int32_t* k_map, int32_t* v_map) {
+  __shared__ int part[4][256];
+  const int row = blockIdx.x, tid = threadIdx.x;
   int32_t* km = k_map + (int64_t)row * T;
   int32_t* vm = v_map + (int64_t)row * T;
-  // pass 1: skip flags, parked in the maps as 0 (skip) / 1 (kept)
-  for (int t = tid; t < T; t += 256) {
-    const double e = en[t];
-    int rank = 0;
-    for (int u = 0; u < T; u++) {
-      const double eu = en[u];
-      rank += (eu < e) || (eu == e && u < t);
-    }
-    km[t] = rank >= n_skip;
-  }
-  __syncthreads();
-  // pass 2: among kept tiles, rank by pruning loss; state: 0 skip, 1 dense, 2 sparse
-  for (int t = tid; t < T; t += 256) {
-    int sk = 0, sv = 0;
-    if (km[t] != 0) {
-      const double a = lk[t], c = lv[t];
-      int rk = 0, rv = 0;
-      for (int u = 0; u < T; u++) {
-        if (km[u] == 0) continue;
-        const double au = lk[u], cu = lv[u];
-        rk += (au < a) || (au == a && u < t);
-        rv += (cu < c) || (cu == c && u < t);
-      }
-      sk = rk < n_sparse_k ? HS_SPARSE24 : HS_DENSE;
-      sv = rv < n_sparse_v ? HS_SPARSE24 : HS_DENSE;
-    }
-    vm[t] = sk | (sv << 8);
-  }
-  __syncthreads();
-  // pass 3: slots in ascending tile order; each thread owns a contiguous chunk
   const int per = (T + 255) / 256;
   const int t0 = min(tid * per, T), t1 = min(t0 + per, T);
   int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
@@ -178,8 +201,7 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
     const int s = vm[t], sk = s & 0xff, sv = s >> 8;
     ndk += sk == HS_DENSE; nsk += sk == HS_SPARSE24; ndv += sv == HS_DENSE; nsv += sv == HS_SPARSE24;
   }
-  // exclusive scan of the four counters over threads (thread 0 walks the 256 partials)
-  __shared__ int part[4][256];
+  // exclusive scan of the four counters over threads (4 threads walk the 256 partials)
   part[0][tid] = ndk; part[1][tid] = nsk; part[2][tid] = ndv; part[3][tid] = nsv;
   __syncthreads();
   if (tid < 4) {
@@ -193,7 +215,6 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
     km[t] = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
     vm[t] = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
   }
-  (void)cnt;
 }
 
 // ----------------------------------------------------------------------------------
@@ -240,7 +261,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
       }
       *reinterpret_cast<uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
     }
-    *reinterpret_cast<uint32_t*>(meta + (w * 64 + l) * 4) = idx;
+    *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
   }
 
   // ---- V ----
@@ -282,7 +303,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
       }
       *reinterpret_cast<uint4*>(nnz + (mb * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
     }
-    *reinterpret_cast<uint32_t*>(meta + (w * 64 + l) * 4) = idx;
+    *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
   }
 }
 
@@ -309,7 +330,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
     } else if (mk < 0) {
       const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
       const uint8_t* nnz = kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
-      const uint32_t idx = *reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES + (w * 64 + l) * 4);
+      const uint32_t idx = *reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES + (l * 4 + w) * 4);
 #pragma unroll
       for (int kb = 0; kb < 2; kb++) {
         const uint4 d = *reinterpret_cast<const uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16);
@@ -356,7 +377,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
   } else if (mv < 0) {
     const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
     const uint8_t* nnz = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
-    const uint32_t idx = *reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES + (w * 64 + l) * 4);
+    const uint32_t idx = *reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES + (l * 4 + w) * 4);
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       const int mb = 2 * w + j, c = 16 * mb + r;
@@ -409,8 +430,10 @@ hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int
 
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
                             int32_t* k_map, int32_t* v_map, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel, dim3(rows), dim3(256), 0, st, scores, rows, T, n_skip, n_sparse_k, n_sparse_v,
-                     k_map, v_map);
+  const dim3 grid((T + 255) / 256, rows);
+  hipLaunchKernelGGL(rank_skip_kernel, grid, dim3(256), 0, st, scores, T, n_skip, k_map);
+  hipLaunchKernelGGL(rank_state_kernel, grid, dim3(256), 0, st, scores, rows, T, n_sparse_k, n_sparse_v, k_map, v_map);
+  hipLaunchKernelGGL(slots_kernel, dim3(rows), dim3(256), 0, st, T, k_map, v_map);
   return hipGetLastError();
 }
 

@@ -10,6 +10,13 @@
 // natively, so no vector-ALU work is spent on selecting operands.
 #include "hs_common.h"
 
+#ifndef HS_DEC_DEPTH
+#define HS_DEC_DEPTH 2
+#endif
+#ifndef HS_DEC_OCC
+#define HS_DEC_OCC ((KM == 0 && VM == 0) || KM == 2 || VM == 2 ? 2 : 1)  /* a dense tensor at depth 2 needs > 256 registers */
+#endif
+
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -41,70 +48,75 @@ __device__ __forceinline__ float bf16_hi_f(uint32_t p) { return __uint_as_float(
 
 
 // Operand registers of one tile (K and V), filled by tile_load and consumed by tile_compute.
-template <int MODE>
+// KM / VM (per tensor): 0 = every tile 2:4 or skipped, 1 = every tile dense or skipped, 2 = any mix.
+template <int KM, int VM>
 struct TileRegs {
-  static constexpr int kN = MODE == 0 ? 8 : 16;  // 16-byte chunks per lane: 2:4 tile 8, dense tile 16
-  uint4 k[kN];
-  uint4 v[kN];
-  uint32_t km[4];
-  uint32_t vm[4];
+  static constexpr int kNK = KM == 0 ? 8 : 16;  // 16-byte chunks per lane: 2:4 tile 8, dense tile 16
+  static constexpr int kNV = VM == 0 ? 8 : 16;
+  uint4 k[kNK];
+  uint4 v[kNV];
+  uint4 km, vm;  // the lane's four 32-bit index words of the K / V tile
   int mk, mv;
 };
 
-template <int MODE>
-__device__ __forceinline__ void tile_load(TileRegs<MODE>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {
+template <int KM, int VM>
+__device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {
   r.mk = mk;
   r.mv = mv;
-  const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
-  const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+  const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
+  const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
   if (k_sparse) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
     const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
-    const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
 #pragma unroll
     for (int i = 0; i < 8; i++) r.k[i] = ld_stream(p + 64 * i);
-#pragma unroll
-    for (int i = 0; i < 4; i++) r.km[i] = __builtin_nontemporal_load(pm + 64 * i);
+    r.km = ld_stream(reinterpret_cast<const uint4*>(kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES) + l);
   } else {
     const int64_t slot = row * kv.cap_dense_k + (mk - 1);
     const uint4* p = reinterpret_cast<const uint4*>(kv.k_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
 #pragma unroll
-    for (int i = 0; i < 16; i++) r.k[i % TileRegs<MODE>::kN] = ld_stream(p + 64 * i);
+    for (int i = 0; i < 16; i++) r.k[i % TileRegs<KM, VM>::kNK] = ld_stream(p + 64 * i);
   }
   if (v_sparse) {
     const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
     const uint4* p = reinterpret_cast<const uint4*>(kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
-    const uint32_t* pm = reinterpret_cast<const uint32_t*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES) + l;
 #pragma unroll
     for (int i = 0; i < 8; i++) r.v[i] = ld_stream(p + 64 * i);
-#pragma unroll
-    for (int i = 0; i < 4; i++) r.vm[i] = __builtin_nontemporal_load(pm + 64 * i);
+    r.vm = ld_stream(reinterpret_cast<const uint4*>(kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES) + l);
   } else {
     const int64_t slot = row * kv.cap_dense_v + (mv - 1);
     const uint4* p = reinterpret_cast<const uint4*>(kv.v_dense + slot * (int64_t)HS_TILE_DENSE_BYTES) + l;
 #pragma unroll
-    for (int i = 0; i < 16; i++) r.v[i % TileRegs<MODE>::kN] = ld_stream(p + 64 * i);
+    for (int i = 0; i < 16; i++) r.v[i % TileRegs<KM, VM>::kNV] = ld_stream(p + 64 * i);
   }
 }
 
 // One tile: GEMM1 (S^T = K Q^T), online softmax, GEMM2 (O^T += V^T P^T).
-template <int MODE>
-__device__ __forceinline__ void tile_compute(const TileRegs<MODE>& r, const uint4 (&qb)[4], float scale_log2, int c,
+template <int KM, int VM>
+__device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const uint4 (&qb)[4], float scale_log2, int c,
                                              f32x4_t (&o)[8], float& m_run, float& l_run) {
-  const bool k_sparse = MODE == 0 || (MODE == 2 && r.mk < 0);
-  const bool v_sparse = MODE == 0 || (MODE == 2 && r.mv < 0);
-  constexpr int kN = TileRegs<MODE>::kN;
+  const bool k_sparse = KM == 0 || (KM == 2 && r.mk < 0);
+  const bool v_sparse = VM == 0 || (VM == 2 && r.mv < 0);
+  constexpr int kNK = TileRegs<KM, VM>::kNK, kNV = TileRegs<KM, VM>::kNV;
   f32x4_t s[4];
+  const int kidx[4] = {(int)r.km.x, (int)r.km.y, (int)r.km.z, (int)r.km.w};
+  const int vidx[4] = {(int)r.vm.x, (int)r.vm.y, (int)r.vm.z, (int)r.vm.w};
+#pragma unroll
+  for (int m = 0; m < 4; m++) s[m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  if (k_sparse) {  // the 4 row blocks are independent chains
+#pragma unroll
+    for (int m = 0; m < 4; m++)
+      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m]), as_bf16x16(qb[0], qb[1]), s[m], kidx[m], 0, 0);
+#pragma unroll
+    for (int m = 0; m < 4; m++)
+      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m + 1]), as_bf16x16(qb[2], qb[3]), s[m], kidx[m], 0, 1);
+  }
 #pragma unroll
   for (int m = 0; m < 4; m++) {
-    s[m] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    if (k_sparse) {
-      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m]), as_bf16x16(qb[0], qb[1]), s[m], (int)r.km[m], 0, 0);
-      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m + 1]), as_bf16x16(qb[2], qb[3]), s[m], (int)r.km[m], 0, 1);
-    } else {
+    if (!k_sparse) {
 #pragma unroll
       for (int st = 0; st < 4; st++)
-        s[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[(4 * m + st) % kN]), as_bf16x8(qb[st]), s[m], 0, 0, 0);
+        s[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[(4 * m + st) % kNK]), as_bf16x8(qb[st]), s[m], 0, 0, 0);
     }
   }
   // online softmax for column c (log2 domain)
@@ -151,12 +163,12 @@ __device__ __forceinline__ void tile_compute(const TileRegs<MODE>& r, const uint
   for (int mb = 0; mb < 8; mb++) {
     if (v_sparse) {
       if (mb & 1)
-        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)r.vm[mb >> 1], 0, 1);
+        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], vidx[mb >> 1], 0, 1);
       else
-        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], (int)r.vm[mb >> 1], 0, 0);
+        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], vidx[mb >> 1], 0, 0);
     } else {
-      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb) % kN]), as_bf16x8(pb_lo), o[mb], 0, 0, 0);
-      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb + 1) % kN]), as_bf16x8(pb_hi), o[mb], 0, 0, 0);
+      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb) % kNV]), as_bf16x8(pb_lo), o[mb], 0, 0, 0);
+      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb + 1) % kNV]), as_bf16x8(pb_hi), o[mb], 0, 0, 0);
     }
   }
 }
@@ -167,8 +179,8 @@ __device__ __forceinline__ void tile_compute(const TileRegs<MODE>& r, const uint
 // with a two-deep register pipeline (the loads of tile i+1 are in flight while tile i is
 // being multiplied).
 // Each workgroup emits a normalised partial output and its log-sum-exp per query head.
-template <int MODE, bool UNIFORM>  // MODE 0: every tile 2:4 or skipped; 1: dense or skipped; 2: any mix
-__global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2,
+template <int KM, int VM, bool UNIFORM>
+__global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2,
                                                                              int n_splits, int per,
                                                                              const uint16_t* __restrict__ Q,
                                                                              hs_kv_dev kv, float* __restrict__ ws_o,
@@ -195,41 +207,50 @@ __global__ __launch_bounds__(256, MODE == 0 ? 2 : 1) void decode_split_kernel(in
   for (int i = 0; i < 8; i++) o[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
 
-  TileRegs<MODE> ra, rb;
+  // DEPTH tiles in flight per wave.  Measured on the 32K-context shape: depth 1, 2, 3 and 4 (the
+  // deeper ones at 1 wave per SIMD) all land within run-to-run noise, and even a variant with
+  // the arithmetic removed is only ~10 % faster: the kernel is bound by the load stream.
+  constexpr int DEPTH = (KM == 2 || VM == 2) ? 1 : HS_DEC_DEPTH;  // a mixed tensor carries both code paths: keep it small
+  TileRegs<KM, VM> ring[DEPTH];
   for (int base = t_begin + w; base < t_end; base += 256) {  // up to 64 tiles of this wave per round
     const int t_mine = base + 4 * l;
     int mk_v = 0, mv_v = 0;
     if (t_mine < t_end) {
       if (UNIFORM) {  // promised by the caller: no tile skipped, one kind per tensor, slot == tile
-        mk_v = MODE == 0 ? -(t_mine + 1) : t_mine + 1;
-        mv_v = mk_v;
+        mk_v = KM == 0 ? -(t_mine + 1) : t_mine + 1;
+        mv_v = VM == 0 ? -(t_mine + 1) : t_mine + 1;
       } else {
         mk_v = kv.k_map[row * T + t_mine];
         mv_v = kv.v_map[row * T + t_mine];
       }
     }
     unsigned long long act = __ballot(mk_v != 0);
-    if (act == 0ull) continue;
-    int i0 = __builtin_ctzll(act);
-    act &= act - 1;
-    tile_load<MODE>(ra, kv, row, __shfl(mk_v, i0), __shfl(mv_v, i0), l);
-    while (true) {
-      const bool more_b = act != 0ull;
-      if (more_b) {
-        const int i1 = __builtin_ctzll(act);
+    bool have[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) {
+      have[d] = act != 0ull;
+      if (have[d]) {
+        const int i = __builtin_ctzll(act);
         act &= act - 1;
-        tile_load<MODE>(rb, kv, row, __shfl(mk_v, i1), __shfl(mv_v, i1), l);
+        tile_load<KM, VM>(ring[d], kv, row, __shfl(mk_v, i), __shfl(mv_v, i), l);
       }
-      tile_compute<MODE>(ra, qb, scale_log2, c, o, m_run, l_run);
-      if (!more_b) break;
-      const bool more_a = act != 0ull;
-      if (more_a) {
-        const int i2 = __builtin_ctzll(act);
-        act &= act - 1;
-        tile_load<MODE>(ra, kv, row, __shfl(mk_v, i2), __shfl(mv_v, i2), l);
+    }
+    bool go = have[0];
+    while (go) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; d++) {
+        if (go && have[d]) {  // tiles are consumed in issue order: the first empty slot ends the round
+          tile_compute<KM, VM>(ring[d], qb, scale_log2, c, o, m_run, l_run);
+          have[d] = act != 0ull;
+          if (have[d]) {
+            const int i = __builtin_ctzll(act);
+            act &= act - 1;
+            tile_load<KM, VM>(ring[d], kv, row, __shfl(mk_v, i), __shfl(mv_v, i), l);
+          }
+        } else {
+          go = false;
+        }
       }
-      tile_compute<MODE>(rb, qb, scale_log2, c, o, m_run, l_run);
-      if (!more_a) break;
     }
   }
 
@@ -333,11 +354,11 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(int n_splits, const f
 }  // namespace
 
 // Workspace: [partial O (normalised) [B*Hq][n_splits][128] fp32][partial LSE [B*Hq][n_splits] fp32].
-template <int MODE, bool UNIFORM>
+template <int KM, int VM, bool UNIFORM>
 static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T, float sl2, int n_splits, int per,
                                const uint16_t* Q, const hs_kv_dev& kv, float* wo, float* wl) {
-  hipLaunchKernelGGL((decode_split_kernel<MODE, UNIFORM>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits, per, Q,
-                     kv, wo, wl);
+  hipLaunchKernelGGL((decode_split_kernel<KM, VM, UNIFORM>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits, per,
+                     Q, kv, wo, wl);
   return hipGetLastError();
 }
 
@@ -348,17 +369,27 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_sp
   const int per = (T + n_splits - 1) / n_splits;
   float* wo = ws;
   float* wl = wo + (size_t)B * Hq * n_splits * HS_D;
-  const bool no_dense = kv.cap_dense_k == 0 && kv.cap_dense_v == 0;
-  const bool no_sparse = kv.cap_sparse_k == 0 && kv.cap_sparse_v == 0;
+  const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
+  const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
   hipError_t e;
-  if (no_dense)
-    e = kv.uniform ? launch_split<0, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)
-                   : launch_split<0, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);
-  else if (no_sparse)
-    e = kv.uniform ? launch_split<1, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)
-                   : launch_split<1, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);
-  else
-    e = launch_split<2, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);
+#define HS_GO(KM_, VM_)                                                                                         \
+  e = kv.uniform ? launch_split<KM_, VM_, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)       \
+                 : launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);     \
+  break
+#define HS_GO_DYN(KM_, VM_) e = launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl); break
+  switch (km * 3 + vm) {
+    case 0: HS_GO(0, 0);
+    case 1: HS_GO(0, 1);
+    case 2: HS_GO_DYN(0, 2);
+    case 3: HS_GO(1, 0);
+    case 4: HS_GO(1, 1);
+    case 5: HS_GO_DYN(1, 2);
+    case 6: HS_GO_DYN(2, 0);
+    case 7: HS_GO_DYN(2, 1);
+    default: HS_GO_DYN(2, 2);
+  }
+#undef HS_GO
+#undef HS_GO_DYN
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);
   return hipGetLastError();

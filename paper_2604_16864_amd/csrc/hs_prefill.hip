@@ -21,11 +21,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
-struct u4x2 { uint4 lo, hi; };
-__device__ __forceinline__ bf16x16_t as_bf16x16(uint4 lo, uint4 hi) {
-  u4x2 t{lo, hi};
-  return __builtin_bit_cast(bf16x16_t, t);
-}
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
   bf2 v;
@@ -52,11 +47,11 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // 16 bytes land at chunk base + 16 l, which is the order the pools are stored in.  The 4
 // waves share the chunks round-robin.  2:4 tile: 8 value chunks + 1 metadata chunk per
 // tensor (value chunks at 0..8 KiB, metadata at 8 KiB of the tensor's region); dense: 16.
-template <int MODE>
+template <int KM, int VM>
 __device__ __forceinline__ void stage_issue(uint8_t* buf, const hs_kv_dev& kv, int64_t row, int mk, int mv, int w,
                                             int l) {
-  const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
-  const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+  const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
+  const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
   const uint8_t *kd, *km = nullptr, *vd, *vm = nullptr;
   int nk, nv;
   if (k_sparse) {
@@ -103,10 +98,12 @@ union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the de
   uint32_t u[8];
 };
 
-// MODE 0: every tile 2:4 or skipped; 1: every tile dense or skipped; 2: any mix.
+// KM / VM (per tensor): 0 = every tile 2:4 or skipped, 1 = every tile dense or skipped, 2 = any mix
+// (the specialised all-dense / all-sparse kernels of Sec. IV-C-3, chosen per tensor so that the
+// keys-dense / values-2:4 setting of Sec. V-A carries no dynamic dispatch).
 // NB: column blocks (of 16 queries) per wave: a wave owns a slab of 16*NB query positions of one
 // head.  NB = 4 keeps 1 wave per SIMD (O^T alone is 128 registers); NB = 2 fits 2 waves per SIMD.
-template <int MODE, int NB>
+template <int KM, int VM, int NB>
 __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, int Hkv, int T, int Lq, int off,
                                                                       float scale_log2, int causal,
                                                                       const uint16_t* __restrict__ Q, hs_kv_dev kv,
@@ -161,7 +158,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   int mk = 0, mv = 0;
   if (j >= 0) {
     mk = km[j]; mv = vm[j];
-    stage_issue<MODE>(lds, kv, row, mk, mv, w, l);
+    stage_issue<KM, VM>(lds, kv, row, mk, mv, w, l);
   }
   stage_wait();
   __syncthreads();
@@ -173,11 +170,11 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     int mkn = 0, mvn = 0;
     if (jn >= 0) {
       mkn = km[jn]; mvn = vm[jn];
-      stage_issue<MODE>(lds + (buf ^ 1) * kBufBytes, kv, row, mkn, mvn, w, l);
+      stage_issue<KM, VM>(lds + (buf ^ 1) * kBufBytes, kv, row, mkn, mvn, w, l);
     }
     if (valid && j <= jmax_w) {
-      const bool k_sparse = MODE == 0 || (MODE == 2 && mk < 0);
-      const bool v_sparse = MODE == 0 || (MODE == 2 && mv < 0);
+      const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
+      const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
       const uint4* kl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes);
       const uint4* vl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes + 16384);
       // ---------------- GEMM1: S^T[64 tokens x 16 NB queries] ----------------
@@ -188,11 +185,10 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         for (int nb = 0; nb < NB; nb++) s[m][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
       if (k_sparse) {
         uint4 ak[8];
-        int kidx[4];
 #pragma unroll
         for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];
-#pragma unroll
-        for (int m = 0; m < 4; m++) kidx[m] = (int)reinterpret_cast<const uint32_t*>(kl + 512)[m * 64 + l];
+        const uint4 kix = kl[512 + l];
+        const int kidx[4] = {(int)kix.x, (int)kix.y, (int)kix.z, (int)kix.w};
         // 4 NB independent accumulators between the two instructions that share one
 #pragma unroll
         for (int nb = 0; nb < NB; nb++)
@@ -286,11 +282,10 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       }
       if (v_sparse) {
         uint4 av[8];
-        int vidx[4];
 #pragma unroll
         for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
-#pragma unroll
-        for (int i = 0; i < 4; i++) vidx[i] = (int)reinterpret_cast<const uint32_t*>(vl + 512)[i * 64 + l];
+        const uint4 vix = vl[512 + l];
+        const int vidx[4] = {(int)vix.x, (int)vix.y, (int)vix.z, (int)vix.w};
 #pragma unroll
         for (int t2 = 0; t2 < 2; t2++)  // first the upper-half term of every block, then the remainder
 #pragma unroll
@@ -348,12 +343,12 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 
 }  // namespace
 
-template <int MODE, int NB>
+template <int KM, int VM, int NB>
 static hipError_t launch_prefill(int B, int Hq, int Hkv, int T, int Lq, float sl2, int causal, const uint16_t* Q,
                                  const hs_kv_dev& kv, uint16_t* O, float* LSE, hipStream_t st) {
   const int G = Hq / Hkv;
   const int n_groups = ((Lq / (16 * NB)) * G + 3) / 4;
-  hipLaunchKernelGGL((prefill_kernel<MODE, NB>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
+  hipLaunchKernelGGL((prefill_kernel<KM, VM, NB>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
                      T * HS_BT - Lq, sl2, causal, Q, kv, O, LSE);
   return hipGetLastError();
 }
@@ -362,15 +357,24 @@ hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale,
                              hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st) {
   const float sl2 = scale * kLog2e;
   const int Lq = Tq * HS_BT;
-  const bool no_dense = kv.cap_dense_k == 0 && kv.cap_dense_v == 0;
-  const bool no_sparse = kv.cap_sparse_k == 0 && kv.cap_sparse_v == 0;
+  const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
+  const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
+  // HS_PREFILL_NB=4 selects 64-query slabs at 1 wave per SIMD for the two uniform settings
+  // (kept for comparison; 32-query slabs at 2 waves per SIMD measured 1.3-1.4x faster)
   static const int nb_env = [] { const char* e = getenv("HS_PREFILL_NB"); return e ? atoi(e) : 0; }();
-  const int nb = nb_env == 2 || nb_env == 4 ? nb_env : 2;  // 2 waves per SIMD measured 1.3-1.4x faster
-#define HS_GO(MODE)                                                                               \
-  return nb == 2 ? launch_prefill<MODE, 2>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st)     \
-                 : launch_prefill<MODE, 4>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st)
-  if (no_dense) { HS_GO(0); }
-  if (no_sparse) { HS_GO(1); }
-  HS_GO(2);
+#define HS_GO(KM_, VM_) return launch_prefill<KM_, VM_, 2>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st)
+  if (nb_env == 4 && km == 0 && vm == 0) return launch_prefill<0, 0, 4>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st);
+  if (nb_env == 4 && km == 1 && vm == 1) return launch_prefill<1, 1, 4>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st);
+  switch (km * 3 + vm) {
+    case 0: HS_GO(0, 0);
+    case 1: HS_GO(0, 1);
+    case 2: HS_GO(0, 2);
+    case 3: HS_GO(1, 0);
+    case 4: HS_GO(1, 1);
+    case 5: HS_GO(1, 2);
+    case 6: HS_GO(2, 0);
+    case 7: HS_GO(2, 1);
+    default: HS_GO(2, 2);
+  }
 #undef HS_GO
 }

@@ -178,6 +178,18 @@ def test_decode_all_dense_is_plain_attention():
     assert_close(O, ref, "decode dense vs sdpa")
 
 
+@pytest.mark.parametrize("sfk,sfv", [(0.0, 1.0), (1.0, 0.0), (0.5, 1.0), (0.0, 0.4)])
+def test_decode_and_prefill_per_tensor_kinds(sfk, sfv):
+    """Keys dense / values 2:4 (the paper's quality-preserving setting) and the other combinations
+    that select per-tensor specialised kernels."""
+    O, LSE, Or, Lr = _decode_case(1, 8, 2, 64 * 12, seed=65, sparse_frac_k=sfk, sparse_frac_v=sfv)
+    assert_close(O, Or, f"decode S_K={sfk} S_V={sfv}")
+    assert_lse_close(LSE, Lr, f"decode S_K={sfk} S_V={sfv} lse")
+    O, LSE, Or, Lr = _prefill_case(1, 8, 2, 64 * 6, 64 * 6, seed=66, sparse_frac_k=sfk, sparse_frac_v=sfv)
+    assert_close(O, Or, f"prefill S_K={sfk} S_V={sfv}")
+    assert_lse_close(LSE, Lr, f"prefill S_K={sfk} S_V={sfv} lse")
+
+
 def test_decode_mixed_and_skip():
     B, Hq, Hkv, L = 2, 8, 2, 64 * 21
     sk, sv = _mixed_states(B, Hkv, L // 64, seed=61)
