@@ -63,6 +63,8 @@ template <int KM, int VM>
 __device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {
   r.mk = mk;
   r.mv = mv;
+  r.km = make_uint4(0, 0, 0, 0);  // only 2:4 tiles carry index words
+  r.vm = make_uint4(0, 0, 0, 0);
   const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
   const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
   if (k_sparse) {
@@ -186,7 +188,8 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
                                                                              hs_kv_dev kv, float* __restrict__ ws_o,
                                                                              float* __restrict__ ws_l) {
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, c = l & 15;
+  const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, scalar: branches on it stay scalar
   const int G = Hq / Hkv;
   const int64_t row = (int64_t)b * Hkv + hkv;
   const int t_begin = split * per, t_end = min(T, t_begin + per);
@@ -224,6 +227,10 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
         mv_v = kv.v_map[row * T + t_mine];
       }
     }
+    // Tile kinds must reach the branches below as scalar (wave-uniform) values: matrix
+    // instructions ignore the EXEC mask, so a branch the compiler treats as divergent would run
+    // both the dense and the 2:4 instruction on every tile.  Lane values are therefore read
+    // with v_readlane, never with a lane shuffle.
     unsigned long long act = __ballot(mk_v != 0);
     bool have[DEPTH];
 #pragma unroll
@@ -232,7 +239,7 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
       if (have[d]) {
         const int i = __builtin_ctzll(act);
         act &= act - 1;
-        tile_load<KM, VM>(ring[d], kv, row, __shfl(mk_v, i), __shfl(mv_v, i), l);
+        tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
       }
     }
     bool go = have[0];
@@ -245,7 +252,7 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
           if (have[d]) {
             const int i = __builtin_ctzll(act);
             act &= act - 1;
-            tile_load<KM, VM>(ring[d], kv, row, __shfl(mk_v, i), __shfl(mv_v, i), l);
+            tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
           }
         } else {
           go = false;

@@ -29,12 +29,26 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// p0, p1 -> packed bf16 pair of their upper halves (truncation) and packed bf16 pair of the
-// remainders: hi + lo reproduces p to ~16 bits.
-__device__ __forceinline__ void split_hi_lo(float p0, float p1, uint32_t& hi, uint32_t& lo) {
-  const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
-  hi = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
-  lo = pack_bf16(p0 - __uint_as_float(b0 & 0xffff0000u), p1 - __uint_as_float(b1 & 0xffff0000u));
+// p0, p1 -> hi = packed bf16 pair (round to nearest even) and lo = packed bf16 pair of the
+// remainders p - hi, so that hi + lo reproduces p to ~16 bits.  The remainder is taken with the
+// packed dot product hi . (-1, 0) + p0 (resp. (0, -1) + p1): one instruction per element, and
+// exact, because bf16 products are exact in fp32 and p - hi is representable.
+// The two selector pairs (-1, 0) and (0, -1) are handed in as opaque register values: written
+// as literals the compiler folds the first into the inline constant -1.0, which the
+// instruction does not read as the bf16 pair (-1, 0).
+struct SplitConsts { uint32_t neg_lo, neg_hi; };
+__device__ __forceinline__ SplitConsts split_consts() {
+  SplitConsts c;
+  asm volatile("s_mov_b32 %0, 0x0000bf80\n\ts_mov_b32 %1, 0xbf800000" : "=s"(c.neg_lo), "=s"(c.neg_hi));
+  return c;
+}
+__device__ __forceinline__ void split_hi_lo(float p0, float p1, const SplitConsts& sc, uint32_t& hi, uint32_t& lo) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  hi = pack_bf16(p0, p1);
+  const bf2 h = __builtin_bit_cast(bf2, hi);
+  const float r0 = __builtin_amdgcn_fdot2_f32_bf16(h, __builtin_bit_cast(bf2, sc.neg_lo), p0, false);
+  const float r1 = __builtin_amdgcn_fdot2_f32_bf16(h, __builtin_bit_cast(bf2, sc.neg_hi), p1, false);
+  lo = pack_bf16(r0, r1);
 }
 
 constexpr int kBufBytes = 32768;  // one stage: K region 16 KiB + V region 16 KiB
@@ -111,7 +125,8 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
                                                                       float* __restrict__ LSE) {
   constexpr int QS = 16 * NB;  // query positions per slab
   __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kBufBytes];
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, c = l & 15;
+  const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, scalar: branches on it stay scalar
   const int G = Hq / Hkv;
   const int hkv = blockIdx.y, b = blockIdx.z;
   const int n_slabs = (Lq / QS) * G;
@@ -151,13 +166,16 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 #pragma unroll
     for (int nb = 0; nb < NB; nb++) o[mb][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run[NB], l_run[NB];
+  const SplitConsts sc = split_consts();
 #pragma unroll
   for (int nb = 0; nb < NB; nb++) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
 
+  // Map entries steer branches around matrix instructions, which ignore the EXEC mask: they are
+  // forced into scalar registers so that those branches are scalar too.
   int j = next_active(km, -1, jmax_wg);
   int mk = 0, mv = 0;
   if (j >= 0) {
-    mk = km[j]; mv = vm[j];
+    mk = __builtin_amdgcn_readfirstlane(km[j]); mv = __builtin_amdgcn_readfirstlane(vm[j]);
     stage_issue<KM, VM>(lds, kv, row, mk, mv, w, l);
   }
   stage_wait();
@@ -169,7 +187,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     const int jn = next_active(km, j, jmax_wg);
     int mkn = 0, mvn = 0;
     if (jn >= 0) {
-      mkn = km[jn]; mvn = vm[jn];
+      mkn = __builtin_amdgcn_readfirstlane(km[jn]); mvn = __builtin_amdgcn_readfirstlane(vm[jn]);
       stage_issue<KM, VM>(lds + (buf ^ 1) * kBufBytes, kv, row, mkn, mvn, w, l);
     }
     if (valid && j <= jmax_w) {
@@ -224,31 +242,51 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
             for (int i = 0; i < 4; i++)
               if (16 * m + 4 * a + i > lim + 16 * nb) s[m][nb][i] = -INFINITY;
       }
-      // ---------------- running max, updated lazily ----------------
-      // The reference point m_run of a column only moves when the tile's maximum exceeds it
-      // by more than 2^8; until then P is computed against the stale reference (values up
-      // to 256, harmless in fp32/bf16) and neither O nor l needs rescaling.  The final
+      // ---------------- P = exp2(S*scale - m_run), reference m_run updated lazily ----------------
+      // P is first computed against the current reference of each query column, with no look at
+      // the tile's maximum.  Only if a partial row sum comes out huge (or the column has no
+      // reference yet) is the exact running maximum taken, O and l rescaled, and P recomputed.
+      // With a stale reference P merely holds larger numbers (harmless in fp32 / bf16); the final
       // O / l and LSE = m_run + log2(l) do not depend on which reference was used.
-      float mxl[NB];
-      bool need = false;
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) {
-        float mx = s[0][nb][0];
-#pragma unroll
-        for (int m = 0; m < 4; m++)
-#pragma unroll
-          for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][nb][i]);
-        mxl[nb] = mx * scale_log2;
-        need = need || (mxl[nb] > m_run[nb] + 8.0f);
-      }
-      if (__any(need)) {
+      // P goes through the matrix unit as two bf16 terms (hi + remainder): a single bf16 P alone
+      // costs ~1.3e-3 mean relative error on the output, on top of the bf16 rounding of O itself.
+      B16 ph[NB], pl[NB];
+      float psum[NB];
+      auto softmax_tile = [&]() {
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
-          float mx = mxl[nb];
+          float acc = 0.f;
+          const float mref = m_run[nb] > -INFINITY ? m_run[nb] : 0.f;
+#pragma unroll
+          for (int m = 0; m < 4; m++) {
+            float p[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+              p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
+              acc += p[i];
+            }
+            split_hi_lo(p[0], p[1], sc, ph[nb].u[2 * m], pl[nb].u[2 * m]);
+            split_hi_lo(p[2], p[3], sc, ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
+          }
+          psum[nb] = acc;
+        }
+      };
+      softmax_tile();
+      bool redo = false;
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) redo = redo || !(psum[nb] <= 0x1p40f) || !(m_run[nb] > -INFINITY);
+      if (__any(redo)) {
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+          float mx = s[0][nb][0];
+#pragma unroll
+          for (int m = 0; m < 4; m++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][nb][i]);
+          mx *= scale_log2;
           mx = fmaxf(mx, __shfl_xor(mx, 16));
           mx = fmaxf(mx, __shfl_xor(mx, 32));
-          // a column whose visible part of this tile is empty (can happen in a masked tile when
-          // the slab is shorter than the tile) keeps its reference
+          // a column with nothing visible in this tile keeps its reference
           const float m_new = fmaxf(m_run[nb], mx);
           const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run[nb] - m_new) : 1.0f;
           m_run[nb] = m_new;
@@ -256,30 +294,10 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 #pragma unroll
           for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
         }
+        softmax_tile();
       }
-      // ---------------- P = exp2(S*scale - m) and O^T += V^T P^T ----------------
-      // P goes through the matrix unit as two bf16 terms (upper half of p + remainder): a
-      // single bf16 P alone costs ~1.3e-3 mean relative error on the output, on top of the
-      // bf16 rounding of O itself.
-      B16 ph[NB], pl[NB];
 #pragma unroll
-      for (int nb = 0; nb < NB; nb++) {
-        float psum = 0.f;
-        // a still-unset reference (-inf) only occurs with every score of the column masked
-        const float mref = m_run[nb] > -INFINITY ? m_run[nb] : 0.f;
-#pragma unroll
-        for (int m = 0; m < 4; m++) {
-          float p[4];
-#pragma unroll
-          for (int i = 0; i < 4; i++) {
-            p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
-            psum += p[i];
-          }
-          split_hi_lo(p[0], p[1], ph[nb].u[2 * m], pl[nb].u[2 * m]);
-          split_hi_lo(p[2], p[3], ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
-        }
-        l_run[nb] += psum;
-      }
+      for (int nb = 0; nb < NB; nb++) l_run[nb] += psum[nb];
       if (v_sparse) {
         uint4 av[8];
 #pragma unroll
