@@ -180,6 +180,7 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
   hipStream_t s = (hipStream_t)stream;
   int32_t c[5];
   hipError_t e;
+  int uni_k = 0, uni_v = 0;
   if (policy->state_k != nullptr) {
     // explicit states [host]: walk the tiles in order with one counter per pool (Sec. III-B)
     rc = explicit_counts(shape, policy, c);
@@ -209,10 +210,9 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
       return HS_EINVAL;
     const bool uniform_k = c[1] == 0 || c[2] == 0, uniform_v = c[3] == 0 || c[4] == 0;
     if (c[0] == 0 && uniform_k && uniform_v) {
-      // no ranking needed: every tile in one state
-      e = hs_launch_fill_maps(out->k_map, out->v_map, rows, T, c[2] ? HS_SPARSE24 : HS_DENSE,
-                              c[4] ? HS_SPARSE24 : HS_DENSE, s);
-      if (e != hipSuccess) return hip_fail(e);
+      // no ranking needed: every tile in one state; the pack kernel writes the maps itself
+      uni_k = c[2] ? HS_SPARSE24 : HS_DENSE;
+      uni_v = c[4] ? HS_SPARSE24 : HS_DENSE;
     } else {
       if (workspace == nullptr || ((uintptr_t)workspace & 7u)) return HS_EINVAL;
       if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
@@ -224,7 +224,7 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
     }
   }
   e = hs_launch_pack((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
-                     hs_make_kv_dev(out), s);
+                     hs_make_kv_dev(out), uni_k, uni_v, s);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

@@ -35,17 +35,6 @@ __device__ __forceinline__ void top2_emit(uint32_t mask, uint32_t x0, uint32_t x
 __device__ __forceinline__ double bf16_val(uint32_t bits) { return (double)__uint_as_float(bits << 16); }
 
 // ----------------------------------------------------------------------------------
-// uniform maps: every tile of every row in the same state
-// ----------------------------------------------------------------------------------
-__global__ void fill_maps_kernel(int32_t* k_map, int32_t* v_map, int rows, int T, int state_k, int state_v) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)rows * T) return;
-  const int t = (int)(i % T);
-  k_map[i] = state_k == HS_DENSE ? t + 1 : (state_k == HS_SPARSE24 ? -(t + 1) : 0);
-  v_map[i] = state_v == HS_DENSE ? t + 1 : (state_v == HS_SPARSE24 ? -(t + 1) : 0);
-}
-
-// ----------------------------------------------------------------------------------
 // Staging of one V tile [64 tokens][128 ch] into LDS with coalesced 16-byte loads.
 // ----------------------------------------------------------------------------------
 __device__ __forceinline__ void stage_v_tile(const uint16_t* vt, int64_t tok_stride, uint16_t* lds) {
@@ -220,13 +209,28 @@ __global__ __launch_bounds__(256) void slots_kernel(int T, int32_t* k_map, int32
 // ----------------------------------------------------------------------------------
 // Fused prune + pack (Sec. IV-B): one workgroup per tile, K then V.
 // ----------------------------------------------------------------------------------
+// uni_k / uni_v: 0 = read the tile's map entries (written by an earlier launch); HS_DENSE or
+// HS_SPARSE24 = every tile of that tensor is of this kind, the entry is +-(tile+1) and this
+// kernel writes it (saves the separate map-fill launch of the unranked policies).
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                                                   int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv) {
+                                                   int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv,
+                                                   int uni_k, int uni_v) {
   __shared__ uint16_t vl[HS_BT * kVStride];
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
   const int64_t row = (int64_t)b * Hkv + h;
-  const int mk = kv.k_map[row * T + t], mv = kv.v_map[row * T + t];
+  int mk, mv;
+  if (uni_k != 0) {
+    mk = uni_k == HS_DENSE ? t + 1 : -(t + 1);
+    mv = uni_v == HS_DENSE ? t + 1 : -(t + 1);
+    if (tid == 0) {
+      const_cast<int32_t*>(kv.k_map)[row * T + t] = mk;
+      const_cast<int32_t*>(kv.v_map)[row * T + t] = mv;
+    }
+  } else {
+    mk = kv.k_map[row * T + t];
+    mv = kv.v_map[row * T + t];
+  }
   const uint16_t* kt = K + b * sb + h * sh + (int64_t)t * HS_BT * st;
   const uint16_t* vt = V + b * sb + h * sh + (int64_t)t * HS_BT * st;
   if (mv != 0) stage_v_tile(vt, st, vl);
@@ -414,14 +418,6 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
 
 }  // namespace
 
-hipError_t hs_launch_fill_maps(int32_t* k_map, int32_t* v_map, int rows, int T, int state_k, int state_v,
-                               hipStream_t st) {
-  const int64_t n = (int64_t)rows * T;
-  hipLaunchKernelGGL(fill_maps_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, k_map, v_map, rows, T,
-                     state_k, state_v);
-  return hipGetLastError();
-}
-
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
                            int T, double* scores, hipStream_t st) {
   hipLaunchKernelGGL(score_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, scores);
@@ -438,8 +434,8 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
 }
 
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                          int T, hs_kv_dev kv, hipStream_t st) {
-  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv);
+                          int T, hs_kv_dev kv, int uni_k, int uni_v, hipStream_t st) {
+  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v);
   return hipGetLastError();
 }
 

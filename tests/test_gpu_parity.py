@@ -299,3 +299,43 @@ def test_prefill_cfg2_full_size_sampled_rows():
     idx = tuple(np.array(rows).T)
     assert_close(_f32(O)[idx], Or, "prefill cfg2 sampled")
     assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill cfg2 lse")
+
+
+def test_decode_cfg3_shape_one_batch_row_skip75():
+    """Hierarchical decode sweep workload (L = 131072, 32/8 heads) at its full context for one
+    batch row, 75 % of the tiles skipped + 2:4 in the rest, default launch configuration."""
+    c, q, K, V = wl.make_config("cfg3_decode_b8_128k", B=1)
+    sh, kv, pk, pv, info = compress_both(c["B"], c["Hq"], c["Hkv"], c["L"], K, V, skip_frac=0.75)
+    assert (kv.k_map.cpu().numpy() == pk.map).all() and (kv.v_map.cpu().numpy() == pv.map).all()
+    assert int((pk.map == 0).sum()) == 8 * 1536
+    O, LSE = hb.decode_attn(sh, _dev(q), kv)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, pk, pv)
+    assert_close(_f32(O), Or, "decode cfg3 B=1 skip 0.75")
+    assert_lse_close(LSE.cpu().numpy(), Lr, "decode cfg3 lse")
+
+
+def test_prefill_cfg4_full_size_skip75_sampled_rows():
+    """Long causal prefill at the highest hierarchical sparsity (L = 65536, 75 % of the tiles
+    skipped, 2:4 in the rest): seeded sampled rows plus rows that see no token at all."""
+    c, Q, K, V = wl.make_config("cfg4_prefill_64k")
+    sh, kv, pk, pv, info = compress_both(c["B"], c["Hq"], c["Hkv"], c["L"], K, V, skip_frac=0.75)
+    assert (kv.k_map.cpu().numpy() == pk.map).all() and (kv.v_map.cpu().numpy() == pv.map).all()
+    # rows whose own and all earlier tiles are skipped (kv head 0 ... 7): O = 0, LSE = -inf
+    extra = []
+    for hkv in range(c["Hkv"]):
+        first_kept = int(np.nonzero(pk.map[0, hkv] != 0)[0][0])
+        if first_kept > 0:
+            extra += [(0, 4 * hkv, 0), (0, 4 * hkv + 3, 64 * first_kept - 1)]
+        extra += [(0, 4 * hkv + 1, 64 * first_kept), (0, 4 * hkv + 2, c["L"] - 1)]
+    rows = wl.sample_rows(c["B"], c["Hq"], c["L"], 160, seed=c["seed"] + 4, extra=extra)
+    O, LSE = hb.prefill_attn(sh, _dev(Q), kv)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    got, lse = _f32(O)[idx], LSE.cpu().numpy()[idx]
+    empty = np.isneginf(Lr)
+    assert empty.sum() >= 1
+    assert (got[empty] == 0).all()
+    assert_close(got, Or, "prefill cfg4 skip 0.75 sampled")
+    assert_lse_close(lse, Lr, "prefill cfg4 lse")
