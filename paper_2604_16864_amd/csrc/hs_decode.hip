@@ -273,13 +273,12 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
     }
 
   __shared__ float sm_m[4][8], sm_l[4][8];
-  __shared__ float sm_o[4][8][HS_D];
+  __shared__ __attribute__((aligned(16))) float sm_o[4][8][HS_D];
   if (c < 8) {
     if (a == 0) { sm_m[w][c] = m_run; sm_l[w][c] = l_run; }
 #pragma unroll
     for (int mb = 0; mb < 8; mb++)
-#pragma unroll
-      for (int i = 0; i < 4; i++) sm_o[w][c][16 * mb + 4 * a + i] = o[mb][i];
+      *reinterpret_cast<float4*>(&sm_o[w][c][16 * mb + 4 * a]) = make_float4(o[mb][0], o[mb][1], o[mb][2], o[mb][3]);
   }
   __syncthreads();
   // thread -> (head g = tid / 32, 4 channels)

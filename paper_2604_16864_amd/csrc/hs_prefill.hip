@@ -15,6 +15,13 @@
 
 #include "hs_common.h"
 
+// Wave priority per phase.  Two waves share a SIMD; letting the one that is in its vector-ALU
+// (softmax) phase issue first measured ~5 % faster than equal priorities or the opposite choice.
+#ifndef HS_PRIO_MFMA
+#define HS_PRIO_MFMA 0
+#define HS_PRIO_VALU 1
+#endif
+
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -196,6 +203,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       const uint4* kl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes);
       const uint4* vl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes + 16384);
       // ---------------- GEMM1: S^T[64 tokens x 16 NB queries] ----------------
+      __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
       f32x4_t s[4][NB];
 #pragma unroll
       for (int m = 0; m < 4; m++)
@@ -231,6 +239,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
               s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[st]), as_bf16x8(qb[nb][st >> 1].q[st & 1]), s[m][nb], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
       // causal mask inside a tile that reaches past the slab's first query
       if (causal && HS_BT * j + HS_BT - 1 > qpos + off) {
         const int lim = qpos + off - HS_BT * j + c;  // query 16nb+c sees in-tile tokens <= lim + 16nb
@@ -298,6 +307,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       }
 #pragma unroll
       for (int nb = 0; nb < NB; nb++) l_run[nb] += psum[nb];
+      __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
       if (v_sparse) {
         uint4 av[8];
 #pragma unroll
@@ -332,6 +342,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         }
       }
     }
+    __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
     stage_wait();
     __syncthreads();
     j = jn; mk = mkn; mv = mvn;
