@@ -28,8 +28,8 @@ HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_DENSE_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE on this workload (summary, commands and
 # the copy-kernel calibration: profiles/bench_cfg1_hbm_traffic.md).  Only valid for cfg1 with 2:4 on all tiles.
-TRAFFIC_BYTES = {"decode": (36949.8 * 2.000 + 544.0) * 1024, "compress": (65851.7 * 2.000 + 73728.0) * 1024,
-                 "prefill": (823241.6 * 2.000 + 262144.0) * 1024}
+TRAFFIC_BYTES = {"decode": (36950.25 * 2.000 + 544.0) * 1024, "compress": (65608.8 * 2.000 + 74255.6) * 1024,
+                 "prefill": (711828.0 * 2.000 + 262144.2) * 1024}
 
 
 def packed_bytes(B, Hkv, T, counts):
@@ -314,10 +314,10 @@ def main():
                    "sparsity": "2:4 on every K and V tile (S_K = S_V = 1), no skipping",
                    "step": "compress -> causal prefill (Lq = L) -> decode (1 token)"},
         "stages": stages,
-        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0> (+ merge)", "achieved": decode_bytes / dec_s / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0, 0, true> (+ decode_merge_kernel)", "achieved": decode_bytes / dec_s / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": decode_bytes / dec_s / 1e9 / HBM_PEAK_GBPS,
                      "traffic": TRAFFIC_BYTES["decode"]},
-        "roofline_prefill": {"bound": "mfma", "kernel": "prefill_kernel<0>", "achieved": prefill_flops / pre_s / 1e12,
+        "roofline_prefill": {"bound": "mfma", "kernel": "prefill_kernel<0, 0, 2>", "achieved": prefill_flops / pre_s / 1e12,
                              "peak": MFMA_BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": prefill_flops / pre_s / 1e12 / MFMA_BF16_DENSE_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES["prefill"],
                              "note": "dense-equivalent causal FLOPs over the dense bf16 peak"},
