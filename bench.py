@@ -105,7 +105,24 @@ def extra_legs(hb, torch, Q, K, V, qd, sh, args):
     res["sk0_sv1_same_workload"] = {"prefill_ms": t_p * 1e3, "decode_us": t_d * 1e6,
                                     "decode_GBps": packed_bytes(B, Hkv, T, cts) / t_d / 1e9,
                                     "ideal_prefill_speedup": 4.0 / 3.0, "ideal_decode_speedup": 1.0 / (1.0 - 0.21875)}
-    del kvm, O
+    del kvm
+    # (1b) block-sparsity sweep S_K = S_V = S with the paper's pruning-loss ranking (Eq. 2c-d), against
+    # the analytical curves of Sec. III-D: decode 1/(1 - 0.4375 S), prefill 4/(4 - 2S)
+    sweep_s = []
+    for S in (0.0, 0.25, 0.5, 0.75, 1.0):
+        pol = hb.make_policy(sparse_frac_k=S, sparse_frac_v=S)
+        cts = hb.tile_counts(sh, pol)
+        kvs_ = [hb.compress_kv(sh, pol, K, V, workspace=ws_c) for _ in range(6)]
+        t_p = _time(torch, lambda i: hb.prefill_attn(sh, Q, kvs_[i % 6], causal=True, want_lse=False, out=O), 2)
+        t_d = _time(torch, lambda i: hb.decode_attn(sh, qd, kvs_[i % 6], n_splits=n, want_lse=False, out=Od, workspace=ws_d), 24, warm=6)
+        sweep_s.append({"S": S, "prefill_ms": t_p * 1e3, "decode_us": t_d * 1e6, "packed_MB": packed_bytes(B, Hkv, T, cts) / 1e6,
+                        "ideal_prefill_speedup": 4.0 / (4.0 - 2 * S), "ideal_decode_speedup": 1.0 / (1.0 - 0.4375 * S)})
+        del kvs_
+    for r in sweep_s:
+        r["prefill_speedup_vs_S0"] = sweep_s[0]["prefill_ms"] / r["prefill_ms"]
+        r["decode_speedup_vs_S0"] = sweep_s[0]["decode_us"] / r["decode_us"]
+    res["block_sparsity_sweep_same_workload"] = sweep_s
+    del O
     torch.cuda.empty_cache()
     g = torch.Generator(device="cuda")
     g.manual_seed(3000)
@@ -241,6 +258,24 @@ def main():
     t_c = np.array([e[0].elapsed_time(e[1]) for e in evs]) * 1e-3
     t_p = np.array([e[1].elapsed_time(e[2]) for e in evs]) * 1e-3
     t_d = np.array([e[2].elapsed_time(e[3]) for e in evs]) * 1e-3
+    # The split-KV kernel alone (the kernel that streams the cache): the same launch, over the same rotation
+    # of cold buffers, back to back between two events, the merge kernel left out (phases = 1).
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_rep = max(args.steps, 16)
+    for i in range(args.copies):
+        hb.decode_attn(sh, qd, kvs[i], n_splits=n_splits, out=Od, lse=lse_d, workspace=ws_d, phases=1)
+    e0.record()
+    for i in range(n_rep):
+        hb.decode_attn(sh, qd, kvs[i % args.copies], n_splits=n_splits, out=Od, lse=lse_d, workspace=ws_d, phases=1)
+    e1.record()
+    torch.cuda.synchronize()
+    t_ds = np.array([e0.elapsed_time(e1) / n_rep]) * 1e-3
+    e0.record()
+    for i in range(n_rep):
+        hb.decode_attn(sh, qd, kvs[i % args.copies], n_splits=n_splits, out=Od, lse=lse_d, workspace=ws_d, phases=2)
+    e1.record()
+    torch.cuda.synchronize()
+    t_dm = e0.elapsed_time(e1) / n_rep * 1e-3
 
     kv_bytes = packed_bytes(B, Hkv, T, counts)
     q_bytes = B * Hq * D * 2
@@ -249,12 +284,15 @@ def main():
     compress_bytes = 2 * B * Hkv * L * D * 2 + kv_bytes     # read dense K,V once + write packed
     prefill_flops = 4.0 * D * Hq * B * (L * (L + 1) / 2.0)  # dense-equivalent causal FLOPs
     dec_s, pre_s, cmp_s = float(t_d.mean()), float(t_p.mean()), float(t_c.mean())
+    dec_split_s = float(t_ds.mean())
 
     stages = {
         "compress_us": cmp_s * 1e6, "compress_GBps": compress_bytes / cmp_s / 1e9,
         "compress_frac_of_prefill": cmp_s / pre_s,
         "prefill_ms": pre_s * 1e3, "prefill_dense_equiv_TFLOPs": prefill_flops / pre_s / 1e12,
         "decode_us": dec_s * 1e6, "decode_us_min": float(t_d.min()) * 1e6, "decode_GBps": decode_bytes / dec_s / 1e9,
+        "decode_split_kernel_us": dec_split_s * 1e6, "decode_split_kernel_GBps": decode_bytes / dec_split_s / 1e9,
+        "decode_merge_kernel_us": t_dm * 1e6,
         "decode_n_splits": n_splits, "packed_MB": kv_bytes / 1e6, "dense_MB": 2 * B * Hkv * L * D * 2 / 1e6,
         "compression_ratio": 2 * B * Hkv * L * D * 2 / kv_bytes,
         "ideal_decode_speedup": 1.0 / (1.0 - 0.21875 * 2), "ideal_prefill_speedup": 2.0,
@@ -314,9 +352,12 @@ def main():
                    "sparsity": "2:4 on every K and V tile (S_K = S_V = 1), no skipping",
                    "step": "compress -> causal prefill (Lq = L) -> decode (1 token)"},
         "stages": stages,
-        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0, 0, true> (+ decode_merge_kernel)", "achieved": decode_bytes / dec_s / 1e9,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": decode_bytes / dec_s / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": TRAFFIC_BYTES["decode"]},
+        # dominant kernel of the metric: the split-KV kernel alone (back-to-back launches with the merge kernel
+        # left out); `value` above is the whole decode call (split + merge + launch gap) inside the step
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0, 0, true>", "achieved": decode_bytes / dec_split_s / 1e9,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": decode_bytes / dec_split_s / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": TRAFFIC_BYTES["decode"], "avg_launch_us": dec_split_s * 1e6,
+                     "whole_call_us": dec_s * 1e6, "whole_call_frac": decode_bytes / dec_s / 1e9 / HBM_PEAK_GBPS},
         "roofline_prefill": {"bound": "mfma", "kernel": "prefill_kernel<0, 0, 2>", "achieved": prefill_flops / pre_s / 1e12,
                              "peak": MFMA_BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": prefill_flops / pre_s / 1e12 / MFMA_BF16_DENSE_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES["prefill"],

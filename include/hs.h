@@ -162,6 +162,15 @@ HS_API int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
                    const void* Q, const hs_kv* kv, void* O, float* LSE,
                    void* workspace, void* stream);
 
+/* hs_decode_attn in separable phases, for benchmarking and profiling: `phases` bit 0 launches
+ * the split-KV kernel (reads Q and the cache, writes the partials into `workspace`), bit 1
+ * launches the merge kernel (reads the partials, writes O and LSE).  phases == 3 is
+ * hs_decode_attn; phases == 1 lets a caller time the kernel that streams the cache on its own
+ * (back-to-back launches between two events).  Everything else as hs_decode_attn. */
+HS_API int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_splits,
+                          const void* Q, const hs_kv* kv, void* O, float* LSE,
+                          void* workspace, void* stream, int phases);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,6 +52,8 @@ EXPORTS = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_decode_attn_phases": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV),
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
 }
 
 
@@ -200,8 +202,9 @@ def prefill_attn(shape, Q, kv, causal=True, scale=0.0, want_lse=True, out=None, 
     return O, lse
 
 
-def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, lse=None, workspace=None):
-    """Q: bf16 [B, Hq, D] contiguous.  Returns (O bf16 [B, Hq, D], LSE fp32 [B, Hq] or None)."""
+def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, lse=None, workspace=None, phases=3):
+    """Q: bf16 [B, Hq, D] contiguous.  Returns (O bf16 [B, Hq, D], LSE fp32 [B, Hq] or None).
+    phases: 3 = whole call; 1 = split-KV kernel only, 2 = merge kernel only (benchmarking)."""
     assert Q.dtype == torch.bfloat16 and Q.is_contiguous() and Q.is_cuda
     O = torch.empty_like(Q) if out is None else out
     if lse is None and want_lse:
@@ -209,8 +212,12 @@ def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, ls
     if workspace is None:
         workspace = _workspace(workspace_bytes(shape, 2, n_splits), Q.device)
     kvs = kv.struct()
-    _check(lib().hs_decode_attn(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(O),
-                                _ptr(lse), _ptr(workspace), _stream()))
+    if phases == 3:
+        _check(lib().hs_decode_attn(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(O),
+                                    _ptr(lse), _ptr(workspace), _stream()))
+    else:
+        _check(lib().hs_decode_attn_phases(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(O),
+                                           _ptr(lse), _ptr(workspace), _stream(), int(phases)))
     return O, lse
 
 

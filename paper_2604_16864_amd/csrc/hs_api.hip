@@ -262,6 +262,12 @@ int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal, 
 
 int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
                    float* LSE, void* workspace, void* stream) {
+  return hs_decode_attn_phases(shape, scale, n_splits, Q, kv, O, LSE, workspace, stream, 3);
+}
+
+int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
+                          float* LSE, void* workspace, void* stream, int phases) {
+  if (phases < 1 || phases > 3) return HS_EINVAL;
   int rc = check_shape(shape);
   if (rc != HS_OK) return rc;
   rc = check_kv(shape, kv);
@@ -280,7 +286,7 @@ int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const v
   }
   const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
                                         (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
-                                        (float*)workspace, (hipStream_t)stream);
+                                        (float*)workspace, (hipStream_t)stream, phases);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

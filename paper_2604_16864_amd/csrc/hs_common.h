@@ -82,6 +82,6 @@ hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int6
                           int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
-                            hs_kv_dev kv, uint16_t* O, float* LSE, float* ws, hipStream_t st);
+                            hs_kv_dev kv, uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases);
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
                              hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st);

@@ -369,7 +369,7 @@ static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T
 }
 
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q, hs_kv_dev kv,
-                            uint16_t* O, float* LSE, float* ws, hipStream_t st) {
+                            uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases) {
   const dim3 grid(n_splits, Hkv, B);
   const float sl2 = scale * kLog2e;
   const int per = (T + n_splits - 1) / n_splits;
@@ -377,7 +377,8 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_sp
   float* wl = wo + (size_t)B * Hq * n_splits * HS_D;
   const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
   const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
-  hipError_t e;
+  hipError_t e = hipSuccess;
+  if (phases & 1) {
 #define HS_GO(KM_, VM_)                                                                                         \
   e = kv.uniform ? launch_split<KM_, VM_, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)       \
                  : launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);     \
@@ -396,7 +397,8 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_sp
   }
 #undef HS_GO
 #undef HS_GO_DYN
-  if (e != hipSuccess) return e;
+  }
+  if (e != hipSuccess || !(phases & 2)) return e;
   hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);
   return hipGetLastError();
 }
