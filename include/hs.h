@@ -70,13 +70,28 @@ typedef struct {
  *   state_k/_v     [host] optional explicit per-tile states, int8 [B, Hkv, T];
  *                  when non-NULL (both or neither) they replace the fractions.
  *                  A tile must be SKIP in both or in neither.
+ *   dense_first_tiles, dense_last_tiles
+ *                  the first / last so many tiles of every row stay DENSE in K and V and
+ *                  take no part in either ranking (the "sink" and "local window" tokens
+ *                  the paper's evaluation keeps dense, Sec. V-A: 64 and 256 tokens = 1 and
+ *                  4 tiles); the fractions then apply to the T - first - last tiles in
+ *                  between.  Ignored with explicit states.
+ *   element_rule   HS_RULE_MAGNITUDE: keep the 2 largest magnitudes of every group of 4
+ *                  (the fused magnitude compressor, Sec. IV-B).  HS_RULE_NONZERO: the input
+ *                  already carries an element mask (pruned entries are zero): keep the
+ *                  non-zero entries, and if a group has fewer than 2, fill up with its
+ *                  lowest-position zeros (the generic compressor of Sec. IV-B).
  * Ties in either ranking go to the lower tile index. */
+enum { HS_RULE_MAGNITUDE = 0, HS_RULE_NONZERO = 1 };
 typedef struct {
   double skip_frac;
   double sparse_frac_k;
   double sparse_frac_v;
   const int8_t* state_k;
   const int8_t* state_v;
+  int32_t dense_first_tiles;
+  int32_t dense_last_tiles;
+  int32_t element_rule;
 } hs_policy;
 
 /* Packed cache: caller-owned device buffers, rectangular per (b, kv head).
@@ -133,7 +148,7 @@ HS_API int hs_decode_auto_splits(const hs_shape* shape);
  * token axes (NULL = contiguous).  Element mask: K keeps the 2 largest
  * magnitudes of every 4 consecutive channels of a token, V of every 4
  * consecutive tokens of a channel (magnitude = bits & 0x7fff, ties to the lower
- * position).  Writes maps and pools of `out`; slots beyond the used count are
+ * position; with HS_RULE_NONZERO the key is magnitude != 0 instead).  Writes maps and pools of `out`; slots beyond the used count are
  * left untouched.  workspace: hs_workspace_bytes(op 0). */
 HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],

@@ -42,15 +42,23 @@ def bf16_to_f64(bits):
 # ----------------------------------------------------------------------------
 # element-level 2:4 mask (Sec. III-A, Eq. 2a-b; fused top-2 form of Sec. IV-B)
 # ----------------------------------------------------------------------------
-def _top2_of_4(bits_g):
+def _top2_of_4(bits_g, rule="magnitude"):
     """bits_g: uint16 [..., 4].  Boolean keep mask with exactly two True per group.
 
     Order is by magnitude, i.e. by the integer (bits & 0x7FFF), descending; equal
     magnitudes are resolved in favour of the lower position, so that exactly two
     survive (Eq. 2b would keep more than two on ties, which the 2:4 format cannot
     store).
+
+    rule "nonzero" is the generic compressor of Sec. IV-B for input that already carries an
+    element mask (pruned entries are zero): the key is "is non-zero", so the non-zero entries
+    are kept and a group with fewer than two of them is filled up with its leftmost zeros.
     """
     key = (bits_g & np.uint16(0x7FFF)).astype(np.int32)
+    if rule == "nonzero":
+        key = (key != 0).astype(np.int32)
+    else:
+        assert rule == "magnitude"
     pos = np.arange(4, dtype=np.int32)
     # beats[..., i, j] = element j is ranked ahead of element i
     ki = key[..., :, None]
@@ -60,24 +68,24 @@ def _top2_of_4(bits_g):
     return rank < 2
 
 
-def element_mask_k(K_bits):
+def element_mask_k(K_bits, rule="magnitude"):
     """K is the sparse operand of S^T = K Q^T, contraction over channels: groups
     are 4 consecutive channels of one token (Sec. III-C, Table II)."""
     K_bits = np.asarray(K_bits, dtype=np.uint16)
     B, H, L, D = K_bits.shape
     assert D % 4 == 0
-    m = _top2_of_4(K_bits.reshape(B, H, L, D // 4, 4))
+    m = _top2_of_4(K_bits.reshape(B, H, L, D // 4, 4), rule)
     return m.reshape(B, H, L, D)
 
 
-def element_mask_v(V_bits):
+def element_mask_v(V_bits, rule="magnitude"):
     """V^T is the sparse operand of O^T = V^T P^T, contraction over tokens: groups
     are 4 consecutive tokens of one channel (Sec. III-C, Table II)."""
     V_bits = np.asarray(V_bits, dtype=np.uint16)
     B, H, L, D = V_bits.shape
     assert L % 4 == 0
     g = V_bits.reshape(B, H, L // 4, 4, D).transpose(0, 1, 2, 4, 3)  # [..., L/4, D, 4]
-    m = _top2_of_4(g)
+    m = _top2_of_4(g, rule)
     return m.transpose(0, 1, 2, 4, 3).reshape(B, H, L, D)
 
 
@@ -109,28 +117,33 @@ def _lowest(scores_row, n, eligible):
     return idx[:n]
 
 
-def select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v):
+def select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v, dense_first=0, dense_last=0):
     """Tile states for K and V, per (b, hkv) row.
 
-    n_skip = floor(skip_frac * T) lowest-energy tiles are SKIP for both tensors.
-    Of the remaining n_keep tiles, floor(sparse_frac_x * n_keep) with the lowest
-    pruning loss (Eq. 2c-d) become SPARSE24, the rest stay DENSE.
+    The first dense_first and the last dense_last tiles stay DENSE and take no part in any
+    ranking (the sink / local-window tokens the paper's evaluation keeps dense, Sec. V-A).
+    Of the T_mid tiles in between, n_skip = floor(skip_frac * T_mid) lowest-energy ones are
+    SKIP for both tensors; of the remaining n_keep, floor(sparse_frac_x * n_keep) with the
+    lowest pruning loss (Eq. 2c-d) become SPARSE24, the rest stay DENSE.
     Returns (state_k, state_v) int8 [B, Hkv, T].
     """
     B, H, T = energy.shape
     sk = np.full((B, H, T), DENSE, dtype=np.int8)
     sv = np.full((B, H, T), DENSE, dtype=np.int8)
-    n_skip = int(np.floor(skip_frac * T))
+    dense_first = min(dense_first, T)
+    dense_last = min(dense_last, T - dense_first)
+    mid = [dense_first <= t < T - dense_last for t in range(T)]
+    n_mid = sum(mid)
+    n_skip = int(np.floor(skip_frac * n_mid))
     for b in range(B):
         for h in range(H):
-            all_ok = [True] * T
-            skipped = _lowest(energy[b, h], n_skip, all_ok)
-            kept = [True] * T
+            skipped = _lowest(energy[b, h], n_skip, mid)
+            kept = list(mid)
             for t in skipped:
                 kept[t] = False
                 sk[b, h, t] = SKIP
                 sv[b, h, t] = SKIP
-            n_keep = T - n_skip
+            n_keep = n_mid - n_skip
             for st, loss, frac in ((sk, loss_k, sparse_frac_k), (sv, loss_v, sparse_frac_v)):
                 n_sp = int(np.floor(frac * n_keep))
                 for t in _lowest(loss[b, h], n_sp, kept):
@@ -304,19 +317,20 @@ def unpack_tensor(p):
 
 
 def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0,
-                state_k=None, state_v=None):
+                state_k=None, state_v=None, dense_first_tiles=0, dense_last_tiles=0, element_rule="magnitude"):
     """Whole compress step: element masks, tile states (policy or explicit),
     maps, pools.  Returns (PackedKV for K, PackedKV for V, dict of intermediates)."""
     K_bits = np.asarray(K_bits, dtype=np.uint16)
     V_bits = np.asarray(V_bits, dtype=np.uint16)
-    mk = element_mask_k(K_bits)
-    mv = element_mask_v(V_bits)
+    mk = element_mask_k(K_bits, element_rule)
+    mv = element_mask_v(V_bits, element_rule)
     info = {"mask_k": mk, "mask_v": mv}
     if state_k is None:
         energy = tile_energy(K_bits, V_bits, Bt)
         loss_k = tile_prune_loss(K_bits, mk, Bt)
         loss_v = tile_prune_loss(V_bits, mv, Bt)
-        state_k, state_v = select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v)
+        state_k, state_v = select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v,
+                                         dense_first_tiles, dense_last_tiles)
         info.update(energy=energy, loss_k=loss_k, loss_v=loss_v)
     state_k = np.asarray(state_k, dtype=np.int8)
     state_v = np.asarray(state_v, dtype=np.int8)

@@ -27,7 +27,8 @@ class HsShape(C.Structure):
 
 class HsPolicy(C.Structure):
     _fields_ = [("skip_frac", C.c_double), ("sparse_frac_k", C.c_double), ("sparse_frac_v", C.c_double),
-                ("state_k", C.c_void_p), ("state_v", C.c_void_p)]
+                ("state_k", C.c_void_p), ("state_v", C.c_void_p),
+                ("dense_first_tiles", C.c_int32), ("dense_last_tiles", C.c_int32), ("element_rule", C.c_int32)]
 
 
 class HsKV(C.Structure):
@@ -98,10 +99,15 @@ def make_shape(B, Hq, Hkv, L, D=HEAD_DIM, tile=TILE):
     return HsShape(B, Hq, Hkv, L, D, tile)
 
 
-def make_policy(skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0, state_k=None, state_v=None):
+RULE_MAGNITUDE, RULE_NONZERO = 0, 1
+
+
+def make_policy(skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0, state_k=None, state_v=None,
+                dense_first_tiles=0, dense_last_tiles=0, element_rule=RULE_MAGNITUDE):
     """state_k/state_v: optional host int8 arrays [B, Hkv, T].  The returned object
     keeps them alive."""
-    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None)
+    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None,
+                 int(dense_first_tiles), int(dense_last_tiles), int(element_rule))
     if state_k is not None:
         sk = np.ascontiguousarray(state_k, dtype=np.int8)
         sv = np.ascontiguousarray(state_v, dtype=np.int8)

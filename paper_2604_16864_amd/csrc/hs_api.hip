@@ -29,12 +29,23 @@ int check_shape(const hs_shape* s) {
 bool frac_ok(double f) { return f >= 0.0 && f <= 1.0; }
 
 // Tile counts of a fraction policy (same for every row).
+// Protected (always dense) tiles at both ends, clipped so that they never overlap.
+void protected_tiles(int T, const hs_policy* p, int* n_first, int* n_last) {
+  int f = p->dense_first_tiles < T ? p->dense_first_tiles : T;
+  int l = p->dense_last_tiles < T - f ? p->dense_last_tiles : T - f;
+  *n_first = f;
+  *n_last = l;
+}
+
 void policy_counts(int T, const hs_policy* p, int32_t c[5]) {
-  const int n_skip = (int)floor(p->skip_frac * T);
-  const int n_keep = T - n_skip;
+  int n_first, n_last;
+  protected_tiles(T, p, &n_first, &n_last);
+  const int n_prot = n_first + n_last, n_mid = T - n_prot;
+  const int n_skip = (int)floor(p->skip_frac * n_mid);
+  const int n_keep = n_mid - n_skip;
   const int nsk = (int)floor(p->sparse_frac_k * n_keep);
   const int nsv = (int)floor(p->sparse_frac_v * n_keep);
-  c[0] = n_skip; c[1] = n_keep - nsk; c[2] = nsk; c[3] = n_keep - nsv; c[4] = nsv;
+  c[0] = n_skip; c[1] = n_prot + n_keep - nsk; c[2] = nsk; c[3] = n_prot + n_keep - nsv; c[4] = nsv;
 }
 
 int check_policy(const hs_policy* p) {
@@ -43,7 +54,9 @@ int check_policy(const hs_policy* p) {
   if (p->state_k == nullptr) {
     if (!(p->skip_frac >= 0.0 && p->skip_frac < 1.0)) return HS_EINVAL;
     if (!frac_ok(p->sparse_frac_k) || !frac_ok(p->sparse_frac_v)) return HS_EINVAL;
+    if (p->dense_first_tiles < 0 || p->dense_last_tiles < 0) return HS_EINVAL;
   }
+  if (p->element_rule != HS_RULE_MAGNITUDE && p->element_rule != HS_RULE_NONZERO) return HS_EINVAL;
   return HS_OK;
 }
 
@@ -181,50 +194,69 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
   int32_t c[5];
   hipError_t e;
   int uni_k = 0, uni_v = 0;
-  if (policy->state_k != nullptr) {
-    // explicit states [host]: walk the tiles in order with one counter per pool (Sec. III-B)
-    rc = explicit_counts(shape, policy, c);
-    if (rc != HS_OK) return rc;
-    if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
-      return HS_EINVAL;
+  // maps from per-tile states known on the host: walk the tiles in order with one counter per
+  // pool (Sec. III-B) and copy the result over (synchronously: the host vectors die at return)
+  auto maps_from_states = [&](const int8_t* sk_all, const int8_t* sv_all, int64_t row_stride) -> int {
     std::vector<int32_t> mk((size_t)rows * T), mv((size_t)rows * T);
     for (int r = 0; r < rows; r++) {
       int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
       for (int t = 0; t < T; t++) {
         const size_t i = (size_t)r * T + t;
-        const int sk = policy->state_k[i], sv = policy->state_v[i];
+        const int sk = sk_all[r * row_stride + t], sv = sv_all[r * row_stride + t];
         mk[i] = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
         mv[i] = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
       }
     }
-    // synchronous copies: the host vectors die at return
-    e = hipMemcpyAsync(out->k_map, mk.data(), mk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return hip_fail(e);
-    e = hipMemcpyAsync(out->v_map, mv.data(), mv.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return hip_fail(e);
-    e = hipStreamSynchronize(s);
-    if (e != hipSuccess) return hip_fail(e);
+    hipError_t err = hipMemcpyAsync(out->k_map, mk.data(), mk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+    if (err != hipSuccess) return hip_fail(err);
+    err = hipMemcpyAsync(out->v_map, mv.data(), mv.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+    if (err != hipSuccess) return hip_fail(err);
+    err = hipStreamSynchronize(s);
+    if (err != hipSuccess) return hip_fail(err);
+    return HS_OK;
+  };
+  if (policy->state_k != nullptr) {
+    rc = explicit_counts(shape, policy, c);
+    if (rc != HS_OK) return rc;
+    if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
+      return HS_EINVAL;
+    rc = maps_from_states(policy->state_k, policy->state_v, T);
+    if (rc != HS_OK) return rc;
   } else {
     policy_counts(T, policy, c);
     if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
       return HS_EINVAL;
+    int n_first, n_last;
+    protected_tiles(T, policy, &n_first, &n_last);
+    const int n_keep = T - n_first - n_last - c[0];
     const bool uniform_k = c[1] == 0 || c[2] == 0, uniform_v = c[3] == 0 || c[4] == 0;
     if (c[0] == 0 && uniform_k && uniform_v) {
       // no ranking needed: every tile in one state; the pack kernel writes the maps itself
       uni_k = c[2] ? HS_SPARSE24 : HS_DENSE;
       uni_v = c[4] ? HS_SPARSE24 : HS_DENSE;
+    } else if (c[0] == 0 && (c[2] == 0 || c[2] == n_keep) && (c[4] == 0 || c[4] == n_keep)) {
+      // no ranking needed either: protected end tiles dense, every tile in between in one state
+      std::vector<int8_t> sk(T), sv(T);
+      for (int t = 0; t < T; t++) {
+        const bool prot = t < n_first || t >= T - n_last;
+        sk[t] = prot || c[2] == 0 ? HS_DENSE : HS_SPARSE24;
+        sv[t] = prot || c[4] == 0 ? HS_DENSE : HS_SPARSE24;
+      }
+      rc = maps_from_states(sk.data(), sv.data(), 0);
+      if (rc != HS_OK) return rc;
     } else {
       if (workspace == nullptr || ((uintptr_t)workspace & 7u)) return HS_EINVAL;
       if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
       e = hs_launch_score((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
-                          (double*)workspace, s);
+                          policy->element_rule, (double*)workspace, s);
       if (e != hipSuccess) return hip_fail(e);
-      e = hs_launch_select((const double*)workspace, rows, T, c[0], c[2], c[4], out->k_map, out->v_map, s);
+      e = hs_launch_select((const double*)workspace, rows, T, c[0], c[2], c[4], n_first, n_last, out->k_map,
+                           out->v_map, s);
       if (e != hipSuccess) return hip_fail(e);
     }
   }
   e = hs_launch_pack((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
-                     hs_make_kv_dev(out), uni_k, uni_v, s);
+                     hs_make_kv_dev(out), uni_k, uni_v, policy->element_rule, s);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

@@ -75,11 +75,11 @@ __host__ __device__ static inline int hs_v_group(int a, int q) {
 
 // launchers implemented in the kernel translation units; all return a hipError_t
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                           int B, int Hkv, int T, double* scores, hipStream_t st);
+                           int B, int Hkv, int T, int rule, double* scores, hipStream_t st);
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
-                            int32_t* k_map, int32_t* v_map, hipStream_t st);
+                            int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st);
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                          int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, hipStream_t st);
+                          int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
                             hs_kv_dev kv, uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases);

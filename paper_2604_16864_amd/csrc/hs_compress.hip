@@ -10,8 +10,11 @@ constexpr int kVStride = 132;  // LDS row stride (elements) of a staged V tile: 
 // Top-2-of-4 by magnitude (Eq. 2a-b with an exact count of two): x0..x3 are bf16 bit
 // patterns; element j outranks element i if |x_j| > |x_i|, or |x_j| == |x_i| and j < i.
 // Returns the 4-bit keep mask (exactly two bits set).
-__device__ __forceinline__ uint32_t top2_mask(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3) {
-  const uint32_t k0 = x0 & 0x7fffu, k1 = x1 & 0x7fffu, k2 = x2 & 0x7fffu, k3 = x3 & 0x7fffu;
+// rule != 0 (input already masked): the key is "non-zero" instead of the magnitude, so the
+// non-zero entries win and ties (zeros) go to the lower position.
+__device__ __forceinline__ uint32_t top2_mask(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3, int rule) {
+  uint32_t k0 = x0 & 0x7fffu, k1 = x1 & 0x7fffu, k2 = x2 & 0x7fffu, k3 = x3 & 0x7fffu;
+  if (rule != 0) { k0 = k0 != 0; k1 = k1 != 0; k2 = k2 != 0; k3 = k3 != 0; }
   const uint32_t g01 = k0 >= k1, g02 = k0 >= k2, g03 = k0 >= k3, g12 = k1 >= k2, g13 = k1 >= k3, g23 = k2 >= k3;
   const uint32_t c0 = 3u - g01 - g02 - g03;        // how many outrank element 0
   const uint32_t c1 = g01 + 2u - g12 - g13;
@@ -55,7 +58,7 @@ __device__ __forceinline__ void stage_v_tile(const uint16_t* vt, int64_t tok_str
 // 2:4 mask removes (Eq. 2c).  fp64, fixed reduction order.  scores = [3][rows][T].
 // ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T,
+                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T, int rule,
                                                     double* __restrict__ scores) {
   __shared__ uint16_t vl[HS_BT * kVStride];
   __shared__ double red[3][4];
@@ -75,7 +78,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 #pragma unroll
       for (int q = 0; q < 4; q++) {
         const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
-        const uint32_t m = top2_mask(x0, x1, x2, x3);
+        const uint32_t m = top2_mask(x0, x1, x2, x3, rule);
         const double f0 = bf16_val(x0), f1 = bf16_val(x1), f2 = bf16_val(x2), f3 = bf16_val(x3);
         e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
         lk += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
         const int g = hs_v_group(a, q);
         const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
         const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
-        const uint32_t m = top2_mask(x0, x1, x2, x3);
+        const uint32_t m = top2_mask(x0, x1, x2, x3, rule);
         const double f0 = bf16_val(x0), f1 = bf16_val(x1), f2 = bf16_val(x2), f3 = bf16_val(x3);
         e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
         lv += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
@@ -125,8 +128,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 constexpr int kRankChunk = 2048;
 
 // phase 1: km[t] = 1 if tile t is kept, 0 if it is among the n_skip lowest-energy tiles
+// Tiles t < n_first or t >= T - n_last are protected: always kept dense, outside both rankings.
 __global__ __launch_bounds__(256) void rank_skip_kernel(const double* __restrict__ scores, int T, int n_skip,
-                                                        int32_t* km_all) {
+                                                        int n_first, int n_last, int32_t* km_all) {
   __shared__ double se[kRankChunk];
   const int row = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
   const double* en = scores + (int64_t)row * T;  // plane 0 = energy
@@ -138,18 +142,20 @@ __global__ __launch_bounds__(256) void rank_skip_kernel(const double* __restrict
     for (int i = threadIdx.x; i < n; i += 256) se[i] = en[c0 + i];
     __syncthreads();
     for (int i = 0; i < n; i++) {
+      const int u = c0 + i;
+      if (u < n_first || u >= T - n_last) continue;
       const double eu = se[i];
-      rank += (eu < e) || (eu == e && c0 + i < t);
+      rank += (eu < e) || (eu == e && u < t);
     }
   }
-  if (t < T) km_all[(int64_t)row * T + t] = rank >= n_skip;
+  if (t < T) km_all[(int64_t)row * T + t] = (t < n_first || t >= T - n_last) ? 2 : (rank >= n_skip);  // 2 = protected
 }
 
 // phase 2: vm[t] = state_k | state_v << 8: among kept tiles the n_sparse_x with the lowest
 // pruning loss are 2:4, the others dense
 __global__ __launch_bounds__(256) void rank_state_kernel(const double* __restrict__ scores, int rows, int T,
                                                          int n_sparse_k, int n_sparse_v, const int32_t* km_all,
-                                                         int32_t* vm_all) {
+                                                         int32_t* vm_all) {  // km: 0 skipped, 1 kept, 2 protected
   __shared__ double sk_[kRankChunk], sv_[kRankChunk];
   __shared__ int skept[kRankChunk];
   const int row = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
@@ -164,7 +170,7 @@ __global__ __launch_bounds__(256) void rank_state_kernel(const double* __restric
     for (int i = threadIdx.x; i < n; i += 256) { sk_[i] = lk[c0 + i]; sv_[i] = lv[c0 + i]; skept[i] = km[c0 + i]; }
     __syncthreads();
     for (int i = 0; i < n; i++) {
-      if (skept[i] == 0) continue;
+      if (skept[i] != 1) continue;
       const double au = sk_[i], cu = sv_[i];
       rk += (au < a) || (au == a && c0 + i < t);
       rv += (cu < c) || (cu == c && c0 + i < t);
@@ -172,7 +178,8 @@ __global__ __launch_bounds__(256) void rank_state_kernel(const double* __restric
   }
   if (t < T) {
     int st = 0;
-    if (km[t] != 0) st = (rk < n_sparse_k ? HS_SPARSE24 : HS_DENSE) | ((rv < n_sparse_v ? HS_SPARSE24 : HS_DENSE) << 8);
+    if (km[t] == 1) st = (rk < n_sparse_k ? HS_SPARSE24 : HS_DENSE) | ((rv < n_sparse_v ? HS_SPARSE24 : HS_DENSE) << 8);
+    if (km[t] == 2) st = HS_DENSE | (HS_DENSE << 8);
     vm_all[(int64_t)row * T + t] = st;
   }
 }
@@ -214,7 +221,7 @@ __global__ __launch_bounds__(256) void slots_kernel(int T, int32_t* k_map, int32
 // kernel writes it (saves the separate map-fill launch of the unranked policies).
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv,
-                                                   int uni_k, int uni_v) {
+                                                   int uni_k, int uni_v, int rule) {
   __shared__ uint16_t vl[HS_BT * kVStride];
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
@@ -260,7 +267,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
       for (int q = 0; q < 4; q++) {
         const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
         uint32_t nib;
-        top2_emit(top2_mask(x0, x1, x2, x3), x0, x1, x2, x3, out[q], nib);
+        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, out[q], nib);
         idx |= nib << (16 * kb + 4 * q);
       }
       *reinterpret_cast<uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
@@ -302,7 +309,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
         const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
         const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
         uint32_t nib;
-        top2_emit(top2_mask(x0, x1, x2, x3), x0, x1, x2, x3, out[q], nib);
+        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, out[q], nib);
         idx |= nib << (16 * j + 4 * q);
       }
       *reinterpret_cast<uint4*>(nnz + (mb * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
@@ -419,23 +426,23 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
 }  // namespace
 
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                           int T, double* scores, hipStream_t st) {
-  hipLaunchKernelGGL(score_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, scores);
+                           int T, int rule, double* scores, hipStream_t st) {
+  hipLaunchKernelGGL(score_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);
   return hipGetLastError();
 }
 
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
-                            int32_t* k_map, int32_t* v_map, hipStream_t st) {
+                            int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st) {
   const dim3 grid((T + 255) / 256, rows);
-  hipLaunchKernelGGL(rank_skip_kernel, grid, dim3(256), 0, st, scores, T, n_skip, k_map);
+  hipLaunchKernelGGL(rank_skip_kernel, grid, dim3(256), 0, st, scores, T, n_skip, n_first, n_last, k_map);
   hipLaunchKernelGGL(rank_state_kernel, grid, dim3(256), 0, st, scores, rows, T, n_sparse_k, n_sparse_v, k_map, v_map);
   hipLaunchKernelGGL(slots_kernel, dim3(rows), dim3(256), 0, st, T, k_map, v_map);
   return hipGetLastError();
 }
 
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                          int T, hs_kv_dev kv, int uni_k, int uni_v, hipStream_t st) {
-  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v);
+                          int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st) {
+  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule);
   return hipGetLastError();
 }
 

@@ -44,7 +44,10 @@ def assert_lse_close(lse, ref, what):
 
 def compress_both(B, Hq, Hkv, L, K, V, **pol):
     sh = hb.make_shape(B, Hq, Hkv, L)
-    policy = hb.make_policy(**pol)
+    lib_pol = dict(pol)
+    if "element_rule" in lib_pol:
+        lib_pol["element_rule"] = {"magnitude": hb.RULE_MAGNITUDE, "nonzero": hb.RULE_NONZERO}[lib_pol["element_rule"]]
+    policy = hb.make_policy(**lib_pol)
     kv = hb.compress_kv(sh, policy, _dev(K), _dev(V))
     torch.cuda.synchronize()
     pk, pv, info = orc.compress_kv(K, V, Bt=64, **pol)
@@ -135,6 +138,53 @@ def test_compress_policy_ranking(skip, sfk, sfv):
         gaps = np.diff(s, axis=-1) / s[..., 1:]
         assert ((gaps > 1e-12) | (gaps == 0)).all()
     check_packed_bit_exact(sh, kv, pk, pv)
+
+
+@pytest.mark.parametrize("skip,sfk,sfv,first,last", [(0.0, 1.0, 1.0, 1, 2), (0.5, 1.0, 1.0, 1, 4), (0.25, 0.5, 0.3, 2, 3),
+                                                     (0.0, 1.0, 0.0, 3, 0), (0.5, 1.0, 1.0, 30, 30)])
+def test_compress_protected_end_tiles(skip, sfk, sfv, first, last):
+    """Sink / local-window tiles stay dense (both the host-built map path and the ranked one);
+    the all-zero end tiles would be the first skipped if they took part in the ranking."""
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 40
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=33)
+    K[0, 0, :64] = 0
+    V[0, 0, :64] = 0
+    K[1, 1, -64:] = 0
+    V[1, 1, -64:] = 0
+    pol = dict(skip_frac=skip, sparse_frac_k=sfk, sparse_frac_v=sfv, dense_first_tiles=first, dense_last_tiles=last)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, **pol)
+    assert (pk.map[:, :, :min(first, 40)] > 0).all() and (pv.map[:, :, 40 - min(last, 40 - min(first, 40)):] > 0).all()
+    check_packed_bit_exact(sh, kv, pk, pv)
+    q = Q[:, :, 0, :].copy()
+    O, LSE = hb.decode_attn(sh, _dev(q), kv)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, pk, pv)
+    assert_close(_f32(O), Or, f"decode protected tiles {pol}")
+    assert_lse_close(LSE.cpu().numpy(), Lr, "decode protected tiles lse")
+
+
+def test_compress_nonzero_rule_premasked_input():
+    """Generic compressor (Sec. IV-B): K, V arrive with an arbitrary 2:4 element mask applied
+    (zeros at pruned places); under the non-zero rule the packed form decodes to the input."""
+    B, Hq, Hkv, L = 1, 4, 2, 64 * 6
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=35)
+    rng = np.random.default_rng(36)
+    K[K == 0] = 0x3F80
+    V[V == 0] = 0x3F80
+    pairs = np.array([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]], dtype=bool)
+    mk = pairs[rng.integers(0, 6, size=(B, Hkv, L, 32))].reshape(B, Hkv, L, 128)
+    mv = pairs[rng.integers(0, 6, size=(B, Hkv, L // 4, 128))].transpose(0, 1, 2, 4, 3).reshape(B, Hkv, L, 128)
+    Km, Vm = np.where(mk, K, 0).astype(np.uint16), np.where(mv, V, 0).astype(np.uint16)
+    Km[0, 0, 7, 0:8] = [0, 0x4000, 0, 0, 0, 0, 0, 0]        # one survivor; an empty group
+    Vm[0, 1, 8:12, 5] = [0x8000, 0, 0xC000, 0x4000]         # a negative zero counts as pruned
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Km, Vm, element_rule="nonzero", skip_frac=0.2, sparse_frac_k=0.75)
+    check_packed_bit_exact(sh, kv, pk, pv)
+    Ku, Vu = hb.unpack_kv(sh, kv)
+    kept = np.repeat(pk.map != 0, 64, axis=-1)[..., None]
+    Vw = Vm.copy()
+    Vw[0, 1, 8, 5] = 0
+    assert (hb.bf16_tensor_to_bits(Ku) == np.where(kept, Km, 0)).all()
+    assert (hb.bf16_tensor_to_bits(Vu) == np.where(kept, Vw, 0)).all()
 
 
 # ------------------------------------------------------------------ decode
@@ -339,3 +389,71 @@ def test_prefill_cfg4_full_size_skip75_sampled_rows():
     assert (got[empty] == 0).all()
     assert_close(got, Or, "prefill cfg4 skip 0.75 sampled")
     assert_lse_close(lse, Lr, "prefill cfg4 lse")
+
+
+# ------------------------------------------------------------------ edges and errors
+def test_single_tile_and_odd_batch_shapes():
+    """L = 64 (one tile, one split), B = 3, 3 KV heads: smallest grid dimensions on every kernel."""
+    for (B, Hq, Hkv, L) in ((1, 1, 1, 64), (3, 6, 3, 64 * 3), (2, 16, 2, 64 * 2)):
+        Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=130 + B)
+        sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V)
+        check_packed_bit_exact(sh, kv, pk, pv)
+        O, LSE = hb.prefill_attn(sh, _dev(Q), kv)
+        q = Q[:, :, -1, :].copy()
+        Od, LSEd = hb.decode_attn(sh, _dev(q), kv)
+        torch.cuda.synchronize()
+        rows = [(b, h, i) for b in range(B) for h in range(Hq) for i in range(L)]
+        Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+        assert_close(_f32(O).reshape(-1, 128), Or, f"prefill B{B} Hq{Hq} Hkv{Hkv} L{L}")
+        Odr, Ldr = orc.attention_decode(q, pk, pv)
+        assert_close(_f32(Od), Odr, f"decode B{B} Hq{Hq} Hkv{Hkv} L{L}")
+        assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode lse")
+
+
+def test_scale_argument_and_large_logits():
+    """Explicit softmax scale, and keys scaled so that logits reach the hundreds (the lazily
+    updated softmax reference must follow without overflow)."""
+    B, Hq, Hkv, L = 1, 4, 1, 64 * 6
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=140)
+    Kbig = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(K) * 24.0)
+    # a late tile with much larger keys: the reference has to jump upwards mid-sequence
+    Kbig[:, :, 64 * 4:64 * 5] = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(K[:, :, 64 * 4:64 * 5]) * 96.0)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Kbig, V)
+    for scale in (0.0, 0.25):
+        O, LSE = hb.prefill_attn(sh, _dev(Q), kv, scale=scale)
+        Od, LSEd = hb.decode_attn(sh, _dev(Q[:, :, -1, :].copy()), kv, scale=scale)
+        torch.cuda.synchronize()
+        rows = [(0, h, i) for h in range(Hq) for i in range(L)]
+        Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True, scale=None if scale == 0.0 else scale)
+        assert_close(_f32(O).reshape(-1, 128), Or, f"prefill large logits scale={scale}")
+        assert_lse_close(LSE.cpu().numpy().reshape(-1), Lr, f"prefill large logits lse scale={scale}")
+        Odr, Ldr = orc.attention_decode(Q[:, :, -1, :].copy(), pk, pv, scale=None if scale == 0.0 else scale)
+        assert_close(_f32(Od), Odr, f"decode large logits scale={scale}")
+
+
+def test_argument_errors_on_device_calls():
+    B, Hq, Hkv, L = 1, 4, 1, 256
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=150)
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    Kd, Vd = _dev(K), _dev(V)
+    # pools sized for an all-2:4 policy cannot take a policy that needs dense tiles
+    kv = hb.PackedKV(sh, hb.tile_counts(sh, hb.make_policy()))
+    with pytest.raises(hb.HsError):
+        hb.compress_kv(sh, hb.make_policy(sparse_frac_k=0.5), Kd, Vd, out=kv)
+    # explicit states: a tile skipped in K only is inconsistent
+    sk = np.array([[[2, 0, 2, 2]]], dtype=np.int8)
+    sv = np.array([[[2, 2, 2, 2]]], dtype=np.int8)
+    with pytest.raises(hb.HsError):
+        hb.compress_kv(sh, hb.make_policy(state_k=sk, state_v=sv), Kd, Vd, out=kv)
+    kv = hb.compress_kv(sh, hb.make_policy(), Kd, Vd)
+    # Lq not a multiple of the tile, Lq > L
+    import ctypes as C
+    kvs = kv.struct()
+    Qd = _dev(Q)
+    O = torch.empty_like(Qd)
+    assert hb.lib().hs_prefill_attn(C.byref(sh), 100, 0.0, 1, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, None, None) == -2
+    assert hb.lib().hs_prefill_attn(C.byref(sh), 512, 0.0, 1, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, None, None) == -1
+    # a uniform promise that the capacities contradict
+    kvs.cap_sparse_k = 2
+    assert hb.lib().hs_decode_attn(C.byref(sh), 0.0, 0, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, hb._ptr(O), None) == -1
+    torch.cuda.synchronize()

@@ -50,6 +50,43 @@ def test_size_arithmetic_matches_paper(L):
     assert c == [128, 384, 0, 192, 192]
 
 
+def test_protected_tiles_in_counts(L):
+    sh = hb.make_shape(1, 32, 8, 32768)                          # T = 512
+    # sink 64 tokens + local window 256 tokens dense (Sec. V-A), everything else 2:4
+    c = hb.tile_counts(sh, hb.make_policy(dense_first_tiles=1, dense_last_tiles=4))
+    assert c == [0, 5, 507, 5, 507]
+    c = hb.tile_counts(sh, hb.make_policy(skip_frac=0.5, sparse_frac_v=0.5, dense_first_tiles=1, dense_last_tiles=4))
+    assert c == [253, 5, 254, 5 + 127, 127]
+    c = hb.tile_counts(sh, hb.make_policy(skip_frac=0.5, dense_first_tiles=400, dense_last_tiles=400))
+    assert c == [0, 512, 0, 512, 0]
+    cc = (C.c_int32 * 5)()
+    assert L.hs_tile_counts(C.byref(sh), C.byref(hb.make_policy(dense_first_tiles=-1)), cc) == -1
+    assert L.hs_tile_counts(C.byref(sh), C.byref(hb.make_policy(element_rule=2)), cc) == -1
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors have the size and field offsets the C compiler gives the header's structs."""
+    fields = {"hs_shape": hb.HsShape, "hs_policy": hb.HsPolicy, "hs_kv": hb.HsKV}
+    src = ['#include <stdio.h>', '#include <stddef.h>', '#include "hs.h"', 'int main(void) {']
+    for cname, cls in fields.items():
+        src.append(f'  printf("{cname} %zu", sizeof({cname}));')
+        for f in cls._fields_:
+            src.append(f'  printf(" %zu", offsetof({cname}, {f[0]}));')
+        src.append('  printf("\\n");')
+    src += ['  return 0;', '}']
+    c_file = tmp_path / "layout.c"
+    c_file.write_text("\n".join(src))
+    exe = tmp_path / "layout"
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(c_file), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    for line, (cname, cls) in zip(out, fields.items()):
+        tok = line.split()
+        assert tok[0] == cname
+        assert int(tok[1]) == C.sizeof(cls), cname
+        assert [int(x) for x in tok[2:]] == [getattr(cls, f[0]).offset for f in cls._fields_], cname
+
+
 def test_argument_errors(L):
     bad = hb.make_shape(1, 32, 8, 32768, D=64)
     c = (C.c_int32 * 5)()

@@ -202,6 +202,75 @@ def test_block_sparsity_by_pruning_loss_exact():
     assert (pv.map[0, 0][kept] < 0).all()
 
 
+def test_protected_end_tiles_stay_dense_and_outside_the_ranking():
+    """Sink and local-window tiles (Sec. V-A): dense whatever their scores, and the fractions
+    count over the tiles in between; the ranking of those is checked in exact arithmetic."""
+    K, V = _rand_kv(8, B=1, H=2, L=16 * 12, D=16)
+    # the protected tiles would otherwise be the first to be skipped: all zero
+    for X in (K, V):
+        X[0, :, :16 * 2] = 0
+        X[0, :, 16 * 9:] = 0
+    pk, pv, _ = orc.compress_kv(K, V, Bt=16, skip_frac=0.5, sparse_frac_k=1.0, sparse_frac_v=0.5,
+                                dense_first_tiles=2, dense_last_tiles=3)
+    for h in range(2):
+        assert (pk.map[0, h, :2] > 0).all() and (pk.map[0, h, 9:] > 0).all()
+        assert (pv.map[0, h, :2] > 0).all() and (pv.map[0, h, 9:] > 0).all()
+        mid = list(range(2, 9))
+        e, lv = {}, {}
+        for t in mid:
+            e[t] = sum(Fraction(float(x)) ** 2 for X in (K, V)
+                       for x in wl.bf16_bits_to_f32(X[0, h, 16 * t:16 * (t + 1)]).ravel())
+            tile = wl.bf16_bits_to_f32(V[0, h, 16 * t:16 * (t + 1)])        # [token, channel]
+            acc = Fraction(0)
+            for g in range(4):
+                for c in range(16):
+                    a = sorted(abs(float(x)) for x in tile[4 * g:4 * g + 4, c])
+                    acc += Fraction(a[0]) + Fraction(a[1])
+            lv[t] = acc
+        skipped = set(sorted(mid, key=lambda t: (e[t], t))[:3])               # floor(0.5 * 7)
+        assert set(np.nonzero(pk.map[0, h] == 0)[0].tolist()) == skipped
+        kept = [t for t in mid if t not in skipped]
+        assert (pk.map[0, h][kept] < 0).all()                                 # S_K = 1 over the 4 kept
+        v_sparse = set(sorted(kept, key=lambda t: (lv[t], t))[:2])            # floor(0.5 * 4)
+        assert set(np.nonzero(pv.map[0, h] < 0)[0].tolist()) == v_sparse
+    # protection wider than the sequence: everything dense, nothing to rank
+    pk, pv, _ = orc.compress_kv(K, V, Bt=16, skip_frac=0.5, dense_first_tiles=7, dense_last_tiles=9)
+    assert (pk.map > 0).all() and (pv.map > 0).all()
+    assert (orc.unpack_tensor(pk) == K).all() and (orc.unpack_tensor(pv) == V).all()
+
+
+def test_nonzero_rule_keeps_a_given_element_mask():
+    """Generic compressor of Sec. IV-B: input that already carries some 2:4 element mask (not the
+    magnitude one) packs and unpacks to itself bit for bit; the magnitude rule would not."""
+    rng = np.random.default_rng(9)
+    K, V = _rand_kv(9, B=1, H=2, L=32, D=16)
+    K[K == 0] = 0x3F80
+    V[V == 0] = 0x3F80
+    # random 2-of-4 masks along channels (K) and tokens (V), unrelated to magnitudes
+    pairs = np.array([m for m in itertools.product([0, 1], repeat=4) if sum(m) == 2], dtype=bool)
+    mk = pairs[rng.integers(0, 6, size=(1, 2, 32, 4))].reshape(1, 2, 32, 16)
+    mv = pairs[rng.integers(0, 6, size=(1, 2, 8, 16))]                        # [.., group, channel, 4]
+    mv = mv.transpose(0, 1, 2, 4, 3).reshape(1, 2, 32, 16)
+    Km, Vm = np.where(mk, K, 0).astype(np.uint16), np.where(mv, V, 0).astype(np.uint16)
+    # a group with a single survivor and an all-zero group, and a negative zero as "pruned"
+    Km[0, 0, 3, 0:4] = [0, 0x4000, 0, 0]
+    Km[0, 0, 3, 4:8] = 0
+    Km[0, 0, 4, 0:4] = [0x8000, 0x4000, 0x3F80, 0]
+    pk, pv, info = orc.compress_kv(Km, Vm, Bt=16, element_rule="nonzero")
+    Ku, Vu = orc.unpack_tensor(pk), orc.unpack_tensor(pv)
+    Kw = Km.copy()
+    Kw[0, 0, 4, 0] = 0x8000 if info["mask_k"][0, 0, 4, 0] else 0              # -0 dropped -> stored as +0
+    assert not info["mask_k"][0, 0, 4, 0]
+    assert (Ku == Kw).all() and (Vu == Vm).all()
+    assert (info["mask_k"] | ~mk)[0, 1].all() and (info["mask_v"] | ~mv).all()  # given survivors all kept
+    assert info["mask_k"].reshape(-1, 4).sum(-1).tolist() == [2] * (info["mask_k"].size // 4)
+    # single survivor: filled up with the leftmost zero; empty group: positions 0 and 1
+    assert info["mask_k"][0, 0, 3, 0:8].tolist() == [True, True, False, False, True, True, False, False]
+    # the magnitude rule on the unmasked data does not reproduce the given mask
+    pk2, _, info2 = orc.compress_kv(K, V, Bt=16)
+    assert (info2["mask_k"] != mk).any()
+
+
 # ---------------------------------------------------------------- attention
 def _sdpa(Qf, Kf, Vf, mask=None, causal=False):
     """Independent library routine: torch CPU scaled_dot_product_attention in fp64."""
