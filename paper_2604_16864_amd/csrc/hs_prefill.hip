@@ -2,17 +2,14 @@
 // the first, possibly 2:4-sparse, operand of the matrix instruction) with the mixed
 // dense/sparse dispatch of Sec. III-C-2, online softmax, and tile skipping.
 //
-// Work decomposition: a "slab" is 64 consecutive query positions of one query head; a wave
-// owns one slab (4 column blocks of 16 queries), keeps Q^T (B operand of GEMM1), the
-// running softmax state and O^T (128 x 64 fp32) in registers for the whole kernel.  The 4
-// waves of a workgroup take 4 consecutive slabs in (position-tile, head-in-group) order, so
-// for a GQA group of 4 they are the 4 query heads of one 64-position tile and share every
-// KV tile, which is staged once per workgroup in LDS (double buffered, prefetched through
-// registers one tile ahead).  Pools are stored in operand order, so LDS reads are
-// conflict-free 16-byte-per-lane reads and GEMM1's accumulators become GEMM2's B operand
-// in place (no re-layout step).
-#include <stdlib.h>
-
+// Work decomposition: a "slab" is 16 NB consecutive query positions of one query head (NB = 2:
+// 32 positions); a wave owns one slab, keeps Q^T (B operand of GEMM1), the running softmax
+// state and O^T (128 x 16 NB fp32) in registers for the whole kernel.  The 4 waves of a
+// workgroup take 4 consecutive slabs in (position-tile, head-in-group) order, so for a GQA
+// group of 4 they are the 4 query heads of one position tile and share every KV tile, which is
+// copied once per workgroup into an LDS ring by direct global->LDS loads issued up to 3 tiles
+// ahead.  Pools are stored in operand order, so LDS reads are conflict-free 16-byte-per-lane
+// reads and GEMM1's accumulators become GEMM2's B operand in place (no re-layout step).
 #include "hs_common.h"
 
 // Wave priority per phase.  Two waves share a SIMD; letting the one that is in its vector-ALU
@@ -58,59 +55,88 @@ __device__ __forceinline__ void split_hi_lo(float p0, float p1, const SplitConst
   lo = pack_bf16(r0, r1);
 }
 
-constexpr int kBufBytes = 32768;  // one stage: K region 16 KiB + V region 16 KiB
+// LDS staging ring.  One stage holds one tile: a K region then a V region, each 9 KiB (8 KiB of
+// values + 1 KiB of metadata) when every tile of that tensor is 2:4 and 16 KiB otherwise.  Two
+// workgroups share a compute unit's 160 KiB, so a ring may take 80 KiB: 4 stages when both tensors
+// are 2:4 (tiles are requested 3 iterations before use), 3 when one is, 2 otherwise.
+template <int KM> constexpr int region_bytes() { return KM == 0 ? 9216 : 16384; }
+template <int KM, int VM> constexpr int stage_bytes() { return region_bytes<KM>() + region_bytes<VM>(); }
+#ifndef HS_MAX_STAGES
+#define HS_MAX_STAGES 4  // at most 2 tiles in flight behind the next one (see stage_wait)
+#endif
+template <int KM, int VM> constexpr int n_stages() {
+  constexpr int fit = 81920 / stage_bytes<KM, VM>();
+  return fit < HS_MAX_STAGES ? fit : HS_MAX_STAGES;
+}
+// fewest direct-to-LDS loads any of the 4 waves issues for one tile (chunks / 4; the metadata
+// chunks go to waves 0 and 1 on top of that)
+template <int KM, int VM> constexpr int min_loads_per_tile() { return (KM == 1 ? 4 : 2) + (VM == 1 ? 4 : 2); }
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Copy one tile (K and V operands) from its pool slots into an LDS stage with direct
-// global->LDS loads (no staging registers): a chunk is 64 lanes x 16 B = 1 KiB, lane l's
-// 16 bytes land at chunk base + 16 l, which is the order the pools are stored in.  The 4
-// waves share the chunks round-robin.  2:4 tile: 8 value chunks + 1 metadata chunk per
-// tensor (value chunks at 0..8 KiB, metadata at 8 KiB of the tensor's region); dense: 16.
+// One direct global->LDS load of 64 lanes x 16 B: lane l's bytes come from gbase + 16 l and land
+// at LDS address lds_addr + 16 l.  Written as inline assembly on purpose: the compiler treats
+// the built-in form as a vector-memory write to LDS that any later LDS read may alias, and puts a
+// full vmcnt(0) wait in front of the first such read, i.e. right after the prefetch is issued.
+// Completion is tracked by hand instead (stage_wait + workgroup barrier before a stage is read).
+// gbase and lds_addr are wave-uniform.
+__device__ __forceinline__ void lds_dma16(uint32_t lds_addr, const uint8_t* gbase, uint32_t lane_off) {
+  const uint64_t g = (uint64_t)gbase;
+  const uint32_t glo = __builtin_amdgcn_readfirstlane((uint32_t)g);
+  const uint32_t ghi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
+  const uint64_t gs = ((uint64_t)ghi << 32) | glo;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(lane_off), "s"(gs)
+               : "memory", "m0");
+}
+
+// Copy one tile (K and V operands) from its pool slots into the LDS stage at LDS address `stage`:
+// a chunk is 64 lanes x 16 B = 1 KiB, stored in the pools in the order the lanes consume it.  The
+// 4 waves share the chunks round-robin.  2:4 tile: 8 value chunks + 1 metadata chunk per tensor
+// (value chunks at 0..8 KiB, metadata at 8 KiB of the tensor's region); dense: 16 chunks.
 template <int KM, int VM>
-__device__ __forceinline__ void stage_issue(uint8_t* buf, const hs_kv_dev& kv, int64_t row, int mk, int mv, int w,
-                                            int l) {
+__device__ __forceinline__ void stage_issue(uint32_t stage, const hs_kv_dev& kv, int64_t row, int mk, int mv, int w,
+                                            uint32_t lane_off) {
   const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
   const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
-  const uint8_t *kd, *km = nullptr, *vd, *vm = nullptr;
-  int nk, nv;
+  constexpr uint32_t voff = region_bytes<KM>();
   if (k_sparse) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
-    kd = kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
-    km = kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES;
-    nk = 8;
+    const uint8_t* kd = kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES + w * 1024;
+#pragma unroll
+    for (int i = 0; i < 2; i++) lds_dma16(stage + (w + 4 * i) * 1024, kd + i * 4096, lane_off);
+    if (w == 0) lds_dma16(stage + 8192, kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES, lane_off);
   } else {
-    kd = kv.k_dense + (row * kv.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
-    nk = 16;
+    const uint8_t* kd = kv.k_dense + (row * kv.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES + w * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; i++) lds_dma16(stage + (w + 4 * i) * 1024, kd + i * 4096, lane_off);
   }
   if (v_sparse) {
     const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
-    vd = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
-    vm = kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES;
-    nv = 8;
+    const uint8_t* vd = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES + w * 1024;
+#pragma unroll
+    for (int i = 0; i < 2; i++) lds_dma16(stage + voff + (w + 4 * i) * 1024, vd + i * 4096, lane_off);
+    if (w == 1) lds_dma16(stage + voff + 8192, kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES, lane_off);
   } else {
-    vd = kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
-    nv = 16;
+    const uint8_t* vd = kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES + w * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; i++) lds_dma16(stage + voff + (w + 4 * i) * 1024, vd + i * 4096, lane_off);
   }
-  for (int ch = w; ch < nk; ch += 4)
-    __builtin_amdgcn_global_load_lds((gptr_t)(kd + ch * 1024 + l * 16), (lptr_t)(buf + ch * 1024), 16, 0, 0);
-  for (int ch = w; ch < nv; ch += 4)
-    __builtin_amdgcn_global_load_lds((gptr_t)(vd + ch * 1024 + l * 16), (lptr_t)(buf + 16384 + ch * 1024), 16, 0, 0);
-  if (k_sparse && w == 0)
-    __builtin_amdgcn_global_load_lds((gptr_t)(km + l * 16), (lptr_t)(buf + 8192), 16, 0, 0);
-  if (v_sparse && w == 1)
-    __builtin_amdgcn_global_load_lds((gptr_t)(vm + l * 16), (lptr_t)(buf + 16384 + 8192), 16, 0, 0);
 }
 
-// all of this wave's direct-to-LDS loads have landed (vmcnt = 0; other counters untouched)
-__device__ __forceinline__ void stage_wait() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-// next tile index > j (and <= jmax) whose map entry is not 0, or -1
-__device__ __forceinline__ int next_active(const int32_t* km, int j, int jmax) {
-  for (int t = j + 1; t <= jmax; t++)
-    if (km[t] != 0) return t;
-  return -1;
+// Wait until all but the newest `tiles_in_flight` tiles' worth of this wave's direct-to-LDS loads
+// have landed (loads complete in order).  PER = loads per tile that every wave issues at least.
+// Immediate: vmcnt in bits 3..0 and 15..14, the other counters left at their maxima.
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+template <int PER>
+__device__ __forceinline__ void stage_wait(int tiles_in_flight) {
+  static_assert(2 * PER <= 63, "vmcnt range");
+  switch (tiles_in_flight) {
+    case 0: __builtin_amdgcn_s_waitcnt(vmcnt_imm(0)); break;
+    case 1: __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER)); break;
+    default: __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER)); break;
+  }
 }
 
 union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the dense 16x16x32 one
@@ -123,7 +149,7 @@ union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the de
 // (the specialised all-dense / all-sparse kernels of Sec. IV-C-3, chosen per tensor so that the
 // keys-dense / values-2:4 setting of Sec. V-A carries no dynamic dispatch).
 // NB: column blocks (of 16 queries) per wave: a wave owns a slab of 16*NB query positions of one
-// head.  NB = 4 keeps 1 wave per SIMD (O^T alone is 128 registers); NB = 2 fits 2 waves per SIMD.
+// head.  NB = 2 fits 2 waves per SIMD (NB = 4, 1 wave per SIMD, measured 1.3-1.4x slower).
 template <int KM, int VM, int NB>
 __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, int Hkv, int T, int Lq, int off,
                                                                       float scale_log2, int causal,
@@ -131,7 +157,17 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
                                                                       uint16_t* __restrict__ O,
                                                                       float* __restrict__ LSE) {
   constexpr int QS = 16 * NB;  // query positions per slab
-  __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kBufBytes];
+  constexpr int NS = n_stages<KM, VM>(), D = NS - 1;  // ring size, prefetch distance in tiles
+  // MID: the per-tile barrier sits between softmax and GEMM2 instead of at the end of the
+  // iteration, so that the next tile's K operands can be fetched from LDS while GEMM2 runs.  Needs
+  // the next tile requested at least two iterations ahead (NS >= 3), which all-2:4 keys give.
+  constexpr bool MID = KM == 0 && VM != 2;  // (mixed V on top of the K prefetch runs out of registers)
+  static_assert(!MID || NS >= 3, "mid-iteration barrier needs a ring of 3");
+  // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
+  // already holds the registers (both together spill; measured no gain there)
+  constexpr bool V_EARLY = VM == 0 && !MID;
+  constexpr int kStage = stage_bytes<KM, VM>();
+  __shared__ __attribute__((aligned(16))) uint8_t lds[NS * kStage];
   const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, scalar: branches on it stay scalar
   const int G = Hq / Hkv;
@@ -179,29 +215,80 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 
   // Map entries steer branches around matrix instructions, which ignore the EXEC mask: they are
   // forced into scalar registers so that those branches are scalar too.
-  int j = next_active(km, -1, jmax_wg);
-  int mk = 0, mv = 0;
-  if (j >= 0) {
-    mk = __builtin_amdgcn_readfirstlane(km[j]); mv = __builtin_amdgcn_readfirstlane(vm[j]);
-    stage_issue<KM, VM>(lds, kv, row, mk, mv, w, l);
-  }
-  stage_wait();
-  __syncthreads();
-  int buf = 0;
-  while (j >= 0) {
-    // prefetch the next visible tile into the other stage; it is waited for at the end of
-    // this iteration, after the arithmetic on the current one
-    const int jn = next_active(km, j, jmax_wg);
-    int mkn = 0, mvn = 0;
-    if (jn >= 0) {
-      mkn = __builtin_amdgcn_readfirstlane(km[jn]); mvn = __builtin_amdgcn_readfirstlane(vm[jn]);
-      stage_issue<KM, VM>(lds + (buf ^ 1) * kBufBytes, kv, row, mkn, mvn, w, l);
+  // tj[i]: the i-th visible tile from the current one on (-1: none), tk / tv: its map entries;
+  // tile tj[i] sits in (or is on its way to) stage (st + i) % NS.
+  int tj[NS], tk[NS], tv[NS];
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds);
+  const uint32_t lane_off = 16 * l;
+  // The maps are read 64 tiles at a time, lane t of the window holding the entries of tile
+  // wbase + t; entries are picked out with readlane and the next visible tile is found on the
+  // ballot of "entry != 0".  This keeps map reads (vector loads, which complete in order with
+  // the tile loads and would otherwise have to wait for them) off the per-tile path.
+  int wbase = 0;
+  int32_t wk = 0, wv = 0;
+  uint64_t wact = 0;
+  auto window_load = [&](int base) {
+    const int t = base + l;
+    wk = t <= jmax_wg ? km[t] : 0;
+    wv = t <= jmax_wg ? vm[t] : 0;
+    wact = __ballot(wk != 0);
+    wbase = base;
+  };
+  auto next_visible = [&](int j) -> int {  // first tile > j (and <= jmax_wg) that is not skipped, or -1
+    for (;;) {
+      const int rel = j + 1 - wbase;  // 0 .. 64
+      const uint64_t m = rel < 64 ? (wact >> rel) : 0;
+      if (m != 0) return j + 1 + __builtin_ctzll(m);
+      if (wbase + 64 > jmax_wg) return -1;
+      window_load(wbase + 64);
+      j = wbase - 1;
     }
-    if (valid && j <= jmax_w) {
-      const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
-      const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
-      const uint4* kl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes);
-      const uint4* vl = reinterpret_cast<const uint4*>(lds + buf * kBufBytes + 16384);
+  };
+  window_load(0);
+#pragma unroll
+  for (int i = 0; i < D; i++) {
+    tj[i] = i == 0 ? next_visible(-1) : (tj[i - 1] >= 0 ? next_visible(tj[i - 1]) : -1);
+    tk[i] = tv[i] = 0;
+    if (tj[i] >= 0) {
+      tk[i] = __builtin_amdgcn_readlane(wk, tj[i] - wbase); tv[i] = __builtin_amdgcn_readlane(wv, tj[i] - wbase);
+      stage_issue<KM, VM>(lds_base + i * kStage, kv, row, tk[i], tv[i], w, lane_off);
+    }
+  }
+  stage_wait<1>(0);
+  __syncthreads();
+  int st = 0;
+  // 2:4 operands of the sparse instruction are fetched from LDS a phase ahead of their use:
+  // V of the current tile before the softmax, K of the next tile before GEMM2 (MID mode).
+  uint4 ak[8], kix, av[8], vix;
+  auto k_fetch = [&](int stage) {
+    const uint4* kl = reinterpret_cast<const uint4*>(lds + stage * kStage);
+#pragma unroll
+    for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];
+    kix = kl[512 + l];
+  };
+  auto request = [&]() {  // look up the tile D ahead and start its copy into the stage D ahead
+    tj[D] = tj[D - 1] >= 0 ? next_visible(tj[D - 1]) : -1;
+    tk[D] = tv[D] = 0;
+    if (tj[D] >= 0) {
+      tk[D] = __builtin_amdgcn_readlane(wk, tj[D] - wbase); tv[D] = __builtin_amdgcn_readlane(wv, tj[D] - wbase);
+      int sd = st + D;
+      if (sd >= NS) sd -= NS;
+      stage_issue<KM, VM>(lds_base + sd * kStage, kv, row, tk[D], tv[D], w, lane_off);
+    }
+  };
+  if (MID && valid && tj[0] >= 0) k_fetch(0);
+  while (tj[0] >= 0) {
+    const int j = tj[0], mk = tk[0], mv = tv[0];
+    // END mode: request the tile D ahead now; its stage held the tile of the previous iteration,
+    // which every wave has left behind (barrier at the end of that iteration)
+    if (!MID) request();
+    const bool ok = valid && j <= jmax_w;
+    const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
+    const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
+    const uint4* kl = reinterpret_cast<const uint4*>(lds + st * kStage);
+    const uint4* vl = reinterpret_cast<const uint4*>(lds + st * kStage + region_bytes<KM>());
+    B16 ph[NB], pl[NB];
+    if (ok) {
       // ---------------- GEMM1: S^T[64 tokens x 16 NB queries] ----------------
       __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
       f32x4_t s[4][NB];
@@ -210,10 +297,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) s[m][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
       if (k_sparse) {
-        uint4 ak[8];
-#pragma unroll
-        for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];
-        const uint4 kix = kl[512 + l];
+        if (!MID) k_fetch(st);
         const int kidx[4] = {(int)kix.x, (int)kix.y, (int)kix.z, (int)kix.w};
         // 4 NB independent accumulators between the two instructions that share one
 #pragma unroll
@@ -239,6 +323,12 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
               s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[st]), as_bf16x8(qb[nb][st >> 1].q[st & 1]), s[m][nb], 0, 0, 0);
         }
       }
+      if (V_EARLY) {  // V operands: on their way while the softmax runs
+#pragma unroll
+        for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
+        vix = vl[512 + l];
+        __builtin_amdgcn_sched_barrier(0);
+      }
       __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
       // causal mask inside a tile that reaches past the slab's first query
       if (causal && HS_BT * j + HS_BT - 1 > qpos + off) {
@@ -259,7 +349,6 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       // O / l and LSE = m_run + log2(l) do not depend on which reference was used.
       // P goes through the matrix unit as two bf16 terms (hi + remainder): a single bf16 P alone
       // costs ~1.3e-3 mean relative error on the output, on top of the bf16 rounding of O itself.
-      B16 ph[NB], pl[NB];
       float psum[NB];
       auto softmax_tile = [&]() {
 #pragma unroll
@@ -307,12 +396,30 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       }
 #pragma unroll
       for (int nb = 0; nb < NB; nb++) l_run[nb] += psum[nb];
+    }
+    if (MID) {
+      // The next tile must have landed in full (own loads, then everybody's: barrier) before its K
+      // operands are fetched; tiles requested after it may still be in flight.  The stage of the
+      // previous tile is free from here on (all of its reads precede this barrier).
+      int later = 0;
+#pragma unroll
+      for (int i = 2; i < D; i++) later += tj[i] >= 0;
+      stage_wait<min_loads_per_tile<KM, VM>()>(later);
+      __syncthreads();
+      request();
+      if (valid && tj[1] >= 0) {
+        k_fetch(st + 1 == NS ? 0 : st + 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (ok) {
       __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
       if (v_sparse) {
-        uint4 av[8];
+        if (!V_EARLY) {
 #pragma unroll
-        for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
-        const uint4 vix = vl[512 + l];
+          for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
+          vix = vl[512 + l];
+        }
         const int vidx[4] = {(int)vix.x, (int)vix.y, (int)vix.z, (int)vix.w};
 #pragma unroll
         for (int t2 = 0; t2 < 2; t2++)  // first the upper-half term of every block, then the remainder
@@ -343,10 +450,17 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       }
     }
     __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
-    stage_wait();
-    __syncthreads();
-    j = jn; mk = mkn; mv = mvn;
-    buf ^= 1;
+    if (!MID) {
+      // the next tile must have landed; the ones requested after it may still be in flight
+      int later = 0;
+#pragma unroll
+      for (int i = 2; i <= D; i++) later += tj[i] >= 0;
+      stage_wait<min_loads_per_tile<KM, VM>()>(later);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < D; i++) { tj[i] = tj[i + 1]; tk[i] = tk[i + 1]; tv[i] = tv[i + 1]; }
+    st = st + 1 == NS ? 0 : st + 1;
   }
 
   // ---------------- epilogue: O = O^T / l, LSE ----------------
@@ -388,12 +502,7 @@ hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale,
   const int Lq = Tq * HS_BT;
   const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
   const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
-  // HS_PREFILL_NB=4 selects 64-query slabs at 1 wave per SIMD for the two uniform settings
-  // (kept for comparison; 32-query slabs at 2 waves per SIMD measured 1.3-1.4x faster)
-  static const int nb_env = [] { const char* e = getenv("HS_PREFILL_NB"); return e ? atoi(e) : 0; }();
 #define HS_GO(KM_, VM_) return launch_prefill<KM_, VM_, 2>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st)
-  if (nb_env == 4 && km == 0 && vm == 0) return launch_prefill<0, 0, 4>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st);
-  if (nb_env == 4 && km == 1 && vm == 1) return launch_prefill<1, 1, 4>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st);
   switch (km * 3 + vm) {
     case 0: HS_GO(0, 0);
     case 1: HS_GO(0, 1);
