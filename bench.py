@@ -172,6 +172,36 @@ def extra_legs(hb, torch, Q, K, V, qd, sh, args):
     for r in pf:
         r["speedup_vs_dense"] = pf[0]["prefill_ms"] / r["prefill_ms"]
     res["prefill_64k"] = pf
+    del K4, V4, Q4, O4, ws4
+    torch.cuda.empty_cache()
+    # (4) the shape of the paper's own kernel benchmarks (Sec. V-B: batch 8, 32K tokens), 32/8 heads: context only
+    B5, L5 = 8, 32768
+    sh5 = hb.make_shape(B5, Hq, Hkv, L5)
+    K5 = torch.randn((B5, Hkv, L5, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    V5 = torch.randn((B5, Hkv, L5, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Q5 = torch.randn((B5, Hq, L5, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    q5 = Q5[:, :, -1, :].contiguous()
+    O5 = torch.empty_like(Q5)
+    o5 = torch.empty_like(q5)
+    ws5 = torch.empty(hb.workspace_bytes(sh5, 0), dtype=torch.uint8, device="cuda")
+    n5 = hb.decode_auto_splits(sh5)
+    wsd5 = torch.empty(hb.workspace_bytes(sh5, 2, n5), dtype=torch.uint8, device="cuda")
+    flops5 = 4.0 * 128 * Hq * B5 * (L5 * (L5 + 1) / 2.0)
+    b8 = []
+    for name5, kw in (("dense", dict(sparse_frac_k=0.0, sparse_frac_v=0.0)), ("sk0_sv1", dict(sparse_frac_k=0.0)), ("2:4", dict())):
+        p5 = hb.make_policy(**kw)
+        c5 = hb.tile_counts(sh5, p5)
+        kv5 = hb.compress_kv(sh5, p5, K5, V5, workspace=ws5)
+        t_p = _time(torch, lambda i: hb.prefill_attn(sh5, Q5, kv5, causal=True, want_lse=False, out=O5), 2)
+        t_d = _time(torch, lambda i: hb.decode_attn(sh5, q5, kv5, n_splits=n5, want_lse=False, out=o5, workspace=wsd5), 10, warm=2)
+        nb = packed_bytes(B5, Hkv, L5 // 64, c5)
+        b8.append({"case": name5, "prefill_ms": t_p * 1e3, "prefill_dense_equiv_TFLOPs": flops5 / t_p / 1e12,
+                   "decode_us": t_d * 1e6, "decode_GBps": nb / t_d / 1e9, "hbm_frac": nb / t_d / 1e9 / HBM_PEAK_GBPS})
+        del kv5
+    for r in b8:
+        r["prefill_speedup_vs_dense"] = b8[0]["prefill_ms"] / r["prefill_ms"]
+        r["decode_speedup_vs_dense"] = b8[0]["decode_us"] / r["decode_us"]
+    res["paper_kernel_shape_b8_32k"] = b8
     return res
 
 
