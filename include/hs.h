@@ -177,6 +177,19 @@ HS_API int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
                    const void* Q, const hs_kv* kv, void* O, float* LSE,
                    void* workspace, void* stream);
 
+/* Decode attention over the packed cache plus a dense tail: the tokens generated since the
+ * last full tile was compressed are not in the pools yet; they are attended to as they are
+ * (recent tokens stay dense, Sec. V-A; the cache itself only ever holds whole tiles, Sec.
+ * III-B).  tail_k, tail_v: device, bf16 [B, Hkv, HS_TILE, D] contiguous, rows 0..tail_len-1
+ * valid, 0 <= tail_len <= HS_TILE (tail_len == 0: pointers may be NULL and the call equals
+ * hs_decode_attn).  The query sees every cached token of a non-skipped tile and the tail_len
+ * tail tokens.  The tail is one more split: workspace must hold
+ * hs_workspace_bytes(op 2, n + 1) bytes, n = n_splits or, for n_splits == 0,
+ * hs_decode_auto_splits.  Everything else as hs_decode_attn. */
+HS_API int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_splits,
+                        const void* Q, const hs_kv* kv, const void* tail_k, const void* tail_v,
+                        int32_t tail_len, void* O, float* LSE, void* workspace, void* stream);
+
 /* hs_decode_attn in separable phases, for benchmarking and profiling: `phases` bit 0 launches
  * the split-KV kernel (reads Q and the cache, writes the partials into `workspace`), bit 1
  * launches the merge kernel (reads the partials, writes O and LSE).  phases == 3 is

@@ -388,14 +388,40 @@ def attention_rows(Q_bits, pk, pv, rows, causal, scale=None, q_offset=None):
     return O, LSE
 
 
-def attention_decode(q_bits, pk, pv, scale=None):
+def attention_decode(q_bits, pk, pv, scale=None, tail_k=None, tail_v=None, tail_len=0):
     """One new query token per (b, hq) against the whole cache.  q_bits [B, Hq, D].
-    Returns (O [B, Hq, D] fp64, LSE [B, Hq] fp64)."""
+    Returns (O [B, Hq, D] fp64, LSE [B, Hq] fp64).
+
+    tail_k, tail_v (bf16 bits [B, Hkv, >= tail_len, D]): recent tokens that are not in the
+    packed cache yet; they are kept as they are (the local window stays dense, Sec. V-A)
+    and the query sees the first tail_len of them after the cache.
+    """
     q_bits = np.asarray(q_bits, dtype=np.uint16)
     B, Hq, D = q_bits.shape
-    rows = [(b, h, 0) for b in range(B) for h in range(Hq)]
-    O, LSE = attention_rows(q_bits[:, :, None, :], pk, pv, rows, causal=False, scale=scale)
-    return O.reshape(B, Hq, D), LSE.reshape(B, Hq)
+    if tail_len == 0:
+        rows = [(b, h, 0) for b in range(B) for h in range(Hq)]
+        O, LSE = attention_rows(q_bits[:, :, None, :], pk, pv, rows, causal=False, scale=scale)
+        return O.reshape(B, Hq, D), LSE.reshape(B, Hq)
+    Hkv = pk.map.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    Kd = bf16_to_f64(unpack_tensor(pk))
+    Vd = bf16_to_f64(unpack_tensor(pv))
+    Kt = bf16_to_f64(np.asarray(tail_k, dtype=np.uint16)[:, :, :tail_len])
+    Vt = bf16_to_f64(np.asarray(tail_v, dtype=np.uint16)[:, :, :tail_len])
+    tok_visible = np.repeat(pk.map != 0, pk.Bt, axis=-1)
+    O = np.zeros((B, Hq, D), dtype=np.float64)
+    LSE = np.zeros((B, Hq), dtype=np.float64)
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // G
+            vis = tok_visible[b, h]
+            Kall = np.concatenate([Kd[b, h][vis], Kt[b, h]], axis=0)
+            Vall = np.concatenate([Vd[b, h][vis], Vt[b, h]], axis=0)
+            s = (Kall @ bf16_to_f64(q_bits[b, hq])) * scale
+            O[b, hq], LSE[b, hq] = _softmax_av(s, Vall)
+    return O, LSE
 
 
 # ----------------------------------------------------------------------------

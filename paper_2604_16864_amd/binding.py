@@ -53,6 +53,8 @@ EXPORTS = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_decode_attn_tail": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
+                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn_phases": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV),
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
 }
@@ -208,16 +210,28 @@ def prefill_attn(shape, Q, kv, causal=True, scale=0.0, want_lse=True, out=None, 
     return O, lse
 
 
-def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, lse=None, workspace=None, phases=3):
+def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, lse=None, workspace=None, phases=3,
+                tail_k=None, tail_v=None, tail_len=None):
     """Q: bf16 [B, Hq, D] contiguous.  Returns (O bf16 [B, Hq, D], LSE fp32 [B, Hq] or None).
-    phases: 3 = whole call; 1 = split-KV kernel only, 2 = merge kernel only (benchmarking)."""
+    phases: 3 = whole call; 1 = split-KV kernel only, 2 = merge kernel only (benchmarking).
+    tail_k, tail_v (bf16 [B, Hkv, 64, D]) with tail_len: dense tail of not yet compressed tokens."""
     assert Q.dtype == torch.bfloat16 and Q.is_contiguous() and Q.is_cuda
     O = torch.empty_like(Q) if out is None else out
     if lse is None and want_lse:
         lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
+    kvs = kv.struct()
+    if tail_len is not None:
+        assert phases == 3
+        n = n_splits if n_splits else decode_auto_splits(shape)
+        if workspace is None:
+            workspace = _workspace(workspace_bytes(shape, 2, n + 1), Q.device)
+        for t in (tail_k, tail_v):
+            assert t is None or (t.dtype == torch.bfloat16 and t.is_contiguous() and tuple(t.shape) == (shape.B, shape.Hkv, 64, shape.D))
+        _check(lib().hs_decode_attn_tail(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(tail_k),
+                                         _ptr(tail_v), int(tail_len), _ptr(O), _ptr(lse), _ptr(workspace), _stream()))
+        return O, lse
     if workspace is None:
         workspace = _workspace(workspace_bytes(shape, 2, n_splits), Q.device)
-    kvs = kv.struct()
     if phases == 3:
         _check(lib().hs_decode_attn(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(O),
                                     _ptr(lse), _ptr(workspace), _stream()))

@@ -96,6 +96,35 @@ int check_kv(const hs_shape* s, const hs_kv* kv) {
 
 constexpr int kSelectMaxTiles = 65536;  // O(T^2) ranking: 4M tokens per row
 
+// shared body of the decode entry points; tail_len < 0: no dense tail
+int decode_common(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
+                  const void* tail_k, const void* tail_v, int tail_len, void* O, float* LSE, void* workspace,
+                  void* stream, int phases) {
+  if (phases < 1 || phases > 3) return HS_EINVAL;
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, kv);
+  if (rc != HS_OK) return rc;
+  if (Q == nullptr || O == nullptr || workspace == nullptr) return HS_EINVAL;
+  if (((uintptr_t)Q | (uintptr_t)workspace) & 15u) return HS_EINVAL;
+  if (n_splits < 0 || n_splits > 65535) return HS_EINVAL;
+  if (!(scale >= 0.f)) return HS_EINVAL;
+  if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
+  if (n_splits == 0) n_splits = hs_decode_auto_splits(shape);
+  if (kv->uniform) {
+    const int T = shape->L / HS_BT;
+    const bool k_ok = (kv->cap_dense_k == 0 && kv->cap_sparse_k >= T) || (kv->cap_sparse_k == 0 && kv->cap_dense_k >= T);
+    const bool v_ok = (kv->cap_dense_v == 0 && kv->cap_sparse_v >= T) || (kv->cap_sparse_v == 0 && kv->cap_dense_v >= T);
+    if (!k_ok || !v_ok) return HS_EINVAL;
+  }
+  const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
+                                        (const uint16_t*)Q, hs_make_kv_dev(kv), (const uint16_t*)tail_k,
+                                        (const uint16_t*)tail_v, tail_len, (uint16_t*)O, LSE, (float*)workspace,
+                                        (hipStream_t)stream, phases);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -299,28 +328,16 @@ int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const v
 
 int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
                           float* LSE, void* workspace, void* stream, int phases) {
-  if (phases < 1 || phases > 3) return HS_EINVAL;
-  int rc = check_shape(shape);
-  if (rc != HS_OK) return rc;
-  rc = check_kv(shape, kv);
-  if (rc != HS_OK) return rc;
-  if (Q == nullptr || O == nullptr || workspace == nullptr) return HS_EINVAL;
-  if (((uintptr_t)Q | (uintptr_t)workspace) & 15u) return HS_EINVAL;
-  if (n_splits < 0 || n_splits > 65535) return HS_EINVAL;
-  if (!(scale >= 0.f)) return HS_EINVAL;
-  if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
-  if (n_splits == 0) n_splits = hs_decode_auto_splits(shape);
-  if (kv->uniform) {
-    const int T = shape->L / HS_BT;
-    const bool k_ok = (kv->cap_dense_k == 0 && kv->cap_sparse_k >= T) || (kv->cap_sparse_k == 0 && kv->cap_dense_k >= T);
-    const bool v_ok = (kv->cap_dense_v == 0 && kv->cap_sparse_v >= T) || (kv->cap_sparse_v == 0 && kv->cap_dense_v >= T);
-    if (!k_ok || !v_ok) return HS_EINVAL;
-  }
-  const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
-                                        (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
-                                        (float*)workspace, (hipStream_t)stream, phases);
-  if (e != hipSuccess) return hip_fail(e);
-  return HS_OK;
+  return decode_common(shape, scale, n_splits, Q, kv, nullptr, nullptr, -1, O, LSE, workspace, stream, phases);
+}
+
+int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
+                        const void* tail_k, const void* tail_v, int32_t tail_len, void* O, float* LSE, void* workspace,
+                        void* stream) {
+  if (tail_len < 0 || tail_len > HS_BT) return HS_EINVAL;
+  if (tail_len > 0 && (tail_k == nullptr || tail_v == nullptr)) return HS_EINVAL;
+  if (((uintptr_t)tail_k | (uintptr_t)tail_v) & 15u) return HS_EINVAL;
+  return decode_common(shape, scale, n_splits, Q, kv, tail_k, tail_v, tail_len, O, LSE, workspace, stream, 3);
 }
 
 }  // extern "C"

@@ -81,7 +81,10 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
                           int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
+// tail_len < 0: no tail slot; tail_len >= 0: one extra partial per query head, computed from the
+// dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D])
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
-                            hs_kv_dev kv, uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases);
+                            hs_kv_dev kv, const uint16_t* tail_k, const uint16_t* tail_v, int tail_len,
+                            uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases);
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
                              hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st);

@@ -357,6 +357,71 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(int n_splits, const f
   }
 }
 
+
+__device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Partial for the dense tail (at most one tile of not yet compressed tokens): plain fp32
+// attention of the G query heads of one kv head over tail_len tokens, written as split `slot`.
+// One workgroup per (kv head, b); thread t: phase 1 token t%64 for heads t/64 and t/64 + 4,
+// phase 3 channel t%128 for heads t/128, t/128 + 2, ...
+__global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float scale_log2, int n_slots, int slot,
+                                                          int tail_len, const uint16_t* __restrict__ Q,
+                                                          const uint16_t* __restrict__ TK,
+                                                          const uint16_t* __restrict__ TV, float* __restrict__ ws_o,
+                                                          float* __restrict__ ws_l) {
+  __shared__ float sq[8][HS_D];
+  __shared__ float sp[8][HS_BT];
+  __shared__ float sl_[8];
+  const int tid = threadIdx.x, hkv = blockIdx.x, b = blockIdx.y;
+  const int G = Hq / Hkv;
+  const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;
+  const uint16_t* tk = TK + ((int64_t)b * Hkv + hkv) * HS_BT * HS_D;
+  const uint16_t* tv = TV + ((int64_t)b * Hkv + hkv) * HS_BT * HS_D;
+  for (int i = tid; i < G * HS_D; i += 256) sq[i / HS_D][i % HS_D] = bf16_val(Q[hq0 * HS_D + i]);
+  __syncthreads();
+  {  // scores (log2 units) and softmax numerators: wave w serves heads w and w + 4, lane = token
+    const int tok = tid & 63, w = tid >> 6;
+    for (int g = w; g < G; g += 4) {
+      float sc = -INFINITY;
+      if (tok < tail_len) {
+        float acc = 0.f;
+        for (int c = 0; c < HS_D; c += 8) {
+          const uint4 kk = *reinterpret_cast<const uint4*>(tk + (int64_t)tok * HS_D + c);
+          const uint32_t wds[4] = {kk.x, kk.y, kk.z, kk.w};
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            acc = fmaf(__uint_as_float(wds[e] << 16), sq[g][c + 2 * e], acc);
+            acc = fmaf(__uint_as_float(wds[e] & 0xffff0000u), sq[g][c + 2 * e + 1], acc);
+          }
+        }
+        sc = acc * scale_log2;
+      }
+      float mx = sc;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+      const float p = tok < tail_len ? __builtin_amdgcn_exp2f(sc - mx) : 0.f;
+      float l = p;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+      sp[g][tok] = p;
+      if (tok == 0) {
+        sl_[g] = l;
+        ws_l[(hq0 + g) * n_slots + slot] = l > 0.f ? (mx + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+      }
+    }
+  }
+  __syncthreads();
+  {
+    const int ch = tid & 127;
+    for (int g = tid >> 7; g < G; g += 2) {
+      float acc = 0.f;
+      for (int t = 0; t < tail_len; t++) acc = fmaf(sp[g][t], bf16_val(tv[(int64_t)t * HS_D + ch]), acc);
+      const float l = sl_[g];
+      ws_o[((hq0 + g) * n_slots + slot) * HS_D + ch] = l > 0.f ? acc / l : 0.f;
+    }
+  }
+}
+
 }  // namespace
 
 // Workspace: [partial O (normalised) [B*Hq][n_splits][128] fp32][partial LSE [B*Hq][n_splits] fp32].
@@ -368,11 +433,15 @@ static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T
   return hipGetLastError();
 }
 
-hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q, hs_kv_dev kv,
-                            uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases) {
-  const dim3 grid(n_splits, Hkv, B);
+hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_work, const uint16_t* Q, hs_kv_dev kv,
+                            const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, uint16_t* O, float* LSE,
+                            float* ws, hipStream_t st, int phases) {
+  const dim3 grid(n_work, Hkv, B);
   const float sl2 = scale * kLog2e;
-  const int per = (T + n_splits - 1) / n_splits;
+  const int per = (T + n_work - 1) / n_work;
+  // partial slots per query head: the n_work cache splits, then one for the dense tail if there is
+  // one (the kernels take the slot count as their stride)
+  const int n_splits = n_work + (tail_len >= 0 ? 1 : 0);
   float* wo = ws;
   float* wl = wo + (size_t)B * Hq * n_splits * HS_D;
   const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
@@ -397,6 +466,11 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_sp
   }
 #undef HS_GO
 #undef HS_GO_DYN
+  }
+  if (e == hipSuccess && (phases & 1) && tail_len >= 0) {
+    hipLaunchKernelGGL(decode_tail_kernel, dim3(Hkv, B), dim3(256), 0, st, Hq, Hkv, sl2, n_splits, n_work, tail_len, Q,
+                       tail_k, tail_v, wo, wl);
+    e = hipGetLastError();
   }
   if (e != hipSuccess || !(phases & 2)) return e;
   hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);

@@ -391,6 +391,39 @@ def test_prefill_cfg4_full_size_skip75_sampled_rows():
     assert_lse_close(lse, Lr, "prefill cfg4 lse")
 
 
+def test_decode_with_dense_tail():
+    """Cache of whole tiles plus 0..64 recent tokens that are not compressed yet."""
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 7
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L + 64, 128, 1, seed=160)
+    q = Q[:, :, 0, :].copy()
+    Kc, Vc, Kt, Vt = K[:, :, :L].copy(), V[:, :, :L].copy(), K[:, :, L:].copy(), V[:, :, L:].copy()
+    sk, sv = _mixed_states(B, Hkv, L // 64, seed=161, p_skip=0.3)
+    for pol in (dict(), dict(state_k=sk, state_v=sv)):
+        sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Kc, Vc, **pol)
+        for tail_len in (0, 1, 17, 64):
+            for ns in (0, 3):
+                O, LSE = hb.decode_attn(sh, _dev(q), kv, n_splits=ns, tail_k=_dev(Kt), tail_v=_dev(Vt), tail_len=tail_len)
+                torch.cuda.synchronize()
+                Or, Lr = orc.attention_decode(q, pk, pv, tail_k=Kt, tail_v=Vt, tail_len=tail_len)
+                assert_close(_f32(O), Or, f"decode tail {tail_len} splits {ns} {sorted(pol)}")
+                assert_lse_close(LSE.cpu().numpy(), Lr, f"decode tail {tail_len} lse")
+    # every cached tile skipped: the tail alone answers
+    z = np.zeros((B, Hkv, L // 64), dtype=np.int8)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Kc, Vc, state_k=z, state_v=z)
+    O, LSE = hb.decode_attn(sh, _dev(q), kv, tail_k=_dev(Kt), tail_v=_dev(Vt), tail_len=5)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, pk, pv, tail_k=Kt, tail_v=Vt, tail_len=5)
+    assert_close(_f32(O), Or, "decode tail only")
+    assert_lse_close(LSE.cpu().numpy(), Lr, "decode tail only lse")
+    import ctypes as C
+    kvs = kv.struct()
+    qd = _dev(q)
+    assert hb.lib().hs_decode_attn_tail(C.byref(sh), 0.0, 0, hb._ptr(qd), C.byref(kvs), None, None, 65, hb._ptr(qd), None,
+                                        hb._ptr(qd), None) == -1
+    assert hb.lib().hs_decode_attn_tail(C.byref(sh), 0.0, 0, hb._ptr(qd), C.byref(kvs), None, None, 3, hb._ptr(qd), None,
+                                        hb._ptr(qd), None) == -1
+
+
 # ------------------------------------------------------------------ edges and errors
 def test_single_tile_and_odd_batch_shapes():
     """L = 64 (one tile, one split), B = 3, 3 KV heads: smallest grid dimensions on every kernel."""

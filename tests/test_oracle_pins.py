@@ -361,6 +361,32 @@ def test_decode_equals_last_causal_row():
     assert np.allclose(LSE.reshape(B, Hkv * G), LSEd, rtol=1e-12)
 
 
+def test_decode_with_dense_tail_equals_library_sdpa_on_concatenation():
+    """Tail tokens join the softmax unpruned: equals the library attention over [masked cache ; tail]."""
+    rng = np.random.default_rng(11)
+    K, V = _rand_kv(11, B=2, H=2, L=48, D=16)
+    q = wl.f32_to_bf16_bits(rng.standard_normal((2, 4, 16)).astype(np.float32))
+    tk = wl.f32_to_bf16_bits(rng.standard_normal((2, 2, 16, 16)).astype(np.float32))
+    tv = wl.f32_to_bf16_bits(rng.standard_normal((2, 2, 16, 16)).astype(np.float32))
+    sk = np.array([[[2, 0, 1]] * 2] * 2, dtype=np.int8)
+    pk, pv, info = orc.compress_kv(K, V, Bt=16, state_k=sk, state_v=sk)
+    for tail_len in (1, 7, 16):
+        O, LSE = orc.attention_decode(q, pk, pv, tail_k=tk, tail_v=tv, tail_len=tail_len)
+        Km = np.where(info["mask_k"], K, 0).astype(np.uint16)
+        Vm = np.where(info["mask_v"], V, 0).astype(np.uint16)
+        Km[:, :, 32:] = K[:, :, 32:]                               # tile 2 dense
+        Vm[:, :, 32:] = V[:, :, 32:]
+        keep = np.r_[0:16, 32:48]                                  # tile 1 skipped
+        Kc = np.concatenate([Km[:, :, keep], tk[:, :, :tail_len]], axis=2)
+        Vc = np.concatenate([Vm[:, :, keep], tv[:, :, :tail_len]], axis=2)
+        ref = _sdpa(_f(q)[:, :, None, :], np.repeat(_f(Kc), 2, axis=1), np.repeat(_f(Vc), 2, axis=1))
+        assert np.allclose(O, ref[:, :, 0, :], rtol=1e-12, atol=1e-13)
+    # an empty tail is the plain decode
+    O0, L0 = orc.attention_decode(q, pk, pv)
+    O1, L1 = orc.attention_decode(q, pk, pv, tail_k=tk, tail_v=tv, tail_len=0)
+    assert (O0 == O1).all() and (L0 == L1).all()
+
+
 def test_brute_force_python_floats_tiny():
     """Whole path (prune, skip, attention) redone with Python lists and math.exp."""
     B, Hkv, G, L, D, Bt = 1, 1, 2, 16, 8, 4
