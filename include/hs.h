@@ -154,6 +154,22 @@ HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],
                    const hs_kv* out, void* workspace, void* stream);
 
+/* Fill one tile of a cache that grows during decode.  The pools hand out slots in sequence
+ * order with one counter per pool (Sec. III-B), so a cache can be allocated for a capacity of
+ * shape->L tokens, compressed with the tiles beyond the current length SKIP (explicit states;
+ * attention ignores SKIP tiles), and extended tile by tile: tile `tile` (0 <= tile < L/64), SKIP
+ * in every (b, kv head) row on entry, becomes state_k / state_v (HS_DENSE or HS_SPARSE24, the
+ * same for every row; 2:4 by `element_rule`) and takes the next slot of its pool = the number of
+ * tiles of that kind the row already holds (appending in tile order keeps slots in tile order,
+ * i.e. the result equals one hs_compress_kv over everything).
+ * K_tile, V_tile: device bf16 [B, Hkv, 64, D], element strides tile_strides[3] = {batch, head,
+ * token} (innermost contiguous; NULL = contiguous), 16-byte aligned.  kv->uniform must be 0.
+ * A row whose pool has no free slot (capacity cap_* of `kv`) keeps the tile SKIP; if `overflow`
+ * (device int32, set to 0 by the caller) is not NULL it is then set to 1.  No workspace. */
+HS_API int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, int32_t state_v,
+                   int32_t element_rule, const void* K_tile, const void* V_tile,
+                   const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
+
 /* Inverse of the packing, for tests and debugging: dense bf16 [B, Hkv, L, D]
  * (contiguous) with zeros at pruned positions and in skipped tiles. */
 HS_API int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_out, void* stream);

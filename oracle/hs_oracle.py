@@ -297,6 +297,37 @@ def pack_tensor(kind, X_bits, mask, state, Bt):
     return PackedKV(kind, Bt, D, mp, dense, nnz, meta)
 
 
+def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, element_rule="magnitude"):
+    """Fill tile `tile` of a cache whose pools grow during decode (Sec. III-B: blocks are handed
+    to the dense or the sparse pool in sequence order, one counter per pool).  The tile must be
+    SKIP (not filled yet) in every row; it takes the next slot of its pool, i.e. the number of
+    tiles of the same kind the row already holds.  K_tile_bits, V_tile_bits: [B, Hkv, Bt, D];
+    state_k, state_v: DENSE or SPARSE24, the same for every row.  Works in place."""
+    K_tile_bits = np.asarray(K_tile_bits, dtype=np.uint16)
+    V_tile_bits = np.asarray(V_tile_bits, dtype=np.uint16)
+    B, H, Bt, D = K_tile_bits.shape
+    assert Bt == pk.Bt and state_k in (DENSE, SPARSE24) and state_v in (DENSE, SPARSE24)
+    masks = (element_mask_k(K_tile_bits, element_rule), element_mask_v(V_tile_bits, element_rule))
+    for p, X, mask, state in ((pk, K_tile_bits, masks[0], state_k), (pv, V_tile_bits, masks[1], state_v)):
+        assert (p.map[:, :, tile] == 0).all()
+        for b in range(B):
+            for h in range(H):
+                if state == DENSE:
+                    slot = int((p.map[b, h] > 0).sum())
+                    if slot >= p.dense.shape[2]:
+                        p.dense = np.concatenate([p.dense, np.zeros_like(p.dense[:, :, :1])], axis=2)
+                    p.dense[b, h, slot] = X[b, h]
+                    p.map[b, h, tile] = slot + 1
+                else:
+                    slot = int((p.map[b, h] < 0).sum())
+                    if slot >= p.nnz.shape[2]:
+                        p.nnz = np.concatenate([p.nnz, np.zeros_like(p.nnz[:, :, :1])], axis=2)
+                        p.meta = np.concatenate([p.meta, np.zeros_like(p.meta[:, :, :1])], axis=2)
+                    pack = pack_k_tile if p.kind == "k" else pack_v_tile
+                    p.nnz[b, h, slot], p.meta[b, h, slot] = pack(X[b, h], mask[b, h])
+                    p.map[b, h, tile] = -(slot + 1)
+
+
 def unpack_tensor(p):
     """Packed -> dense bf16 bits [B, Hkv, L, D] with zeros at pruned positions and
     in skipped tiles."""

@@ -53,6 +53,8 @@ EXPORTS = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_append_tile": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
     "hs_decode_attn_tail": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                       C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn_phases": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV),
@@ -183,10 +185,24 @@ def compress_kv(shape, policy, K, V, out=None, workspace=None):
     if workspace is None:
         workspace = _workspace(workspace_bytes(shape, 0), K.device)
     strides = (C.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
+    if policy.state_k:
+        out.uniform = 0      # explicit states may skip tiles or mix kinds: no "slot == tile" promise
     kvs = out.struct()
     _check(lib().hs_compress_kv(C.byref(shape), C.byref(policy), _ptr(K), _ptr(V), strides, C.byref(kvs),
                                 _ptr(workspace), _stream()))
     return out
+
+
+def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARSE24, element_rule=RULE_MAGNITUDE,
+                overflow=None):
+    """K_tile, V_tile: bf16 device tensors [B, Hkv, 64, D] (last dim contiguous); fills tile `tile` of kv.
+    overflow: optional int32 device tensor (1 element) raised when a row's pool is full."""
+    assert K_tile.dtype == torch.bfloat16 and V_tile.dtype == torch.bfloat16 and K_tile.stride() == V_tile.stride()
+    assert K_tile.stride(-1) == 1 and tuple(K_tile.shape) == (shape.B, shape.Hkv, TILE, shape.D)
+    strides = (C.c_int64 * 3)(K_tile.stride(0), K_tile.stride(1), K_tile.stride(2))
+    kvs = kv.struct()
+    _check(lib().hs_append_tile(C.byref(shape), int(tile), int(state_k), int(state_v), int(element_rule), _ptr(K_tile),
+                                _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
 
 
 def unpack_kv(shape, kv):

@@ -80,6 +80,10 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
                             int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st);
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
                           int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st);
+// one tile [B, Hkv, 64, D] into tile index `tile` of a cache of T tiles per row
+hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
+                            int B, int Hkv, int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule,
+                            int32_t* overflow, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 // tail_len < 0: no tail slot; tail_len >= 0: one extra partial per query head, computed from the
 // dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D])

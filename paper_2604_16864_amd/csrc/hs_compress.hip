@@ -213,6 +213,40 @@ __global__ __launch_bounds__(256) void slots_kernel(int T, int32_t* k_map, int32
   }
 }
 
+// Appending (Sec. III-B counters): map entries of tile `tile` of every row = next slot of the
+// pool its state names = how many tiles of that kind the row holds; a full pool leaves the
+// tile skipped and raises *overflow.  One workgroup per row.
+__global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int state_k, int state_v, hs_kv_dev kv,
+                                                           int32_t* overflow) {
+  __shared__ int part[4][4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  int32_t* km = const_cast<int32_t*>(kv.k_map) + (int64_t)row * T;
+  int32_t* vm = const_cast<int32_t*>(kv.v_map) + (int64_t)row * T;
+  int n[4] = {0, 0, 0, 0};  // dense K, 2:4 K, dense V, 2:4 V
+  for (int t = tid; t < T; t += 256) {
+    if (t == tile) continue;
+    const int a = km[t], c = vm[t];
+    n[0] += a > 0; n[1] += a < 0; n[2] += c > 0; n[3] += c < 0;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) n[i] += __shfl_xor(n[i], off);
+    if ((tid & 63) == 0) part[i][tid >> 6] = n[i];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int c[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) c[i] = part[i][0] + part[i][1] + part[i][2] + part[i][3];
+    const bool fits = (state_k == HS_DENSE ? c[0] < kv.cap_dense_k : c[1] < kv.cap_sparse_k) &&
+                      (state_v == HS_DENSE ? c[2] < kv.cap_dense_v : c[3] < kv.cap_sparse_v);
+    km[tile] = !fits ? 0 : (state_k == HS_DENSE ? c[0] + 1 : -(c[1] + 1));
+    vm[tile] = !fits ? 0 : (state_v == HS_DENSE ? c[2] + 1 : -(c[3] + 1));
+    if (!fits && overflow != nullptr) *overflow = 1;
+  }
+}
+
 // ----------------------------------------------------------------------------------
 // Fused prune + pack (Sec. IV-B): one workgroup per tile, K then V.
 // ----------------------------------------------------------------------------------
@@ -221,9 +255,10 @@ __global__ __launch_bounds__(256) void slots_kernel(int T, int32_t* k_map, int32
 // kernel writes it (saves the separate map-fill launch of the unranked policies).
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv,
-                                                   int uni_k, int uni_v, int rule) {
+                                                   int uni_k, int uni_v, int rule, int t0) {
   __shared__ uint16_t vl[HS_BT * kVStride];
-  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // source tile blockIdx.x of K, V goes to tile t of the cache (t0 = 0 except when appending)
+  const int ts = blockIdx.x, t = ts + t0, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
   const int64_t row = (int64_t)b * Hkv + h;
   int mk, mv;
@@ -238,8 +273,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
     mk = kv.k_map[row * T + t];
     mv = kv.v_map[row * T + t];
   }
-  const uint16_t* kt = K + b * sb + h * sh + (int64_t)t * HS_BT * st;
-  const uint16_t* vt = V + b * sb + h * sh + (int64_t)t * HS_BT * st;
+  const uint16_t* kt = K + b * sb + h * sh + (int64_t)ts * HS_BT * st;
+  const uint16_t* vt = V + b * sb + h * sh + (int64_t)ts * HS_BT * st;
   if (mv != 0) stage_v_tile(vt, st, vl);
 
   // ---- K ----
@@ -442,7 +477,17 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
 
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
                           int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st) {
-  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule);
+  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0);
+  return hipGetLastError();
+}
+
+hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
+                            int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule, int32_t* overflow,
+                            hipStream_t st) {
+  hipLaunchKernelGGL(append_slots_kernel, dim3(B * Hkv), dim3(256), 0, st, T, tile, state_k, state_v, kv, overflow);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(pack_kernel, dim3(1, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile);
   return hipGetLastError();
 }
 

@@ -424,6 +424,59 @@ def test_decode_with_dense_tail():
                                         hb._ptr(qd), None) == -1
 
 
+def test_append_tiles_during_decode():
+    """A cache allocated for 9 tiles, compressed with 4, then grown tile by tile (mixed tile kinds, the last
+    one from a strided buffer); after every append decode equals the oracle's, and at the end pools and maps
+    are those of compressing everything at once."""
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 9
+    T = L // 64
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=170)
+    q = Q[:, :, 0, :].copy()
+    rng = np.random.default_rng(171)
+    sk = rng.choice([1, 2], size=(T,)).astype(np.int8)
+    sv = rng.choice([1, 2], size=(T,)).astype(np.int8)
+    full_k, full_v = np.broadcast_to(sk, (B, Hkv, T)).copy(), np.broadcast_to(sv, (B, Hkv, T)).copy()
+    pre_k, pre_v = full_k.copy(), full_v.copy()
+    pre_k[:, :, 4:] = 0
+    pre_v[:, :, 4:] = 0
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    caps = [0, int((sk == 1).sum()), int((sk == 2).sum()), int((sv == 1).sum()), int((sv == 2).sum())]
+    kv = hb.PackedKV(sh, caps)
+    hb.compress_kv(sh, hb.make_policy(state_k=pre_k, state_v=pre_v), _dev(K), _dev(V), out=kv)
+    pk, pv, _ = orc.compress_kv(K, V, state_k=pre_k, state_v=pre_v)
+    ovf = torch.zeros(1, dtype=torch.int32, device="cuda")
+    Kd, Vd = _dev(K), _dev(V)
+    for t in range(4, T):
+        kt, vt = Kd[:, :, 64 * t:64 * (t + 1)], Vd[:, :, 64 * t:64 * (t + 1)]      # strided views of the full tensors
+        if t % 2 == 0:
+            kt, vt = kt.contiguous(), vt.contiguous()
+        hb.append_tile(sh, kv, t, kt, vt, state_k=int(sk[t]), state_v=int(sv[t]), overflow=ovf)
+        orc.append_tile(pk, pv, t, K[:, :, 64 * t:64 * (t + 1)], V[:, :, 64 * t:64 * (t + 1)], int(sk[t]), int(sv[t]))
+        O, LSE = hb.decode_attn(sh, _dev(q), kv)
+        torch.cuda.synchronize()
+        Or, Lr = orc.attention_decode(q, pk, pv)
+        assert_close(_f32(O), Or, f"decode after append of tile {t}")
+        assert_lse_close(LSE.cpu().numpy(), Lr, f"decode after append of tile {t} lse")
+    assert int(ovf.item()) == 0
+    pk1, pv1, _ = orc.compress_kv(K, V, state_k=full_k, state_v=full_v)
+    check_packed_bit_exact(sh, kv, pk1, pv1)
+    # a full pool: the tile stays skipped and the flag goes up
+    kv2 = hb.PackedKV(sh, [0, 1, 4, 1, 4])
+    z = np.zeros((B, Hkv, T), dtype=np.int8)
+    z[:, :, :4] = 2
+    hb.compress_kv(sh, hb.make_policy(state_k=z, state_v=z), Kd, Vd, out=kv2)
+    hb.append_tile(sh, kv2, 4, Kd[:, :, 256:320].contiguous(), Vd[:, :, 256:320].contiguous(), overflow=ovf)
+    torch.cuda.synchronize()
+    assert int(ovf.item()) == 1
+    assert (kv2.k_map[:, :, 4].cpu().numpy() == 0).all() and (kv2.v_map[:, :, 4].cpu().numpy() == 0).all()
+    import ctypes as C
+    kvs = kv2.struct()
+    args = (hb._ptr(Kd), hb._ptr(Vd), None, C.byref(kvs), None, None)
+    assert hb.lib().hs_append_tile(C.byref(sh), T, 2, 2, 0, *args) == -1          # tile out of range
+    assert hb.lib().hs_append_tile(C.byref(sh), 5, 0, 2, 0, *args) == -1          # SKIP is not a state to append
+    assert hb.lib().hs_append_tile(C.byref(sh), 5, 2, 2, 7, *args) == -1          # unknown element rule
+
+
 # ------------------------------------------------------------------ edges and errors
 def test_single_tile_and_odd_batch_shapes():
     """L = 64 (one tile, one split), B = 3, 3 KV heads: smallest grid dimensions on every kernel."""

@@ -387,6 +387,34 @@ def test_decode_with_dense_tail_equals_library_sdpa_on_concatenation():
     assert (O0 == O1).all() and (L0 == L1).all()
 
 
+def test_append_in_tile_order_rebuilds_the_one_shot_cache():
+    """Compressing a prefix with the rest of the capacity SKIP and appending the remaining tiles one
+    by one gives the pools and maps of compressing everything at once (slots follow tile order)."""
+    K, V = _rand_kv(12, B=2, H=2, L=16 * 7, D=16)
+    rng = np.random.default_rng(12)
+    sk = rng.choice([1, 2], size=(7,)).astype(np.int8)
+    sv = rng.choice([1, 2], size=(7,)).astype(np.int8)
+    full_k = np.broadcast_to(sk, (2, 2, 7)).copy()
+    full_v = np.broadcast_to(sv, (2, 2, 7)).copy()
+    pk1, pv1, _ = orc.compress_kv(K, V, Bt=16, state_k=full_k, state_v=full_v)
+    pre_k, pre_v = full_k.copy(), full_v.copy()
+    pre_k[:, :, 3:] = 0
+    pre_v[:, :, 3:] = 0
+    pk2, pv2, _ = orc.compress_kv(K, V, Bt=16, state_k=pre_k, state_v=pre_v)
+    q = wl.f32_to_bf16_bits(rng.standard_normal((2, 4, 16)).astype(np.float32))
+    O_pre, _ = orc.attention_decode(q, pk2, pv2)
+    O_ref, _ = orc.attention_rows(np.repeat(q[:, :, None, :], 16 * 7, axis=2), pk1, pv1,
+                                  [(b, h, 16 * 3 - 1) for b in range(2) for h in range(4)], causal=True, q_offset=0)
+    assert np.allclose(O_pre.reshape(-1, 16), O_ref, rtol=1e-12, atol=1e-13)   # unfilled capacity = causal prefix
+    for t in range(3, 7):
+        orc.append_tile(pk2, pv2, t, K[:, :, 16 * t:16 * (t + 1)], V[:, :, 16 * t:16 * (t + 1)], int(sk[t]), int(sv[t]))
+    for a, b in ((pk1, pk2), (pv1, pv2)):
+        assert (a.map == b.map).all()
+        nd, ns = a.dense.shape[2], a.nnz.shape[2]
+        assert (a.dense == b.dense[:, :, :nd]).all() and (a.nnz == b.nnz[:, :, :ns]).all() and (a.meta == b.meta[:, :, :ns]).all()
+    assert (orc.unpack_tensor(pk2) == orc.unpack_tensor(pk1)).all()
+
+
 def test_brute_force_python_floats_tiny():
     """Whole path (prune, skip, attention) redone with Python lists and math.exp."""
     B, Hkv, G, L, D, Bt = 1, 1, 2, 16, 8, 4
