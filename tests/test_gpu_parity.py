@@ -477,6 +477,60 @@ def test_append_tiles_during_decode():
     assert hb.lib().hs_append_tile(C.byref(sh), 5, 2, 2, 7, *args) == -1          # unknown element rule
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_and_policies(seed):
+    """Seeded sweep over shapes (batch, heads, GQA group, tiles, query chunk) and policies (fractions with
+    ranking, protected end tiles, explicit states, non-zero rule); every stage against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 4))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * G
+    T = int(rng.integers(1, 14))
+    L = 64 * T
+    Tq = int(rng.integers(1, T + 1))
+    Lq = 64 * Tq
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, Lq, seed=2000 + seed, k_outliers=bool(rng.integers(0, 2)))
+    kind = int(rng.integers(0, 4))
+    if kind == 0:
+        pol = dict(skip_frac=float(rng.choice([0.0, 0.25, 0.5])), sparse_frac_k=float(rng.choice([0.0, 0.5, 1.0])),
+                   sparse_frac_v=float(rng.choice([0.0, 0.3, 1.0])))
+    elif kind == 1:
+        pol = dict(skip_frac=float(rng.choice([0.0, 0.4])), dense_first_tiles=int(rng.integers(0, 3)),
+                   dense_last_tiles=int(rng.integers(0, 5)))
+    elif kind == 2:
+        sk, sv = _mixed_states(B, Hkv, T, seed=3000 + seed, p_skip=float(rng.choice([0.0, 0.3])))
+        pol = dict(state_k=sk, state_v=sv)
+    else:
+        pol = dict(element_rule="nonzero", sparse_frac_v=float(rng.choice([0.5, 1.0])))
+    sh, kv, pk, pv, info = compress_both(B, Hq, Hkv, L, K, V, **pol)
+    if "energy" in info:       # ranked: the cut must not sit on a rounding-level near-tie (see test_compress_policy_ranking)
+        for key in ("energy", "loss_k", "loss_v"):
+            sc = np.sort(info[key], axis=-1)
+            gaps = np.diff(sc, axis=-1) / np.maximum(sc[..., 1:], 1e-300)
+            assert ((gaps > 1e-12) | (gaps == 0)).all()
+    check_packed_bit_exact(sh, kv, pk, pv)
+    causal = bool(rng.integers(0, 4))          # mostly causal
+    O, LSE = hb.prefill_attn(sh, _dev(Q), kv, causal=causal)
+    n_rows = min(96, B * Hq * Lq)
+    flat = rng.choice(B * Hq * Lq, size=n_rows, replace=False)
+    rows = [(int(f // (Hq * Lq)), int((f // Lq) % Hq), int(f % Lq)) for f in flat]
+    rows.append((B - 1, Hq - 1, Lq - 1))
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=causal)
+    idx = tuple(np.array(rows).T)
+    what = f"seed {seed}: B{B} Hq{Hq} Hkv{Hkv} L{L} Lq{Lq} causal={causal} {sorted(pol)}"
+    torch.cuda.synchronize()
+    assert_close(_f32(O)[idx], Or, "prefill " + what)
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill lse " + what)
+    q = Q[:, :, -1, :].copy()
+    ns = int(rng.choice([0, 1, 5, 40]))
+    Od, LSEd = hb.decode_attn(sh, _dev(q), kv, n_splits=ns)
+    torch.cuda.synchronize()
+    Odr, Ldr = orc.attention_decode(q, pk, pv)
+    assert_close(_f32(Od), Odr, f"decode splits {ns} " + what)
+    assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode lse " + what)
+
+
 # ------------------------------------------------------------------ edges and errors
 def test_single_tile_and_odd_batch_shapes():
     """L = 64 (one tile, one split), B = 3, 3 KV heads: smallest grid dimensions on every kernel."""
