@@ -202,6 +202,32 @@ def extra_legs(hb, torch, Q, K, V, qd, sh, args):
         r["prefill_speedup_vs_dense"] = b8[0]["prefill_ms"] / r["prefill_ms"]
         r["decode_speedup_vs_dense"] = b8[0]["decode_us"] / r["decode_us"]
     res["paper_kernel_shape_b8_32k"] = b8
+    del K5, V5, Q5, O5, ws5
+    torch.cuda.empty_cache()
+    # (5) the paper's element type: fp16 at the benchmark workload's shape (N(0,1) inputs), one term of P in GEMM2
+    sh6 = hb.make_shape(B, Hq, Hkv, L, dtype=hb.FP16)
+    K6 = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.float16, generator=g)
+    V6 = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.float16, generator=g)
+    Q6 = torch.randn((B, Hq, L, 128), device="cuda", dtype=torch.float16, generator=g)
+    q6 = Q6[:, :, -1, :].contiguous()
+    O6 = torch.empty_like(Q6)
+    o6 = torch.empty_like(q6)
+    flops6 = 4.0 * 128 * Hq * B * (L * (L + 1) / 2.0)
+    f16 = []
+    for name6, kw in (("dense", dict(sparse_frac_k=0.0, sparse_frac_v=0.0)), ("sk0_sv1", dict(sparse_frac_k=0.0)), ("2:4", dict())):
+        p6 = hb.make_policy(**kw)
+        c6 = hb.tile_counts(sh6, p6)
+        kv6 = [hb.compress_kv(sh6, p6, K6, V6, workspace=ws_c) for _ in range(6)]
+        t_p = _time(torch, lambda i: hb.prefill_attn(sh6, Q6, kv6[i % 6], causal=True, want_lse=False, out=O6), 3)
+        t_d = _time(torch, lambda i: hb.decode_attn(sh6, q6, kv6[i % 6], n_splits=n, want_lse=False, out=o6, workspace=ws_d), 24, warm=6)
+        nb = packed_bytes(B, Hkv, T, c6)
+        f16.append({"case": name6, "prefill_ms": t_p * 1e3, "prefill_dense_equiv_TFLOPs": flops6 / t_p / 1e12,
+                    "decode_us": t_d * 1e6, "decode_GBps": nb / t_d / 1e9})
+        del kv6
+    for r in f16:
+        r["prefill_speedup_vs_dense"] = f16[0]["prefill_ms"] / r["prefill_ms"]
+        r["decode_speedup_vs_dense"] = f16[0]["decode_us"] / r["decode_us"]
+    res["fp16_same_shape"] = f16
     return res
 
 

@@ -10,7 +10,9 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers unless marked [host].
- *   - bf16 tensors are raw 16-bit patterns; D (head dim) is contiguous.
+ *   - Q, K, V, O are 16-bit floating point, raw bit patterns: bf16 (the benchmark workloads) or
+ *     IEEE fp16 (the paper's type), chosen by hs_shape.dtype for all four; "bf16" in the
+ *     descriptions below stands for that type.  D (head dim) is contiguous.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
  *     the default stream).  The library allocates nothing, frees nothing and
  *     keeps no pointer after a call returns; the caller owns every buffer.
@@ -59,7 +61,14 @@ typedef struct {
   int32_t L;    /* tokens in the cache */
   int32_t D;    /* head dim */
   int32_t tile; /* tokens per tile */
+  int32_t dtype; /* HS_BF16 or HS_FP16: element type of Q, K, V, O and of the pools */
 } hs_shape;
+
+/* Element types.  Pruning compares magnitudes through the bit patterns (bits & 0x7fff), which
+ * orders both formats; packed values are copied bit for bit.  With fp16 the softmax
+ * numerators enter the second product as one fp16 term (11 significant bits); with bf16 as
+ * two bf16 terms. */
+enum { HS_BF16 = 0, HS_FP16 = 1 };
 
 /* Policy of the built-in magnitude pruner (Sec. III-A, Eq. 2a-d).
  *   skip_frac      floor(skip_frac * T) tiles per (b, kv head) with the lowest

@@ -31,12 +31,20 @@ SKIP, DENSE, SPARSE24 = 0, 1, 2
 
 
 # ----------------------------------------------------------------------------
-# bf16 <-> real numbers
+# 16-bit patterns <-> real numbers
 # ----------------------------------------------------------------------------
 def bf16_to_f64(bits):
     """Exact value of bf16 bit patterns (uint16) as float64."""
     bits = np.asarray(bits, dtype=np.uint16)
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def to_f64(bits, dtype="bf16"):
+    """Exact value of 16-bit patterns: "bf16", or "fp16" = IEEE binary16 (the paper's type)."""
+    if dtype == "fp16":
+        return np.ascontiguousarray(np.asarray(bits, dtype=np.uint16)).view(np.float16).astype(np.float64)
+    assert dtype == "bf16"
+    return bf16_to_f64(bits)
 
 
 # ----------------------------------------------------------------------------
@@ -92,20 +100,20 @@ def element_mask_v(V_bits, rule="magnitude"):
 # ----------------------------------------------------------------------------
 # block-level decisions (Sec. III-A Eq. 2c-d; skip = workload extension)
 # ----------------------------------------------------------------------------
-def tile_energy(K_bits, V_bits, Bt):
+def tile_energy(K_bits, V_bits, Bt, dtype="bf16"):
     """Skip score per tile: sum of squares of the tile's K and V entries (the
     squared joint L2 norm), accumulated in fp64.  [B, Hkv, T]."""
-    K = bf16_to_f64(K_bits)
-    V = bf16_to_f64(V_bits)
+    K = to_f64(K_bits, dtype)
+    V = to_f64(V_bits, dtype)
     B, H, L, D = K.shape
     T = L // Bt
     e = (K * K).reshape(B, H, T, Bt * D).sum(axis=-1) + (V * V).reshape(B, H, T, Bt * D).sum(axis=-1)
     return e
 
 
-def tile_prune_loss(X_bits, mask, Bt):
+def tile_prune_loss(X_bits, mask, Bt, dtype="bf16"):
     """Eq. 2c: L1 norm of what the element mask removes, per block.  [B, Hkv, T]."""
-    X = np.abs(bf16_to_f64(X_bits)) * (~mask)
+    X = np.abs(to_f64(X_bits, dtype)) * (~mask)
     B, H, L, D = X.shape
     return X.reshape(B, H, L // Bt, Bt * D).sum(axis=-1)
 
@@ -252,8 +260,8 @@ def unpack_v_tile(nnz, meta):
 class PackedKV:
     """Canonical packed cache for one tensor (K or V): pools + signed map."""
 
-    def __init__(self, kind, Bt, D, mp, dense, nnz, meta):
-        self.kind, self.Bt, self.D = kind, Bt, D
+    def __init__(self, kind, Bt, D, mp, dense, nnz, meta, dtype="bf16"):
+        self.kind, self.Bt, self.D, self.dtype = kind, Bt, D, dtype
         self.map, self.dense, self.nnz, self.meta = mp, dense, nnz, meta
 
     def nbytes(self):
@@ -348,18 +356,22 @@ def unpack_tensor(p):
 
 
 def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0,
-                state_k=None, state_v=None, dense_first_tiles=0, dense_last_tiles=0, element_rule="magnitude"):
+                state_k=None, state_v=None, dense_first_tiles=0, dense_last_tiles=0, element_rule="magnitude",
+                dtype="bf16"):
     """Whole compress step: element masks, tile states (policy or explicit),
-    maps, pools.  Returns (PackedKV for K, PackedKV for V, dict of intermediates)."""
+    maps, pools.  Returns (PackedKV for K, PackedKV for V, dict of intermediates).
+    dtype names the 16-bit format of the patterns; it matters for the tile scores and for
+    attention, not for the element masks (the magnitude order is the order of bits & 0x7fff in
+    both formats) nor for the packing (bits are copied)."""
     K_bits = np.asarray(K_bits, dtype=np.uint16)
     V_bits = np.asarray(V_bits, dtype=np.uint16)
     mk = element_mask_k(K_bits, element_rule)
     mv = element_mask_v(V_bits, element_rule)
     info = {"mask_k": mk, "mask_v": mv}
     if state_k is None:
-        energy = tile_energy(K_bits, V_bits, Bt)
-        loss_k = tile_prune_loss(K_bits, mk, Bt)
-        loss_v = tile_prune_loss(V_bits, mv, Bt)
+        energy = tile_energy(K_bits, V_bits, Bt, dtype)
+        loss_k = tile_prune_loss(K_bits, mk, Bt, dtype)
+        loss_v = tile_prune_loss(V_bits, mv, Bt, dtype)
         state_k, state_v = select_states(energy, loss_k, loss_v, skip_frac, sparse_frac_k, sparse_frac_v,
                                          dense_first_tiles, dense_last_tiles)
         info.update(energy=energy, loss_k=loss_k, loss_v=loss_v)
@@ -369,6 +381,7 @@ def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_
     info.update(state_k=state_k, state_v=state_v)
     pk = pack_tensor("k", K_bits, mk, state_k, Bt)
     pv = pack_tensor("v", V_bits, mv, state_v, Bt)
+    pk.dtype = pv.dtype = dtype
     return pk, pv, info
 
 
@@ -402,8 +415,8 @@ def attention_rows(Q_bits, pk, pv, rows, causal, scale=None, q_offset=None):
         scale = 1.0 / np.sqrt(D)
     if q_offset is None:
         q_offset = L - Lq
-    Kd = bf16_to_f64(unpack_tensor(pk))
-    Vd = bf16_to_f64(unpack_tensor(pv))
+    Kd = to_f64(unpack_tensor(pk), pk.dtype)
+    Vd = to_f64(unpack_tensor(pv), pk.dtype)
     tok_visible = np.repeat(pk.map != 0, pk.Bt, axis=-1)       # [B, Hkv, L]
     rows = list(rows)
     O = np.zeros((len(rows), D), dtype=np.float64)
@@ -413,7 +426,7 @@ def attention_rows(Q_bits, pk, pv, rows, causal, scale=None, q_offset=None):
         vis = tok_visible[b, h].copy()
         if causal:
             vis[i + q_offset + 1:] = False
-        q = bf16_to_f64(Q_bits[b, hq, i])
+        q = to_f64(Q_bits[b, hq, i], pk.dtype)
         s = (Kd[b, h][vis] @ q) * scale
         O[n], LSE[n] = _softmax_av(s, Vd[b, h][vis])
     return O, LSE
@@ -437,10 +450,10 @@ def attention_decode(q_bits, pk, pv, scale=None, tail_k=None, tail_v=None, tail_
     G = Hq // Hkv
     if scale is None:
         scale = 1.0 / np.sqrt(D)
-    Kd = bf16_to_f64(unpack_tensor(pk))
-    Vd = bf16_to_f64(unpack_tensor(pv))
-    Kt = bf16_to_f64(np.asarray(tail_k, dtype=np.uint16)[:, :, :tail_len])
-    Vt = bf16_to_f64(np.asarray(tail_v, dtype=np.uint16)[:, :, :tail_len])
+    Kd = to_f64(unpack_tensor(pk), pk.dtype)
+    Vd = to_f64(unpack_tensor(pv), pk.dtype)
+    Kt = to_f64(np.asarray(tail_k, dtype=np.uint16)[:, :, :tail_len], pk.dtype)
+    Vt = to_f64(np.asarray(tail_v, dtype=np.uint16)[:, :, :tail_len], pk.dtype)
     tok_visible = np.repeat(pk.map != 0, pk.Bt, axis=-1)
     O = np.zeros((B, Hq, D), dtype=np.float64)
     LSE = np.zeros((B, Hq), dtype=np.float64)
@@ -450,7 +463,7 @@ def attention_decode(q_bits, pk, pv, scale=None, tail_k=None, tail_v=None, tail_
             vis = tok_visible[b, h]
             Kall = np.concatenate([Kd[b, h][vis], Kt[b, h]], axis=0)
             Vall = np.concatenate([Vd[b, h][vis], Vt[b, h]], axis=0)
-            s = (Kall @ bf16_to_f64(q_bits[b, hq])) * scale
+            s = (Kall @ to_f64(q_bits[b, hq], pk.dtype)) * scale
             O[b, hq], LSE[b, hq] = _softmax_av(s, Vall)
     return O, LSE
 

@@ -22,7 +22,7 @@ TILE_DENSE_BYTES, TILE_NNZ_BYTES, TILE_META_BYTES = 16384, 8192, 1024
 
 class HsShape(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("L", C.c_int32), ("D", C.c_int32),
-                ("tile", C.c_int32)]
+                ("tile", C.c_int32), ("dtype", C.c_int32)]
 
 
 class HsPolicy(C.Structure):
@@ -99,8 +99,20 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_shape(B, Hq, Hkv, L, D=HEAD_DIM, tile=TILE):
-    return HsShape(B, Hq, Hkv, L, D, tile)
+BF16, FP16 = 0, 1
+
+
+def make_shape(B, Hq, Hkv, L, D=HEAD_DIM, tile=TILE, dtype=BF16):
+    """dtype: BF16 or FP16 (or the torch dtype) = element type of Q, K, V, O."""
+    if dtype is torch.bfloat16:
+        dtype = BF16
+    elif dtype is torch.float16:
+        dtype = FP16
+    return HsShape(B, Hq, Hkv, L, D, tile, int(dtype))
+
+
+def torch_dtype(shape):
+    return torch.float16 if shape.dtype == FP16 else torch.bfloat16
 
 
 RULE_MAGNITUDE, RULE_NONZERO = 0, 1
@@ -178,7 +190,7 @@ def _workspace(nbytes, device):
 
 def compress_kv(shape, policy, K, V, out=None, workspace=None):
     """K, V: bf16 device tensors [B, Hkv, L, D] (last dim contiguous).  Returns PackedKV."""
-    assert K.dtype == torch.bfloat16 and V.dtype == torch.bfloat16 and K.is_cuda and V.is_cuda
+    assert K.dtype == torch_dtype(shape) and V.dtype == K.dtype and K.is_cuda and V.is_cuda
     assert K.stride(-1) == 1 and V.stride(-1) == 1 and K.stride() == V.stride()
     if out is None:
         out = PackedKV(shape, tile_counts(shape, policy), K.device)
@@ -197,7 +209,7 @@ def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARS
                 overflow=None):
     """K_tile, V_tile: bf16 device tensors [B, Hkv, 64, D] (last dim contiguous); fills tile `tile` of kv.
     overflow: optional int32 device tensor (1 element) raised when a row's pool is full."""
-    assert K_tile.dtype == torch.bfloat16 and V_tile.dtype == torch.bfloat16 and K_tile.stride() == V_tile.stride()
+    assert K_tile.dtype == torch_dtype(shape) and V_tile.dtype == K_tile.dtype and K_tile.stride() == V_tile.stride()
     assert K_tile.stride(-1) == 1 and tuple(K_tile.shape) == (shape.B, shape.Hkv, TILE, shape.D)
     strides = (C.c_int64 * 3)(K_tile.stride(0), K_tile.stride(1), K_tile.stride(2))
     kvs = kv.struct()
@@ -206,7 +218,7 @@ def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARS
 
 
 def unpack_kv(shape, kv):
-    K = torch.empty((shape.B, shape.Hkv, shape.L, shape.D), dtype=torch.bfloat16, device=kv.k_map.device)
+    K = torch.empty((shape.B, shape.Hkv, shape.L, shape.D), dtype=torch_dtype(shape), device=kv.k_map.device)
     V = torch.empty_like(K)
     kvs = kv.struct()
     _check(lib().hs_unpack_kv(C.byref(shape), C.byref(kvs), _ptr(K), _ptr(V), _stream()))
@@ -215,7 +227,7 @@ def unpack_kv(shape, kv):
 
 def prefill_attn(shape, Q, kv, causal=True, scale=0.0, want_lse=True, out=None, lse=None):
     """Q: bf16 [B, Hq, Lq, D] contiguous.  Returns (O bf16 [B, Hq, Lq, D], LSE fp32 [B, Hq, Lq] or None)."""
-    assert Q.dtype == torch.bfloat16 and Q.is_contiguous() and Q.is_cuda
+    assert Q.dtype == torch_dtype(shape) and Q.is_contiguous() and Q.is_cuda
     Lq = Q.shape[2]
     O = torch.empty_like(Q) if out is None else out
     if lse is None and want_lse:
@@ -231,7 +243,7 @@ def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, ls
     """Q: bf16 [B, Hq, D] contiguous.  Returns (O bf16 [B, Hq, D], LSE fp32 [B, Hq] or None).
     phases: 3 = whole call; 1 = split-KV kernel only, 2 = merge kernel only (benchmarking).
     tail_k, tail_v (bf16 [B, Hkv, 64, D]) with tail_len: dense tail of not yet compressed tokens."""
-    assert Q.dtype == torch.bfloat16 and Q.is_contiguous() and Q.is_cuda
+    assert Q.dtype == torch_dtype(shape) and Q.is_contiguous() and Q.is_cuda
     O = torch.empty_like(Q) if out is None else out
     if lse is None and want_lse:
         lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
@@ -242,7 +254,7 @@ def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, ls
         if workspace is None:
             workspace = _workspace(workspace_bytes(shape, 2, n + 1), Q.device)
         for t in (tail_k, tail_v):
-            assert t is None or (t.dtype == torch.bfloat16 and t.is_contiguous() and tuple(t.shape) == (shape.B, shape.Hkv, 64, shape.D))
+            assert t is None or (t.dtype == Q.dtype and t.is_contiguous() and tuple(t.shape) == (shape.B, shape.Hkv, 64, shape.D))
         _check(lib().hs_decode_attn_tail(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(tail_k),
                                          _ptr(tail_v), int(tail_len), _ptr(O), _ptr(lse), _ptr(workspace), _stream()))
         return O, lse
@@ -257,10 +269,10 @@ def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, ls
     return O, lse
 
 
-def bits_to_bf16_tensor(bits, device="cuda"):
-    """numpy uint16 bit patterns -> torch bf16 tensor on the device (same bits)."""
+def bits_to_bf16_tensor(bits, device="cuda", dtype=torch.bfloat16):
+    """numpy uint16 bit patterns -> torch bf16 (or fp16) tensor on the device (same bits)."""
     t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
-    return t.to(device).view(torch.bfloat16)
+    return t.to(device).view(dtype)
 
 
 def bf16_tensor_to_bits(t):

@@ -21,6 +21,7 @@ int check_shape(const hs_shape* s) {
   if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->L <= 0) return HS_EINVAL;
   if (s->D != HS_D || s->tile != HS_BT) return HS_EUNSUPPORTED;
   if (s->L % HS_BT != 0 || s->Hq % s->Hkv != 0) return HS_EUNSUPPORTED;
+  if (s->dtype != HS_BF16 && s->dtype != HS_FP16) return HS_EUNSUPPORTED;
   if (s->Hq / s->Hkv > 8) return HS_EUNSUPPORTED;
   if (s->B > 65535 || s->Hkv > 65535 || (int64_t)s->B * s->Hkv > 65535) return HS_EUNSUPPORTED;
   return HS_OK;
@@ -120,7 +121,7 @@ int decode_common(const hs_shape* shape, float scale, int32_t n_splits, const vo
   const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
                                         (const uint16_t*)Q, hs_make_kv_dev(kv), (const uint16_t*)tail_k,
                                         (const uint16_t*)tail_v, tail_len, (uint16_t*)O, LSE, (float*)workspace,
-                                        (hipStream_t)stream, phases);
+                                        (hipStream_t)stream, phases, shape->dtype);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }
@@ -277,7 +278,7 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
       if (workspace == nullptr || ((uintptr_t)workspace & 7u)) return HS_EINVAL;
       if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
       e = hs_launch_score((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
-                          policy->element_rule, (double*)workspace, s);
+                          policy->element_rule, shape->dtype, (double*)workspace, s);
       if (e != hipSuccess) return hip_fail(e);
       e = hs_launch_select((const double*)workspace, rows, T, c[0], c[2], c[4], n_first, n_last, out->k_map,
                            out->v_map, s);
@@ -343,7 +344,7 @@ int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal, 
   if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
   const hipError_t e = hs_launch_prefill(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, Lq / HS_BT, scale,
                                          causal != 0, (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
-                                         (hipStream_t)stream);
+                                         (hipStream_t)stream, shape->dtype);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

@@ -46,8 +46,59 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x16_t __attribute__((ext_vector_type(16)));
+
 #define HS_D 128
 #define HS_BT 64
+
+// Element type dependent pieces (hs_shape.dtype): conversions and the matrix instructions.  The
+// 16-bit operand layouts of the bf16 and f16 forms of an instruction are the same, so everything
+// about tiles, pools and lanes is type independent.  Device code only.
+struct hs_u4x2 { uint4 lo, hi; };
+template <bool F16> struct hs_elem;
+template <> struct hs_elem<false> {
+  static __device__ __forceinline__ float to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+  static __device__ __forceinline__ float lo_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+  static __device__ __forceinline__ float hi_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // round to nearest even
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    bf2 v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
+  }
+  static __device__ __forceinline__ f32x4_t mma(uint4 a, uint4 b, f32x4_t c) {  // dense 16x16x32
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+  template <int ABID>
+  static __device__ __forceinline__ f32x4_t smma(uint4 a, uint4 b0, uint4 b1, f32x4_t c, int idx) {  // 2:4 16x16x64
+    const hs_u4x2 b{b0, b1};
+    return __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x16_t, b), c, idx, 0, ABID);
+  }
+};
+template <> struct hs_elem<true> {
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  static __device__ __forceinline__ float to_f32(uint32_t bits16) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+  }
+  static __device__ __forceinline__ float lo_f32(uint32_t pair) { return (float)__builtin_bit_cast(h2, pair)[0]; }
+  static __device__ __forceinline__ float hi_f32(uint32_t pair) { return (float)__builtin_bit_cast(h2, pair)[1]; }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // round to nearest even
+    h2 v;
+    v[0] = (_Float16)a;
+    v[1] = (_Float16)b;
+    return __builtin_bit_cast(uint32_t, v);
+  }
+  static __device__ __forceinline__ f32x4_t mma(uint4 a, uint4 b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+  template <int ABID>
+  static __device__ __forceinline__ f32x4_t smma(uint4 a, uint4 b0, uint4 b1, f32x4_t c, int idx) {
+    const hs_u4x2 b{b0, b1};
+    return __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x16_t, b), c, idx, 0, ABID);
+  }
+};
 
 struct hs_kv_dev {  // device-side view of hs_kv (passed by value to kernels)
   const uint8_t* k_dense; const uint8_t* k_nnz; const uint8_t* k_meta; const int32_t* k_map;
@@ -75,7 +126,7 @@ __host__ __device__ static inline int hs_v_group(int a, int q) {
 
 // launchers implemented in the kernel translation units; all return a hipError_t
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                           int B, int Hkv, int T, int rule, double* scores, hipStream_t st);
+                           int B, int Hkv, int T, int rule, int dtype, double* scores, hipStream_t st);
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
                             int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st);
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
@@ -89,6 +140,6 @@ hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out
 // dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D])
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
                             hs_kv_dev kv, const uint16_t* tail_k, const uint16_t* tail_v, int tail_len,
-                            uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases);
+                            uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases, int dtype);
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
-                             hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st);
+                             hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st, int dtype);

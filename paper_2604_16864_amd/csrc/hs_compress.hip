@@ -35,7 +35,7 @@ __device__ __forceinline__ void top2_emit(uint32_t mask, uint32_t x0, uint32_t x
   nib = i0 | (i1 << 2);
 }
 
-__device__ __forceinline__ double bf16_val(uint32_t bits) { return (double)__uint_as_float(bits << 16); }
+template <bool F16> __device__ __forceinline__ double elem_val(uint32_t bits) { return (double)hs_elem<F16>::to_f32(bits); }
 
 // ----------------------------------------------------------------------------------
 // Staging of one V tile [64 tokens][128 ch] into LDS with coalesced 16-byte loads.
@@ -57,6 +57,7 @@ __device__ __forceinline__ void stage_v_tile(const uint16_t* vt, int64_t tok_str
 // Tile scores: energy = sum K^2 + sum V^2 (skip ranking), loss_x = L1 norm of what the
 // 2:4 mask removes (Eq. 2c).  fp64, fixed reduction order.  scores = [3][rows][T].
 // ----------------------------------------------------------------------------------
+template <bool F16>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                     int64_t sb, int64_t sh, int64_t st, int Hkv, int T, int rule,
                                                     double* __restrict__ scores) {
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
       for (int q = 0; q < 4; q++) {
         const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
         const uint32_t m = top2_mask(x0, x1, x2, x3, rule);
-        const double f0 = bf16_val(x0), f1 = bf16_val(x1), f2 = bf16_val(x2), f3 = bf16_val(x3);
+        const double f0 = elem_val<F16>(x0), f1 = elem_val<F16>(x1), f2 = elem_val<F16>(x2), f3 = elem_val<F16>(x3);
         e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
         lk += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
       }
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
         const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
         const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
         const uint32_t m = top2_mask(x0, x1, x2, x3, rule);
-        const double f0 = bf16_val(x0), f1 = bf16_val(x1), f2 = bf16_val(x2), f3 = bf16_val(x3);
+        const double f0 = elem_val<F16>(x0), f1 = elem_val<F16>(x1), f2 = elem_val<F16>(x2), f3 = elem_val<F16>(x3);
         e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
         lv += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
       }
@@ -461,8 +462,11 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
 }  // namespace
 
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                           int T, int rule, double* scores, hipStream_t st) {
-  hipLaunchKernelGGL(score_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);
+                           int T, int rule, int dtype, double* scores, hipStream_t st) {
+  if (dtype == HS_FP16)
+    hipLaunchKernelGGL(score_kernel<true>, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);
+  else
+    hipLaunchKernelGGL(score_kernel<false>, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);
   return hipGetLastError();
 }
 

@@ -22,7 +22,6 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
 // streaming (non-temporal) 16-byte load: the packed cache is read once per call
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -30,21 +29,6 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p) {
   return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p)));
 }
 
-struct u4x2 { uint4 lo, hi; };
-__device__ __forceinline__ bf16x16_t as_bf16x16(uint4 lo, uint4 hi) {
-  u4x2 t{lo, hi};
-  return __builtin_bit_cast(bf16x16_t, t);
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
-  bf2 v;
-  v[0] = (__bf16)a;
-  v[1] = (__bf16)b;
-  return __builtin_bit_cast(uint32_t, v);
-}
-__device__ __forceinline__ float bf16_lo_f(uint32_t p) { return __uint_as_float(p << 16); }
-__device__ __forceinline__ float bf16_hi_f(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
 
 
 // Operand registers of one tile (K and V), filled by tile_load and consumed by tile_compute.
@@ -94,12 +78,17 @@ __device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& 
 }
 
 // One tile: GEMM1 (S^T = K Q^T), online softmax, GEMM2 (O^T += V^T P^T).
-template <int KM, int VM>
+// F16: element type (hs_elem).  With fp16 the running reference sits kShift = 8 binades under the
+// running maximum, so that numerators reach 2^8 and what fp16 flushes to zero is below 2^-32 of
+// the largest one (a context of 2^17 tokens then loses < 2^-15 of the sum); bf16 has the range.
+template <int KM, int VM, bool F16>
 __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const uint4 (&qb)[4], float scale_log2, int c,
                                              f32x4_t (&o)[8], float& m_run, float& l_run) {
   const bool k_sparse = KM == 0 || (KM == 2 && r.mk < 0);
   const bool v_sparse = VM == 0 || (VM == 2 && r.mv < 0);
   constexpr int kNK = TileRegs<KM, VM>::kNK, kNV = TileRegs<KM, VM>::kNV;
+  typedef hs_elem<F16> E;
+  constexpr float kShift = F16 ? 8.f : 0.f;
   f32x4_t s[4];
   const int kidx[4] = {(int)r.km.x, (int)r.km.y, (int)r.km.z, (int)r.km.w};
   const int vidx[4] = {(int)r.vm.x, (int)r.vm.y, (int)r.vm.z, (int)r.vm.w};
@@ -108,17 +97,17 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
   if (k_sparse) {  // the 4 row blocks are independent chains
 #pragma unroll
     for (int m = 0; m < 4; m++)
-      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m]), as_bf16x16(qb[0], qb[1]), s[m], kidx[m], 0, 0);
+      s[m] = E::template smma<0>(r.k[2 * m], qb[0], qb[1], s[m], kidx[m]);
 #pragma unroll
     for (int m = 0; m < 4; m++)
-      s[m] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.k[2 * m + 1]), as_bf16x16(qb[2], qb[3]), s[m], kidx[m], 0, 1);
+      s[m] = E::template smma<1>(r.k[2 * m + 1], qb[2], qb[3], s[m], kidx[m]);
   }
 #pragma unroll
   for (int m = 0; m < 4; m++) {
     if (!k_sparse) {
 #pragma unroll
       for (int st = 0; st < 4; st++)
-        s[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[(4 * m + st) % kNK]), as_bf16x8(qb[st]), s[m], 0, 0, 0);
+        s[m] = E::mma(r.k[(4 * m + st) % kNK], qb[st], s[m]);
     }
   }
   // online softmax for column c (log2 domain)
@@ -129,7 +118,7 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
     for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][i]);
   mx = fmaxf(mx, __shfl_xor(mx, 16));
   mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m_run, mx * scale_log2);
+  const float m_new = fmaxf(m_run, mx * scale_log2 - kShift);
   const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
   m_run = m_new;
   float psum = 0.f;
@@ -146,13 +135,13 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
       p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][i], scale_log2, -m_new));
       psum += p[i];
     }
-    hi[0] = pack_bf16(p[0], p[1]);
-    hi[1] = pack_bf16(p[2], p[3]);
-    rsd[0] = p[0] - bf16_lo_f(hi[0]);
-    rsd[1] = p[1] - bf16_hi_f(hi[0]);
-    rsd[2] = p[2] - bf16_lo_f(hi[1]);
-    rsd[3] = p[3] - bf16_hi_f(hi[1]);
-    const uint32_t lo0 = pack_bf16(rsd[0], rsd[1]), lo1 = pack_bf16(rsd[2], rsd[3]);
+    hi[0] = E::pack2(p[0], p[1]);
+    hi[1] = E::pack2(p[2], p[3]);
+    rsd[0] = p[0] - E::lo_f32(hi[0]);
+    rsd[1] = p[1] - E::hi_f32(hi[0]);
+    rsd[2] = p[2] - E::lo_f32(hi[1]);
+    rsd[3] = p[3] - E::hi_f32(hi[1]);
+    const uint32_t lo0 = E::pack2(rsd[0], rsd[1]), lo1 = E::pack2(rsd[2], rsd[3]);
     pb[2 * m] = c < 8 ? hi[0] : lo0;
     pb[2 * m + 1] = c < 8 ? hi[1] : lo1;
   }
@@ -165,12 +154,12 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
   for (int mb = 0; mb < 8; mb++) {
     if (v_sparse) {
       if (mb & 1)
-        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], vidx[mb >> 1], 0, 1);
+        o[mb] = E::template smma<1>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
       else
-        o[mb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(r.v[mb]), as_bf16x16(pb_lo, pb_hi), o[mb], vidx[mb >> 1], 0, 0);
+        o[mb] = E::template smma<0>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
     } else {
-      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb) % kNV]), as_bf16x8(pb_lo), o[mb], 0, 0, 0);
-      o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[(2 * mb + 1) % kNV]), as_bf16x8(pb_hi), o[mb], 0, 0, 0);
+      o[mb] = E::mma(r.v[(2 * mb) % kNV], pb_lo, o[mb]);
+      o[mb] = E::mma(r.v[(2 * mb + 1) % kNV], pb_hi, o[mb]);
     }
   }
 }
@@ -181,7 +170,7 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
 // with a two-deep register pipeline (the loads of tile i+1 are in flight while tile i is
 // being multiplied).
 // Each workgroup emits a normalised partial output and its log-sum-exp per query head.
-template <int KM, int VM, bool UNIFORM>
+template <int KM, int VM, bool UNIFORM, bool F16>
 __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2,
                                                                              int n_splits, int per,
                                                                              const uint16_t* __restrict__ Q,
@@ -247,7 +236,7 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
 #pragma unroll
       for (int d = 0; d < DEPTH; d++) {
         if (go && have[d]) {  // tiles are consumed in issue order: the first empty slot ends the round
-          tile_compute<KM, VM>(ring[d], qb, scale_log2, c, o, m_run, l_run);
+          tile_compute<KM, VM, F16>(ring[d], qb, scale_log2, c, o, m_run, l_run);
           have[d] = act != 0ull;
           if (have[d]) {
             const int i = __builtin_ctzll(act);
@@ -312,6 +301,7 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
 // merges") needs device-scope visibility between workgroups on different XCDs, and both ways
 // of getting it (a device-wide fence per workgroup, or write-through stores and L2-bypassing
 // loads) measured slower than this launch.
+template <bool F16>
 __global__ __launch_bounds__(256) void decode_merge_kernel(int n_splits, const float* __restrict__ ws_o,
                                                            const float* __restrict__ ws_l, uint16_t* __restrict__ O,
                                                            float* __restrict__ LSE) {
@@ -352,18 +342,17 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(int n_splits, const f
       }
     }
     const float out = d > 0.f ? num / d : 0.f;
-    O[(int64_t)hq * HS_D + tid] = (uint16_t)(pack_bf16(out, 0.f) & 0xffffu);
+    O[(int64_t)hq * HS_D + tid] = (uint16_t)(hs_elem<F16>::pack2(out, 0.f) & 0xffffu);
     if (LSE != nullptr && tid == 0) LSE[hq] = d > 0.f ? Mt + __logf(d) : -INFINITY;
   }
 }
 
 
-__device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
 // Partial for the dense tail (at most one tile of not yet compressed tokens): plain fp32
 // attention of the G query heads of one kv head over tail_len tokens, written as split `slot`.
 // One workgroup per (kv head, b); thread t: phase 1 token t%64 for heads t/64 and t/64 + 4,
 // phase 3 channel t%128 for heads t/128, t/128 + 2, ...
+template <bool F16>
 __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float scale_log2, int n_slots, int slot,
                                                           int tail_len, const uint16_t* __restrict__ Q,
                                                           const uint16_t* __restrict__ TK,
@@ -377,7 +366,7 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float
   const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;
   const uint16_t* tk = TK + ((int64_t)b * Hkv + hkv) * HS_BT * HS_D;
   const uint16_t* tv = TV + ((int64_t)b * Hkv + hkv) * HS_BT * HS_D;
-  for (int i = tid; i < G * HS_D; i += 256) sq[i / HS_D][i % HS_D] = bf16_val(Q[hq0 * HS_D + i]);
+  for (int i = tid; i < G * HS_D; i += 256) sq[i / HS_D][i % HS_D] = hs_elem<F16>::to_f32(Q[hq0 * HS_D + i]);
   __syncthreads();
   {  // scores (log2 units) and softmax numerators: wave w serves heads w and w + 4, lane = token
     const int tok = tid & 63, w = tid >> 6;
@@ -390,8 +379,8 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float
           const uint32_t wds[4] = {kk.x, kk.y, kk.z, kk.w};
 #pragma unroll
           for (int e = 0; e < 4; e++) {
-            acc = fmaf(__uint_as_float(wds[e] << 16), sq[g][c + 2 * e], acc);
-            acc = fmaf(__uint_as_float(wds[e] & 0xffff0000u), sq[g][c + 2 * e + 1], acc);
+            acc = fmaf(hs_elem<F16>::lo_f32(wds[e]), sq[g][c + 2 * e], acc);
+            acc = fmaf(hs_elem<F16>::hi_f32(wds[e]), sq[g][c + 2 * e + 1], acc);
           }
         }
         sc = acc * scale_log2;
@@ -415,7 +404,7 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float
     const int ch = tid & 127;
     for (int g = tid >> 7; g < G; g += 2) {
       float acc = 0.f;
-      for (int t = 0; t < tail_len; t++) acc = fmaf(sp[g][t], bf16_val(tv[(int64_t)t * HS_D + ch]), acc);
+      for (int t = 0; t < tail_len; t++) acc = fmaf(sp[g][t], hs_elem<F16>::to_f32(tv[(int64_t)t * HS_D + ch]), acc);
       const float l = sl_[g];
       ws_o[((hq0 + g) * n_slots + slot) * HS_D + ch] = l > 0.f ? acc / l : 0.f;
     }
@@ -427,16 +416,21 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float
 // Workspace: [partial O (normalised) [B*Hq][n_splits][128] fp32][partial LSE [B*Hq][n_splits] fp32].
 template <int KM, int VM, bool UNIFORM>
 static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T, float sl2, int n_splits, int per,
-                               const uint16_t* Q, const hs_kv_dev& kv, float* wo, float* wl) {
-  hipLaunchKernelGGL((decode_split_kernel<KM, VM, UNIFORM>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits, per,
-                     Q, kv, wo, wl);
+                               const uint16_t* Q, const hs_kv_dev& kv, float* wo, float* wl, bool f16) {
+  if (f16)
+    hipLaunchKernelGGL((decode_split_kernel<KM, VM, UNIFORM, true>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits,
+                       per, Q, kv, wo, wl);
+  else
+    hipLaunchKernelGGL((decode_split_kernel<KM, VM, UNIFORM, false>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits,
+                       per, Q, kv, wo, wl);
   return hipGetLastError();
 }
 
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_work, const uint16_t* Q, hs_kv_dev kv,
                             const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, uint16_t* O, float* LSE,
-                            float* ws, hipStream_t st, int phases) {
+                            float* ws, hipStream_t st, int phases, int dtype) {
   const dim3 grid(n_work, Hkv, B);
+  const bool f16 = dtype == HS_FP16;
   const float sl2 = scale * kLog2e;
   const int per = (T + n_work - 1) / n_work;
   // partial slots per query head: the n_work cache splits, then one for the dense tail if there is
@@ -449,10 +443,10 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_wo
   hipError_t e = hipSuccess;
   if (phases & 1) {
 #define HS_GO(KM_, VM_)                                                                                         \
-  e = kv.uniform ? launch_split<KM_, VM_, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl)       \
-                 : launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl);     \
+  e = kv.uniform ? launch_split<KM_, VM_, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16)  \
+                 : launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16); \
   break
-#define HS_GO_DYN(KM_, VM_) e = launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl); break
+#define HS_GO_DYN(KM_, VM_) e = launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16); break
   switch (km * 3 + vm) {
     case 0: HS_GO(0, 0);
     case 1: HS_GO(0, 1);
@@ -468,11 +462,18 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_wo
 #undef HS_GO_DYN
   }
   if (e == hipSuccess && (phases & 1) && tail_len >= 0) {
-    hipLaunchKernelGGL(decode_tail_kernel, dim3(Hkv, B), dim3(256), 0, st, Hq, Hkv, sl2, n_splits, n_work, tail_len, Q,
-                       tail_k, tail_v, wo, wl);
+    if (f16)
+      hipLaunchKernelGGL(decode_tail_kernel<true>, dim3(Hkv, B), dim3(256), 0, st, Hq, Hkv, sl2, n_splits, n_work,
+                         tail_len, Q, tail_k, tail_v, wo, wl);
+    else
+      hipLaunchKernelGGL(decode_tail_kernel<false>, dim3(Hkv, B), dim3(256), 0, st, Hq, Hkv, sl2, n_splits, n_work,
+                         tail_len, Q, tail_k, tail_v, wo, wl);
     e = hipGetLastError();
   }
   if (e != hipSuccess || !(phases & 2)) return e;
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);
+  if (f16)
+    hipLaunchKernelGGL(decode_merge_kernel<true>, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);
+  else
+    hipLaunchKernelGGL(decode_merge_kernel<false>, dim3(B * Hq), dim3(256), 0, st, n_splits, wo, wl, O, LSE);
   return hipGetLastError();
 }

@@ -24,7 +24,6 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
   bf2 v;
@@ -140,7 +139,6 @@ __device__ __forceinline__ void stage_wait(int tiles_in_flight) {
 }
 
 union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the dense 16x16x32 one
-  bf16x16_t v;
   uint4 q[2];
   uint32_t u[8];
 };
@@ -150,12 +148,19 @@ union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the de
 // keys-dense / values-2:4 setting of Sec. V-A carries no dynamic dispatch).
 // NB: column blocks (of 16 queries) per wave: a wave owns a slab of 16*NB query positions of one
 // head.  NB = 2 fits 2 waves per SIMD (NB = 4, 1 wave per SIMD, measured 1.3-1.4x slower).
-template <int KM, int VM, int NB>
+// F16: element type (hs_elem).  fp16 numerators have 11 significant bits, so P enters GEMM2 as one
+// term; their reference is kept kShift = 8 binades under the running maximum (range, see decode)
+// and renewed before a numerator can reach the fp16 maximum.
+template <int KM, int VM, int NB, bool F16>
 __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, int Hkv, int T, int Lq, int off,
                                                                       float scale_log2, int causal,
                                                                       const uint16_t* __restrict__ Q, hs_kv_dev kv,
                                                                       uint16_t* __restrict__ O,
                                                                       float* __restrict__ LSE) {
+  typedef hs_elem<F16> E;
+  constexpr float kShift = F16 ? 8.f : 0.f;
+  constexpr float kRedo = F16 ? 0x1p14f : 0x1p40f;  // partial row sum above which the reference is renewed
+  constexpr int NT = F16 ? 1 : 2;                   // terms of P
   constexpr int QS = 16 * NB;  // query positions per slab
   constexpr int NS = n_stages<KM, VM>(), D = NS - 1;  // ring size, prefetch distance in tiles
   // MID: the per-tile barrier sits between softmax and GEMM2 instead of at the end of the
@@ -304,12 +309,12 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         for (int nb = 0; nb < NB; nb++)
 #pragma unroll
           for (int m = 0; m < 4; m++)
-            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ak[2 * m]), qb[nb][0].v, s[m][nb], kidx[m], 0, 0);
+            s[m][nb] = E::template smma<0>(ak[2 * m], qb[nb][0].q[0], qb[nb][0].q[1], s[m][nb], kidx[m]);
 #pragma unroll
         for (int nb = 0; nb < NB; nb++)
 #pragma unroll
           for (int m = 0; m < 4; m++)
-            s[m][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(ak[2 * m + 1]), qb[nb][1].v, s[m][nb], kidx[m], 0, 1);
+            s[m][nb] = E::template smma<1>(ak[2 * m + 1], qb[nb][1].q[0], qb[nb][1].q[1], s[m][nb], kidx[m]);
       } else {
 #pragma unroll
         for (int m = 0; m < 4; m++) {
@@ -320,7 +325,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
           for (int st = 0; st < 4; st++)
 #pragma unroll
             for (int nb = 0; nb < NB; nb++)
-              s[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ak[st]), as_bf16x8(qb[nb][st >> 1].q[st & 1]), s[m][nb], 0, 0, 0);
+              s[m][nb] = E::mma(ak[st], qb[nb][st >> 1].q[st & 1], s[m][nb]);
         }
       }
       if (V_EARLY) {  // V operands: on their way while the softmax runs
@@ -363,8 +368,13 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
               p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
               acc += p[i];
             }
-            split_hi_lo(p[0], p[1], sc, ph[nb].u[2 * m], pl[nb].u[2 * m]);
-            split_hi_lo(p[2], p[3], sc, ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
+            if (F16) {
+              ph[nb].u[2 * m] = E::pack2(p[0], p[1]);
+              ph[nb].u[2 * m + 1] = E::pack2(p[2], p[3]);
+            } else {
+              split_hi_lo(p[0], p[1], sc, ph[nb].u[2 * m], pl[nb].u[2 * m]);
+              split_hi_lo(p[2], p[3], sc, ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
+            }
           }
           psum[nb] = acc;
         }
@@ -372,7 +382,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       softmax_tile();
       bool redo = false;
 #pragma unroll
-      for (int nb = 0; nb < NB; nb++) redo = redo || !(psum[nb] <= 0x1p40f) || !(m_run[nb] > -INFINITY);
+      for (int nb = 0; nb < NB; nb++) redo = redo || !(psum[nb] <= kRedo) || !(m_run[nb] > -INFINITY);
       if (__any(redo)) {
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
@@ -381,7 +391,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
           for (int m = 0; m < 4; m++)
 #pragma unroll
             for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][nb][i]);
-          mx *= scale_log2;
+          mx = mx * scale_log2 - kShift;
           mx = fmaxf(mx, __shfl_xor(mx, 16));
           mx = fmaxf(mx, __shfl_xor(mx, 32));
           // a column with nothing visible in this tile keeps its reference
@@ -422,30 +432,28 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         }
         const int vidx[4] = {(int)vix.x, (int)vix.y, (int)vix.z, (int)vix.w};
 #pragma unroll
-        for (int t2 = 0; t2 < 2; t2++)  // first the upper-half term of every block, then the remainder
+        for (int t2 = 0; t2 < NT; t2++)  // first the upper-half term of every block, then the remainder
 #pragma unroll
           for (int nb = 0; nb < NB; nb++)
 #pragma unroll
             for (int mb = 0; mb < 8; mb++) {
-              const bf16x16_t bp = t2 == 0 ? ph[nb].v : pl[nb].v;
+              const B16& bp = t2 == 0 ? ph[nb] : pl[nb];
               if (mb & 1)
-                o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bp, o[mb][nb], vidx[mb >> 1], 0, 1);
+                o[mb][nb] = E::template smma<1>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
               else
-                o[mb][nb] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(as_bf16x8(av[mb]), bp, o[mb][nb], vidx[mb >> 1], 0, 0);
+                o[mb][nb] = E::template smma<0>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
             }
       } else {
 #pragma unroll
         for (int mb = 0; mb < 8; mb++) {
           const uint4 a0 = vl[(2 * mb) * 64 + l], a1 = vl[(2 * mb + 1) * 64 + l];
 #pragma unroll
-          for (int t2 = 0; t2 < 2; t2++)
+          for (int t2 = 0; t2 < NT; t2++)
 #pragma unroll
             for (int h = 0; h < 2; h++)
 #pragma unroll
               for (int nb = 0; nb < NB; nb++)
-                o[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(h == 0 ? a0 : a1),
-                                                                   as_bf16x8(t2 == 0 ? ph[nb].q[h] : pl[nb].q[h]),
-                                                                   o[mb][nb], 0, 0, 0);
+                o[mb][nb] = E::mma(h == 0 ? a0 : a1, t2 == 0 ? ph[nb].q[h] : pl[nb].q[h], o[mb][nb]);
         }
       }
     }
@@ -475,8 +483,8 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     uint16_t* op = O + qrow * HS_D + 4 * a;
 #pragma unroll
     for (int mb = 0; mb < 8; mb++) {
-      const uint2 v = make_uint2(pack_bf16(o[mb][nb][0] * inv, o[mb][nb][1] * inv),
-                                 pack_bf16(o[mb][nb][2] * inv, o[mb][nb][3] * inv));
+      const uint2 v = make_uint2(E::pack2(o[mb][nb][0] * inv, o[mb][nb][1] * inv),
+                                 E::pack2(o[mb][nb][2] * inv, o[mb][nb][3] * inv));
       *reinterpret_cast<uint2*>(op + 16 * mb) = v;
     }
     if (LSE != nullptr && a == 0)
@@ -488,21 +496,26 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 
 template <int KM, int VM, int NB>
 static hipError_t launch_prefill(int B, int Hq, int Hkv, int T, int Lq, float sl2, int causal, const uint16_t* Q,
-                                 const hs_kv_dev& kv, uint16_t* O, float* LSE, hipStream_t st) {
+                                 const hs_kv_dev& kv, uint16_t* O, float* LSE, hipStream_t st, bool f16) {
   const int G = Hq / Hkv;
   const int n_groups = ((Lq / (16 * NB)) * G + 3) / 4;
-  hipLaunchKernelGGL((prefill_kernel<KM, VM, NB>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
-                     T * HS_BT - Lq, sl2, causal, Q, kv, O, LSE);
+  if (f16)
+    hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, true>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
+                       T * HS_BT - Lq, sl2, causal, Q, kv, O, LSE);
+  else
+    hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, false>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
+                       T * HS_BT - Lq, sl2, causal, Q, kv, O, LSE);
   return hipGetLastError();
 }
 
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
-                             hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st) {
+                             hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st, int dtype) {
+  const bool f16 = dtype == HS_FP16;
   const float sl2 = scale * kLog2e;
   const int Lq = Tq * HS_BT;
   const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
   const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
-#define HS_GO(KM_, VM_) return launch_prefill<KM_, VM_, 2>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st)
+#define HS_GO(KM_, VM_) return launch_prefill<KM_, VM_, 2>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st, f16)
   switch (km * 3 + vm) {
     case 0: HS_GO(0, 0);
     case 1: HS_GO(0, 1);

@@ -29,39 +29,50 @@ def f32_to_bf16_bits(x):
     return (r >> np.uint32(16)).astype(np.uint16)
 
 
+def f32_to_f16_bits(x):
+    """Round-to-nearest-even fp32 -> IEEE fp16 bit patterns (uint16)."""
+    return np.asarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits):
+    return np.ascontiguousarray(np.asarray(bits, dtype=np.uint16)).view(np.float16).astype(np.float32)
+
+
 def bf16_bits_to_f32(bits):
     return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def normal_bf16(rng, shape, chunk=1 << 24):
-    """N(0,1) draws rounded to bf16, generated in chunks to bound host memory."""
+def normal_bf16(rng, shape, chunk=1 << 24, dtype="bf16"):
+    """N(0,1) draws rounded to bf16 (or fp16), generated in chunks to bound host memory."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16)
+    rnd = f32_to_bf16_bits if dtype == "bf16" else f32_to_f16_bits
     for s in range(0, n, chunk):
         e = min(n, s + chunk)
-        out[s:e] = f32_to_bf16_bits(rng.standard_normal(e - s, dtype=np.float32))
+        out[s:e] = rnd(rng.standard_normal(e - s, dtype=np.float32))
     return out.reshape(shape)
 
 
-def make_qkv(B, Hq, Hkv, L, D, Lq, seed, k_outliers=False):
-    """Q [B,Hq,Lq,D], K,V [B,Hkv,L,D] as bf16 bit patterns.
+def make_qkv(B, Hq, Hkv, L, D, Lq, seed, k_outliers=False, dtype="bf16"):
+    """Q [B,Hq,Lq,D], K,V [B,Hkv,L,D] as bf16 (or fp16) bit patterns.
 
     One PCG64 stream per tensor: seed+0 -> Q, seed+1 -> K, seed+2 -> V,
     seed+3 -> key channel scales (log-uniform in [0.1, 10], one per
     (kv head, channel), constant over tokens).
     """
-    Q = normal_bf16(np.random.Generator(np.random.PCG64(seed + 0)), (B, Hq, Lq, D))
-    V = normal_bf16(np.random.Generator(np.random.PCG64(seed + 2)), (B, Hkv, L, D))
+    Q = normal_bf16(np.random.Generator(np.random.PCG64(seed + 0)), (B, Hq, Lq, D), dtype=dtype)
+    V = normal_bf16(np.random.Generator(np.random.PCG64(seed + 2)), (B, Hkv, L, D), dtype=dtype)
     rk = np.random.Generator(np.random.PCG64(seed + 1))
+    rnd = f32_to_bf16_bits if dtype == "bf16" else f32_to_f16_bits
     if not k_outliers:
-        K = normal_bf16(rk, (B, Hkv, L, D))
+        K = normal_bf16(rk, (B, Hkv, L, D), dtype=dtype)
     else:
         rs = np.random.Generator(np.random.PCG64(seed + 3))
         scales = np.exp(rs.uniform(np.log(0.1), np.log(10.0), size=(Hkv, D))).astype(np.float32)
         K = np.empty((B, Hkv, L, D), dtype=np.uint16)
         for b in range(B):
             for h in range(Hkv):
-                K[b, h] = f32_to_bf16_bits(rk.standard_normal((L, D), dtype=np.float32) * scales[h][None, :])
+                K[b, h] = rnd(rk.standard_normal((L, D), dtype=np.float32) * scales[h][None, :])
     return Q, K, V
 
 

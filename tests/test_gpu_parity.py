@@ -15,8 +15,8 @@ pytestmark = pytest.mark.gpu
 MAX_TOL, MEAN_TOL = 1e-2, 2e-3
 
 
-def _dev(bits):
-    return hb.bits_to_bf16_tensor(bits, "cuda")
+def _dev(bits, dtype="bf16"):
+    return hb.bits_to_bf16_tensor(bits, "cuda", torch.float16 if dtype == "fp16" else torch.bfloat16)
 
 
 def _f32(t):
@@ -42,15 +42,15 @@ def assert_lse_close(lse, ref, what):
     assert np.allclose(lse[~inf], ref[~inf], rtol=1e-4, atol=1e-4), (what, np.abs(lse[~inf] - ref[~inf]).max())
 
 
-def compress_both(B, Hq, Hkv, L, K, V, **pol):
-    sh = hb.make_shape(B, Hq, Hkv, L)
+def compress_both(B, Hq, Hkv, L, K, V, dtype="bf16", **pol):
+    sh = hb.make_shape(B, Hq, Hkv, L, dtype=hb.FP16 if dtype == "fp16" else hb.BF16)
     lib_pol = dict(pol)
     if "element_rule" in lib_pol:
         lib_pol["element_rule"] = {"magnitude": hb.RULE_MAGNITUDE, "nonzero": hb.RULE_NONZERO}[lib_pol["element_rule"]]
     policy = hb.make_policy(**lib_pol)
-    kv = hb.compress_kv(sh, policy, _dev(K), _dev(V))
+    kv = hb.compress_kv(sh, policy, _dev(K, dtype), _dev(V, dtype))
     torch.cuda.synchronize()
-    pk, pv, info = orc.compress_kv(K, V, Bt=64, **pol)
+    pk, pv, info = orc.compress_kv(K, V, Bt=64, dtype=dtype, **pol)
     return sh, kv, pk, pv, info
 
 
@@ -529,6 +529,73 @@ def test_random_shapes_and_policies(seed):
     Odr, Ldr = orc.attention_decode(q, pk, pv)
     assert_close(_f32(Od), Odr, f"decode splits {ns} " + what)
     assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode lse " + what)
+
+
+# ------------------------------------------------------------------ fp16 (the paper's element type)
+# fp16 output rounding alone is 8x finer than bf16's, so the same bars leave more room; the values checked
+# are the same ones as for bf16.
+@pytest.mark.parametrize("pol", [dict(), dict(sparse_frac_k=0.0, sparse_frac_v=0.0), dict(sparse_frac_k=0.0),
+                                 dict(skip_frac=0.25, sparse_frac_k=0.5, sparse_frac_v=0.7)])
+def test_fp16_all_stages(pol):
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 12
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=180, k_outliers=True, dtype="fp16")
+    K[0, 0, 5, :8] = wl.f32_to_f16_bits(np.array([1, 1, -1, 1, 0, -0.0, 0, 0], dtype=np.float32))    # ties and zeros
+    V[0, 1, 8:12, 7] = wl.f32_to_f16_bits(np.array([6e-8, -6e-8, 1e-7, 0], dtype=np.float32))        # subnormals
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, dtype="fp16", **pol)
+    check_packed_bit_exact(sh, kv, pk, pv)
+    O, LSE = hb.prefill_attn(sh, _dev(Q, "fp16"), kv)
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(B, Hq, L, 160, seed=181, extra=[(0, 0, 0), (B - 1, Hq - 1, L - 1)])
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    assert_close(_f32(O)[idx], Or, f"fp16 prefill {sorted(pol)}")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "fp16 prefill lse")
+    assert np.abs(_f32(O)[idx] - Or).mean() / np.abs(Or).mean() < 4e-4        # one fp16 term of P is enough
+    q = Q[:, :, -1, :].copy()
+    for ns in (0, 5):
+        Od, LSEd = hb.decode_attn(sh, _dev(q, "fp16"), kv, n_splits=ns)
+        torch.cuda.synchronize()
+        Odr, Ldr = orc.attention_decode(q, pk, pv)
+        assert_close(_f32(Od), Odr, f"fp16 decode {sorted(pol)} splits {ns}")
+        assert_lse_close(LSEd.cpu().numpy(), Ldr, "fp16 decode lse")
+    Kt, Vt = K[:, :, :64].copy(), V[:, :, :64].copy()
+    Od, LSEd = hb.decode_attn(sh, _dev(q, "fp16"), kv, tail_k=_dev(Kt, "fp16"), tail_v=_dev(Vt, "fp16"), tail_len=9)
+    torch.cuda.synchronize()
+    Odr, Ldr = orc.attention_decode(q, pk, pv, tail_k=Kt, tail_v=Vt, tail_len=9)
+    assert_close(_f32(Od), Odr, "fp16 decode with tail")
+
+
+def test_fp16_large_logits_and_long_flat_rows():
+    """fp16 numerators: the reference has to be renewed before a numerator reaches 65504 (keys that grow
+    along the sequence), and small numerators of a long, flat row must not be flushed away."""
+    B, Hq, Hkv, L = 1, 4, 1, 64 * 24
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=190, dtype="fp16")
+    Kf = wl.f16_bits_to_f32(K)
+    ramp = np.linspace(0.05, 6.0, L, dtype=np.float32)[None, None, :, None]     # logits grow to the hundreds
+    Kb = wl.f32_to_f16_bits(Kf * ramp)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Kb, V, dtype="fp16")
+    O, LSE = hb.prefill_attn(sh, _dev(Q, "fp16"), kv)
+    Od, LSEd = hb.decode_attn(sh, _dev(Q[:, :, -1, :].copy(), "fp16"), kv)
+    torch.cuda.synchronize()
+    rows = [(0, h, i) for h in range(Hq) for i in range(0, L, 7)] + [(0, h, L - 1) for h in range(Hq)]
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    assert_close(_f32(O)[idx], Or, "fp16 prefill growing logits")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "fp16 prefill growing logits lse")
+    Odr, Ldr = orc.attention_decode(Q[:, :, -1, :].copy(), pk, pv)
+    assert_close(_f32(Od), Odr, "fp16 decode growing logits")
+    # flat row: one key far above 1500 equal ones; the many small numerators carry weight together
+    Kz = np.zeros_like(K)
+    Kz[0, 0, 100] = wl.f32_to_f16_bits(Q[0, 0, -1].view(np.float16).astype(np.float32) * 1.23)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Kz, V, dtype="fp16", sparse_frac_k=0.0, sparse_frac_v=0.0)
+    Od, LSEd = hb.decode_attn(sh, _dev(Q[:, :, -1, :].copy(), "fp16"), kv, n_splits=1)
+    O, LSE = hb.prefill_attn(sh, _dev(Q, "fp16"), kv)
+    torch.cuda.synchronize()
+    Odr, Ldr = orc.attention_decode(Q[:, :, -1, :].copy(), pk, pv)
+    assert_close(_f32(Od), Odr, "fp16 decode flat row")
+    assert_lse_close(LSEd.cpu().numpy(), Ldr, "fp16 decode flat row lse")
+    Or, Lr = orc.attention_rows(Q, pk, pv, [(0, 0, L - 1)], causal=True)
+    assert_close(_f32(O)[0, 0, L - 1][None], Or, "fp16 prefill flat row")
 
 
 # ------------------------------------------------------------------ edges and errors

@@ -415,6 +415,34 @@ def test_append_in_tile_order_rebuilds_the_one_shot_cache():
     assert (orc.unpack_tensor(pk2) == orc.unpack_tensor(pk1)).all()
 
 
+def test_fp16_patterns_are_read_as_ieee_binary16():
+    """The fp16 path differs from bf16 only in what the 16-bit patterns mean: same masks and packed bits,
+    values per IEEE binary16 (checked on hand-written patterns and against struct's 'e' format), scores and
+    attention computed on those values (library SDPA on the converted tensors)."""
+    import struct
+    pats = np.array([0x3C00, 0xC000, 0x0001, 0x0400, 0x7BFF, 0x3555, 0x8000], dtype=np.uint16)
+    want = [1.0, -2.0, 2.0 ** -24, 2.0 ** -14, 65504.0, struct.unpack("<e", struct.pack("<H", 0x3555))[0], -0.0]
+    assert orc.to_f64(pats, "fp16").tolist() == want
+    assert orc.to_f64(np.array([0x3F80, 0xC000], dtype=np.uint16), "bf16").tolist() == [1.0, -2.0]
+    rng = np.random.default_rng(13)
+    K = wl.f32_to_f16_bits(rng.standard_normal((1, 2, 48, 16)).astype(np.float32))
+    V = wl.f32_to_f16_bits(rng.standard_normal((1, 2, 48, 16)).astype(np.float32))
+    q = wl.f32_to_f16_bits(rng.standard_normal((1, 4, 16)).astype(np.float32))
+    pk, pv, info = orc.compress_kv(K, V, Bt=16, dtype="fp16", skip_frac=1 / 3, sparse_frac_k=0.5)
+    pkb, pvb, infob = orc.compress_kv(K, V, Bt=16, dtype="bf16", state_k=info["state_k"], state_v=info["state_v"])
+    assert (info["mask_k"] == infob["mask_k"]).all() and (pk.nnz == pkb.nnz).all() and (pv.meta == pvb.meta).all()
+    f = lambda b: np.ascontiguousarray(b).view(np.float16).astype(np.float64)
+    e = (f(K) ** 2).reshape(1, 2, 3, -1).sum(-1) + (f(V) ** 2).reshape(1, 2, 3, -1).sum(-1)
+    assert np.allclose(info["energy"], e, rtol=1e-13)
+    assert (np.argmin(e, axis=-1) == np.argmax(pk.map == 0, axis=-1)).all()          # one of three tiles skipped
+    O, LSE = orc.attention_decode(q, pk, pv)
+    Ku, Vu = f(orc.unpack_tensor(pk)), f(orc.unpack_tensor(pv))
+    for h in range(4):
+        vis = np.repeat(pk.map[0, h // 2] != 0, 16)
+        ref = _sdpa(f(q)[0, h][None, None, None, :], Ku[0, h // 2][vis][None, None], Vu[0, h // 2][vis][None, None])
+        assert np.allclose(O[0, h], ref[0, 0, 0], rtol=1e-12, atol=1e-13)
+
+
 def test_brute_force_python_floats_tiny():
     """Whole path (prune, skip, attention) redone with Python lists and math.exp."""
     B, Hkv, G, L, D, Bt = 1, 1, 2, 16, 8, 4
