@@ -64,6 +64,14 @@ typedef struct {
   int32_t dtype; /* HS_BF16 or HS_FP16: element type of Q, K, V, O and of the pools */
 } hs_shape;
 
+/* Bit 30 of the magnitude of a v_map entry (bf16 caches only): the tile's stored values (all of a
+ * dense tile, the kept ones of a 2:4 tile) are every one exact in IEEE fp16 and are held in
+ * the pool in fp16 encoding -- same values, other bit patterns; hs_unpack_kv gives the bf16
+ * patterns back.  hs_compress_kv and hs_append_tile decide this per tile.  It lets attention
+ * multiply such a tile by softmax numerators in one fp16 term instead of two bf16 terms.
+ * Slot of an entry m != 0: (|m| & ~HS_MAP_F16) - 1; pool: dense if m > 0, 2:4 if m < 0. */
+enum { HS_MAP_F16 = 1 << 30 };
+
 /* Element types.  Pruning compares magnitudes through the bit patterns (bits & 0x7fff), which
  * orders both formats; packed values are copied bit for bit.  With fp16 the softmax
  * numerators enter the second product as one fp16 term (11 significant bits); with bf16 as

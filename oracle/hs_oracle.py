@@ -29,6 +29,19 @@ import numpy as np
 
 SKIP, DENSE, SPARSE24 = 0, 1, 2
 
+# A v_map entry of a bf16 cache may carry this bit in its magnitude: the tile's stored values are
+# kept in fp16 encoding (same values; see pack_tensor).  Slot = (|entry| & ~MAP_F16) - 1.
+MAP_F16 = 1 << 30
+
+
+def map_slot(entry):
+    """Pool slot (0-based) named by a non-zero map entry."""
+    return (abs(int(entry)) & ~MAP_F16) - 1
+
+
+def map_is_f16(entry):
+    return bool(abs(int(entry)) & MAP_F16)
+
 
 # ----------------------------------------------------------------------------
 # 16-bit patterns <-> real numbers
@@ -37,6 +50,26 @@ def bf16_to_f64(bits):
     """Exact value of bf16 bit patterns (uint16) as float64."""
     bits = np.asarray(bits, dtype=np.uint16)
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def bf16_bits_exact_in_f16(bits):
+    """Elementwise: the bf16 value is a finite number (or an infinity) that IEEE fp16 holds exactly."""
+    v = (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    with np.errstate(over="ignore"):
+        h = v.astype(np.float16)
+    return h.astype(np.float32) == v            # NaN compares unequal: stays bf16
+
+
+def bf16_bits_to_f16_bits(bits):
+    v = (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    with np.errstate(over="ignore"):
+        return v.astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_bf16_bits(bits):
+    """Exact for every value that bf16_bits_exact_in_f16 let through."""
+    v = np.ascontiguousarray(np.asarray(bits, dtype=np.uint16)).view(np.float16).astype(np.float32)
+    return (v.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
 
 
 def to_f64(bits, dtype="bf16"):
@@ -272,10 +305,21 @@ class PackedKV:
         return nd * tile + ns * (tile // 2 + tile // 16) + 4 * self.map.size
 
 
-def pack_tensor(kind, X_bits, mask, state, Bt):
+def _v_tile_store(stored_bits, v_f16):
+    """Encoding of one V tile's stored values (all of a dense tile, the kept ones of a 2:4 tile):
+    when the cache is bf16 and every stored value is exact in fp16, the tile is kept in fp16
+    encoding -- the softmax numerators can then enter the second product as one fp16 term (11
+    significant bits) instead of two bf16 terms -- and its map entry carries MAP_F16.
+    Returns (bits to store, flag)."""
+    if v_f16 and bf16_bits_exact_in_f16(stored_bits).all():
+        return bf16_bits_to_f16_bits(stored_bits), MAP_F16
+    return stored_bits, 0
+
+
+def pack_tensor(kind, X_bits, mask, state, Bt, v_f16=False):
     """Walk the blocks in sequence order (Sec. III-B) and fill the pools.
     Pools are rectangular [B, Hkv, cap, ...] with cap = the largest per-row count;
-    unused slots stay zero."""
+    unused slots stay zero.  v_f16: V tensor of a bf16 cache (see _v_tile_store)."""
     X_bits = np.asarray(X_bits, dtype=np.uint16)
     B, H, L, D = X_bits.shape
     T = L // Bt
@@ -295,13 +339,19 @@ def pack_tensor(kind, X_bits, mask, state, Bt):
                 m = mp[b, h, t]
                 tile = X_bits[b, h, t * Bt:(t + 1) * Bt]
                 if m > 0:
-                    dense[b, h, m - 1] = tile
+                    if kind == "v":
+                        dense[b, h, m - 1], flag = _v_tile_store(tile, v_f16)
+                        mp[b, h, t] = m | flag
+                    else:
+                        dense[b, h, m - 1] = tile
                 elif m < 0:
                     tm = mask[b, h, t * Bt:(t + 1) * Bt]
                     if kind == "k":
                         nnz[b, h, -m - 1], meta[b, h, -m - 1] = pack_k_tile(tile, tm)
                     else:
-                        nnz[b, h, -m - 1], meta[b, h, -m - 1] = pack_v_tile(tile, tm)
+                        vals, meta[b, h, -m - 1] = pack_v_tile(tile, tm)
+                        nnz[b, h, -m - 1], flag = _v_tile_store(vals, v_f16)
+                        mp[b, h, t] = -(-m | flag)
     return PackedKV(kind, Bt, D, mp, dense, nnz, meta)
 
 
@@ -320,20 +370,22 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
         assert (p.map[:, :, tile] == 0).all()
         for b in range(B):
             for h in range(H):
+                v_f16 = p.kind == "v" and p.dtype == "bf16"
                 if state == DENSE:
                     slot = int((p.map[b, h] > 0).sum())
                     if slot >= p.dense.shape[2]:
                         p.dense = np.concatenate([p.dense, np.zeros_like(p.dense[:, :, :1])], axis=2)
-                    p.dense[b, h, slot] = X[b, h]
-                    p.map[b, h, tile] = slot + 1
+                    p.dense[b, h, slot], flag = _v_tile_store(X[b, h], v_f16)
+                    p.map[b, h, tile] = (slot + 1) | flag
                 else:
                     slot = int((p.map[b, h] < 0).sum())
                     if slot >= p.nnz.shape[2]:
                         p.nnz = np.concatenate([p.nnz, np.zeros_like(p.nnz[:, :, :1])], axis=2)
                         p.meta = np.concatenate([p.meta, np.zeros_like(p.meta[:, :, :1])], axis=2)
                     pack = pack_k_tile if p.kind == "k" else pack_v_tile
-                    p.nnz[b, h, slot], p.meta[b, h, slot] = pack(X[b, h], mask[b, h])
-                    p.map[b, h, tile] = -(slot + 1)
+                    vals, p.meta[b, h, slot] = pack(X[b, h], mask[b, h])
+                    p.nnz[b, h, slot], flag = _v_tile_store(vals, v_f16)
+                    p.map[b, h, tile] = -((slot + 1) | flag)
 
 
 def unpack_tensor(p):
@@ -345,13 +397,16 @@ def unpack_tensor(p):
         for h in range(H):
             for t in range(T):
                 m = p.map[b, h, t]
+                if m == 0:
+                    continue
+                slot = map_slot(m)
+                back = f16_bits_to_bf16_bits if map_is_f16(m) else (lambda x: x)
                 if m > 0:
-                    out[b, h, t * p.Bt:(t + 1) * p.Bt] = p.dense[b, h, m - 1]
-                elif m < 0:
-                    if p.kind == "k":
-                        out[b, h, t * p.Bt:(t + 1) * p.Bt] = unpack_k_tile(p.nnz[b, h, -m - 1], p.meta[b, h, -m - 1])
-                    else:
-                        out[b, h, t * p.Bt:(t + 1) * p.Bt] = unpack_v_tile(p.nnz[b, h, -m - 1], p.meta[b, h, -m - 1])
+                    out[b, h, t * p.Bt:(t + 1) * p.Bt] = back(p.dense[b, h, slot])
+                elif p.kind == "k":
+                    out[b, h, t * p.Bt:(t + 1) * p.Bt] = unpack_k_tile(p.nnz[b, h, slot], p.meta[b, h, slot])
+                else:
+                    out[b, h, t * p.Bt:(t + 1) * p.Bt] = unpack_v_tile(back(p.nnz[b, h, slot]), p.meta[b, h, slot])
     return out
 
 
@@ -380,7 +435,7 @@ def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_
     assert ((state_k == SKIP) == (state_v == SKIP)).all(), "a skipped tile removes its tokens from K and V alike"
     info.update(state_k=state_k, state_v=state_v)
     pk = pack_tensor("k", K_bits, mk, state_k, Bt)
-    pv = pack_tensor("v", V_bits, mv, state_v, Bt)
+    pv = pack_tensor("v", V_bits, mv, state_v, Bt, v_f16=(dtype == "bf16"))
     pk.dtype = pv.dtype = dtype
     return pk, pv, info
 

@@ -100,6 +100,7 @@ def _stream():
 
 
 BF16, FP16 = 0, 1
+MAP_F16 = 1 << 30   # in |v_map entry| of a bf16 cache: the tile's stored values are in fp16 encoding
 
 
 def make_shape(B, Hq, Hkv, L, D=HEAD_DIM, tile=TILE, dtype=BF16):

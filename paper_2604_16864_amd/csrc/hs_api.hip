@@ -286,7 +286,7 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
     }
   }
   e = hs_launch_pack((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
-                     hs_make_kv_dev(out), uni_k, uni_v, policy->element_rule, s);
+                     hs_make_kv_dev(out), uni_k, uni_v, policy->element_rule, shape->dtype == HS_BF16, s);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }
@@ -313,7 +313,7 @@ int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, int32_t
   }
   const hipError_t e = hs_launch_append((const uint16_t*)K_tile, (const uint16_t*)V_tile, sb, sh, st, shape->B,
                                         shape->Hkv, T, tile, state_k, state_v, hs_make_kv_dev(kv), element_rule,
-                                        overflow, (hipStream_t)stream);
+                                        shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

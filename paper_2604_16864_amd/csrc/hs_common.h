@@ -119,6 +119,11 @@ static inline hs_kv_dev hs_make_kv_dev(const hs_kv* kv) {
   return d;
 }
 
+// v_map entries: sign = pool (dense > 0, 2:4 < 0), magnitude = slot + 1, plus HS_MAP_F16 when the tile
+// is stored in fp16 encoding
+__host__ __device__ static inline bool hs_map_f16(int m) { return ((m < 0 ? -m : m) & HS_MAP_F16) != 0; }
+__host__ __device__ static inline int hs_map_plain(int m) { return m < 0 ? -(-m & ~HS_MAP_F16) : (m & ~HS_MAP_F16); }
+
 // token group of V held at pair q of lane group a (see layout note above)
 __host__ __device__ static inline int hs_v_group(int a, int q) {
   return 4 * (2 * (a >> 1) + (q & 1)) + 2 * (a & 1) + (q >> 1);
@@ -130,11 +135,11 @@ hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
                             int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st);
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                          int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st);
+                          int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, int v_f16, hipStream_t st);
 // one tile [B, Hkv, 64, D] into tile index `tile` of a cache of T tiles per row
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
                             int B, int Hkv, int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule,
-                            int32_t* overflow, hipStream_t st);
+                            int v_f16, int32_t* overflow, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 // tail_len < 0: no tail slot; tail_len >= 0: one extra partial per query head, computed from the
 // dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D])

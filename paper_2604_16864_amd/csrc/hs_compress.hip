@@ -248,6 +248,18 @@ __global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int 
   }
 }
 
+// V tiles of a bf16 cache in fp16 encoding.  A bf16 pair is converted (round to nearest) and read
+// back: equal values mean the pair survives the round trip (NaN never does, infinities do).
+__device__ __forceinline__ bool pair_to_f16(uint32_t bf_pair, uint32_t& f16_pair) {
+  const float f0 = hs_elem<false>::lo_f32(bf_pair), f1 = hs_elem<false>::hi_f32(bf_pair);
+  f16_pair = hs_elem<true>::pack2(f0, f1);
+  return hs_elem<true>::lo_f32(f16_pair) == f0 && hs_elem<true>::hi_f32(f16_pair) == f1;
+}
+__device__ __forceinline__ uint32_t pair_to_bf16(uint32_t f16_pair) {  // exact for what pair_to_f16 accepted
+  const uint32_t lo = __float_as_uint(hs_elem<true>::lo_f32(f16_pair)), hi = __float_as_uint(hs_elem<true>::hi_f32(f16_pair));
+  return (lo >> 16) | (hi & 0xffff0000u);
+}
+
 // ----------------------------------------------------------------------------------
 // Fused prune + pack (Sec. IV-B): one workgroup per tile, K then V.
 // ----------------------------------------------------------------------------------
@@ -256,7 +268,7 @@ __global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int 
 // kernel writes it (saves the separate map-fill launch of the unranked policies).
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv,
-                                                   int uni_k, int uni_v, int rule, int t0) {
+                                                   int uni_k, int uni_v, int rule, int t0, int v_f16) {
   __shared__ uint16_t vl[HS_BT * kVStride];
   // source tile blockIdx.x of K, V goes to tile t of the cache (t0 = 0 except when appending)
   const int ts = blockIdx.x, t = ts + t0, h = blockIdx.y, b = blockIdx.z;
@@ -312,44 +324,73 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
   }
 
   // ---- V ----
+  // The words to store are built first.  v_f16 (bf16 cache): if every value the tile stores is
+  // exact in fp16 (workgroup vote), the tile is written in fp16 encoding and its map entry gets
+  // HS_MAP_F16, so that the attention kernels can feed the softmax numerators as one fp16 term.
   if (mv == 0) return;
   __syncthreads();
+  uint32_t words[4][4];
+  const int n_chunks = mv > 0 ? 4 : 2;  // 16-byte chunks this lane stores
+  uint32_t idx = 0;
   if (mv > 0) {
-    uint8_t* dst = const_cast<uint8_t*>(kv.v_dense) + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1;
       const int c = 16 * mb + r;
-      uint32_t o[4];
 #pragma unroll
       for (int p = 0; p < 4; p++) {
         const int e0 = 2 * p, e1 = 2 * p + 1;
         const int tok0 = 16 * (2 * hh + (e0 >> 2)) + 4 * a + (e0 & 3);
         const int tok1 = 16 * (2 * hh + (e1 >> 2)) + 4 * a + (e1 & 3);
-        o[p] = (uint32_t)vl[tok0 * kVStride + c] | ((uint32_t)vl[tok1 * kVStride + c] << 16);
+        words[j][p] = (uint32_t)vl[tok0 * kVStride + c] | ((uint32_t)vl[tok1 * kVStride + c] << 16);
       }
-      *reinterpret_cast<uint4*>(dst + (ch * 64 + l) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
     }
   } else {
-    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
-    uint8_t* nnz = const_cast<uint8_t*>(kv.v_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
-    uint8_t* meta = const_cast<uint8_t*>(kv.v_meta) + slot * (int64_t)HS_TILE_META_BYTES;
-    uint32_t idx = 0;
 #pragma unroll
     for (int j = 0; j < 2; j++) {
       const int mb = 2 * w + j, c = 16 * mb + r;
-      uint32_t out[4];
 #pragma unroll
       for (int q = 0; q < 4; q++) {
         const int g = hs_v_group(a, q);
         const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
         const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
         uint32_t nib;
-        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, out[q], nib);
+        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, words[j][q], nib);
         idx |= nib << (16 * j + 4 * q);
       }
-      *reinterpret_cast<uint4*>(nnz + (mb * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
     }
+  }
+  int as_f16 = 0;
+  if (v_f16) {  // workgroup-uniform
+    uint32_t conv[4][4];
+    int bad = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int p = 0; p < 4; p++)
+        if (j < n_chunks) bad |= !pair_to_f16(words[j][p], conv[j][p]);
+    as_f16 = !__syncthreads_or(bad);
+    if (as_f16) {
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int p = 0; p < 4; p++)
+          if (j < n_chunks) words[j][p] = conv[j][p];
+      if (tid == 0) const_cast<int32_t*>(kv.v_map)[row * T + t] = mv > 0 ? (mv | HS_MAP_F16) : -(-mv | HS_MAP_F16);
+    }
+  }
+  if (mv > 0) {
+    uint8_t* dst = const_cast<uint8_t*>(kv.v_dense) + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+      *reinterpret_cast<uint4*>(dst + ((4 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+  } else {
+    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+    uint8_t* nnz = const_cast<uint8_t*>(kv.v_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    uint8_t* meta = const_cast<uint8_t*>(kv.v_meta) + slot * (int64_t)HS_TILE_META_BYTES;
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+      *reinterpret_cast<uint4*>(nnz + ((2 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
     *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
   }
 }
@@ -364,7 +405,9 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
   const int64_t row = (int64_t)b * Hkv + h;
-  const int mk = kv.k_map[row * T + t], mv = kv.v_map[row * T + t];
+  const int mk = kv.k_map[row * T + t], mv_raw = kv.v_map[row * T + t];
+  const bool v_is_f16 = hs_map_f16(mv_raw);
+  const int mv = hs_map_plain(mv_raw);  // +-(slot + 1)
   uint16_t* ko = K_out + (row * T + t) * (int64_t)(HS_BT * HS_D);
   uint16_t* vo = V_out + (row * T + t) * (int64_t)(HS_BT * HS_D);
   {  // K: token 16w+r
@@ -414,7 +457,11 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
     for (int j = 0; j < 4; j++) {
       const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1, c = 16 * mb + r;
       const uint4 d = *reinterpret_cast<const uint4*>(src + (ch * 64 + l) * 16);
-      const uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+      uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+      if (v_is_f16) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) vals[i] = pair_to_bf16(vals[i]);
+      }
 #pragma unroll
       for (int e = 0; e < 8; e++) {
         const int tok = 16 * (2 * hh + (e >> 2)) + 4 * a + (e & 3);
@@ -429,7 +476,11 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
     for (int j = 0; j < 2; j++) {
       const int mb = 2 * w + j, c = 16 * mb + r;
       const uint4 d = *reinterpret_cast<const uint4*>(nnz + (mb * 64 + l) * 16);
-      const uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+      uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+      if (v_is_f16) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) vals[i] = pair_to_bf16(vals[i]);
+      }
 #pragma unroll
       for (int q = 0; q < 4; q++) {
         const int g = hs_v_group(a, q);
@@ -480,18 +531,18 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
 }
 
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                          int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, hipStream_t st) {
-  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0);
+                          int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, int v_f16, hipStream_t st) {
+  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0, v_f16);
   return hipGetLastError();
 }
 
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                            int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule, int32_t* overflow,
-                            hipStream_t st) {
+                            int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule, int v_f16,
+                            int32_t* overflow, hipStream_t st) {
   hipLaunchKernelGGL(append_slots_kernel, dim3(B * Hkv), dim3(256), 0, st, T, tile, state_k, state_v, kv, overflow);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(pack_kernel, dim3(1, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile);
+  hipLaunchKernelGGL(pack_kernel, dim3(1, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16);
   return hipGetLastError();
 }
 

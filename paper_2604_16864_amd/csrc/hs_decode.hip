@@ -8,6 +8,8 @@
 // order), so there is no LDS staging and no cross-lane shuffle in the main loop.  The
 // sparse matrix instruction is used as the decompressor: it consumes the 2-bit metadata
 // natively, so no vector-ALU work is spent on selecting operands.
+#include <type_traits>
+
 #include "hs_common.h"
 
 #ifndef HS_DEC_DEPTH
@@ -44,9 +46,10 @@ struct TileRegs {
 };
 
 template <int KM, int VM>
-__device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {
+__device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {  // mk, mv: wave-uniform
   r.mk = mk;
-  r.mv = mv;
+  r.mv = mv;  // with the encoding bit, for tile_compute
+  mv = hs_map_plain(mv);
   r.km = make_uint4(0, 0, 0, 0);  // only 2:4 tiles carry index words
   r.vm = make_uint4(0, 0, 0, 0);
   const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
@@ -78,17 +81,22 @@ __device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& 
 }
 
 // One tile: GEMM1 (S^T = K Q^T), online softmax, GEMM2 (O^T += V^T P^T).
-// F16: element type (hs_elem).  With fp16 the running reference sits kShift = 8 binades under the
-// running maximum, so that numerators reach 2^8 and what fp16 flushes to zero is below 2^-32 of
-// the largest one (a context of 2^17 tokens then loses < 2^-15 of the sum); bf16 has the range.
-template <int KM, int VM, bool F16>
+// F16: element type of the cache (hs_elem).  A V tile of a bf16 cache may be stored in fp16
+// encoding (HS_MAP_F16 in its map entry); the numerators then go into GEMM2 as fp16 too.  The
+// running reference sits kShift = 8 binades under the running maximum, so that numerators reach
+// 2^8 and what fp16 flushes to zero is below 2^-32 of the largest one (a context of 2^17 tokens
+// then loses < 2^-15 of the sum).
+// ENC: 0 = V tile in bf16, 1 = in fp16 (encoding bit, or an fp16 cache).
+template <int KM, int VM, bool F16, int ENC>
 __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const uint4 (&qb)[4], float scale_log2, int c,
                                              f32x4_t (&o)[8], float& m_run, float& l_run) {
   const bool k_sparse = KM == 0 || (KM == 2 && r.mk < 0);
   const bool v_sparse = VM == 0 || (VM == 2 && r.mv < 0);
   constexpr int kNK = TileRegs<KM, VM>::kNK, kNV = TileRegs<KM, VM>::kNV;
   typedef hs_elem<F16> E;
-  constexpr float kShift = F16 ? 8.f : 0.f;
+  typedef hs_elem<true> E16;
+  constexpr float kShift = 8.f;
+  constexpr bool v_f16 = ENC == 1;
   f32x4_t s[4];
   const int kidx[4] = {(int)r.km.x, (int)r.km.y, (int)r.km.z, (int)r.km.w};
   const int vidx[4] = {(int)r.vm.x, (int)r.vm.y, (int)r.vm.z, (int)r.vm.w};
@@ -125,41 +133,54 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
   // P^T as the B operand: element 8h+4u+i of lane group a <- token 16(2h+u)+4a+i.
   // Columns < 8 carry bf16(p), columns >= 8 carry bf16(p - bf16(p)), so that the sum of
   // the two accumulator columns sees p to ~16 bits although the operand type is bf16.
-  uint32_t pb[8];
+  float p[4][4];
 #pragma unroll
-  for (int m = 0; m < 4; m++) {
-    float p[4], rsd[4];
-    uint32_t hi[2];
+  for (int m = 0; m < 4; m++)
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][i], scale_log2, -m_new));
-      psum += p[i];
+      p[m][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][i], scale_log2, -m_new));
+      psum += p[m][i];
     }
-    hi[0] = E::pack2(p[0], p[1]);
-    hi[1] = E::pack2(p[2], p[3]);
-    rsd[0] = p[0] - E::lo_f32(hi[0]);
-    rsd[1] = p[1] - E::hi_f32(hi[0]);
-    rsd[2] = p[2] - E::lo_f32(hi[1]);
-    rsd[3] = p[3] - E::hi_f32(hi[1]);
-    const uint32_t lo0 = E::pack2(rsd[0], rsd[1]), lo1 = E::pack2(rsd[2], rsd[3]);
-    pb[2 * m] = c < 8 ? hi[0] : lo0;
-    pb[2 * m + 1] = c < 8 ? hi[1] : lo1;
-  }
+  uint32_t pb[8];
+  auto pack_as = [&](auto enc) {
+    typedef hs_elem<decltype(enc)::value> EP;
+#pragma unroll
+    for (int m = 0; m < 4; m++) {
+      const uint32_t hi0 = EP::pack2(p[m][0], p[m][1]), hi1 = EP::pack2(p[m][2], p[m][3]);
+      const uint32_t lo0 = EP::pack2(p[m][0] - EP::lo_f32(hi0), p[m][1] - EP::hi_f32(hi0));
+      const uint32_t lo1 = EP::pack2(p[m][2] - EP::lo_f32(hi1), p[m][3] - EP::hi_f32(hi1));
+      pb[2 * m] = c < 8 ? hi0 : lo0;
+      pb[2 * m + 1] = c < 8 ? hi1 : lo1;
+    }
+  };
+  if (v_f16) pack_as(std::true_type{});
+  else pack_as(std::false_type{});
   l_run = l_run * alpha + psum;
 #pragma unroll
   for (int i = 0; i < 8; i++) o[i] *= alpha;
   const uint4 pb_lo = make_uint4(pb[0], pb[1], pb[2], pb[3]);  // dense step h = 0
   const uint4 pb_hi = make_uint4(pb[4], pb[5], pb[6], pb[7]);  // dense step h = 1
+  if (v_f16) {
 #pragma unroll
-  for (int mb = 0; mb < 8; mb++) {
-    if (v_sparse) {
-      if (mb & 1)
-        o[mb] = E::template smma<1>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
-      else
-        o[mb] = E::template smma<0>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
-    } else {
-      o[mb] = E::mma(r.v[(2 * mb) % kNV], pb_lo, o[mb]);
-      o[mb] = E::mma(r.v[(2 * mb + 1) % kNV], pb_hi, o[mb]);
+    for (int mb = 0; mb < 8; mb++) {
+      if (v_sparse) {
+        if (mb & 1) o[mb] = E16::template smma<1>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
+        else o[mb] = E16::template smma<0>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
+      } else {
+        o[mb] = E16::mma(r.v[(2 * mb) % kNV], pb_lo, o[mb]);
+        o[mb] = E16::mma(r.v[(2 * mb + 1) % kNV], pb_hi, o[mb]);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int mb = 0; mb < 8; mb++) {
+      if (v_sparse) {
+        if (mb & 1) o[mb] = E::template smma<1>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
+        else o[mb] = E::template smma<0>(r.v[mb], pb_lo, pb_hi, o[mb], vidx[mb >> 1]);
+      } else {
+        o[mb] = E::mma(r.v[(2 * mb) % kNV], pb_lo, o[mb]);
+        o[mb] = E::mma(r.v[(2 * mb + 1) % kNV], pb_hi, o[mb]);
+      }
     }
   }
 }
@@ -204,51 +225,64 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
   // the arithmetic removed is only ~10 % faster: the kernel is bound by the load stream.
   constexpr int DEPTH = (KM == 2 || VM == 2) ? 1 : HS_DEC_DEPTH;  // a mixed tensor carries both code paths: keep it small
   TileRegs<KM, VM> ring[DEPTH];
-  for (int base = t_begin + w; base < t_end; base += 256) {  // up to 64 tiles of this wave per round
-    const int t_mine = base + 4 * l;
-    int mk_v = 0, mv_v = 0;
-    if (t_mine < t_end) {
-      if (UNIFORM) {  // promised by the caller: no tile skipped, one kind per tensor, slot == tile
-        mk_v = KM == 0 ? -(t_mine + 1) : t_mine + 1;
-        mv_v = VM == 0 ? -(t_mine + 1) : t_mine + 1;
-      } else {
-        mk_v = kv.k_map[row * T + t_mine];
-        mv_v = kv.v_map[row * T + t_mine];
+  // One sweep over this wave's tiles for one V encoding (enc: 1 = fp16, 0 = bf16): a tile of
+  // the other encoding is left out and reported, so that the matrix instructions of a sweep are
+  // of one type and no branch sits between them.  The softmax recurrence does not care in which
+  // order tiles arrive.
+  auto sweep = [&](auto enc) -> bool {
+    constexpr int kEnc = decltype(enc)::value;
+    bool others = false;
+    for (int base = t_begin + w; base < t_end; base += 256) {  // up to 64 tiles of this wave per round
+      const int t_mine = base + 4 * l;
+      int mk_v = 0, mv_v = 0;
+      if (t_mine < t_end) {
+        if (UNIFORM) {  // promised by the caller: no tile skipped, one kind per tensor, slot == tile
+          mk_v = KM == 0 ? -(t_mine + 1) : t_mine + 1;
+          mv_v = F16 ? (VM == 0 ? -(t_mine + 1) : t_mine + 1) : kv.v_map[row * T + t_mine];  // bf16: encoding bit
+        } else {
+          mk_v = kv.k_map[row * T + t_mine];
+          mv_v = kv.v_map[row * T + t_mine];
+        }
       }
-    }
-    // Tile kinds must reach the branches below as scalar (wave-uniform) values: matrix
-    // instructions ignore the EXEC mask, so a branch the compiler treats as divergent would run
-    // both the dense and the 2:4 instruction on every tile.  Lane values are therefore read
-    // with v_readlane, never with a lane shuffle.
-    unsigned long long act = __ballot(mk_v != 0);
-    bool have[DEPTH];
-#pragma unroll
-    for (int d = 0; d < DEPTH; d++) {
-      have[d] = act != 0ull;
-      if (have[d]) {
-        const int i = __builtin_ctzll(act);
-        act &= act - 1;
-        tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
-      }
-    }
-    bool go = have[0];
-    while (go) {
+      // Tile kinds must reach the branches below as scalar (wave-uniform) values: matrix
+      // instructions ignore the EXEC mask, so a branch the compiler treats as divergent would run
+      // both the dense and the 2:4 instruction on every tile.  Lane values are therefore read
+      // with v_readlane, never with a lane shuffle.
+      const bool mine = F16 || hs_map_f16(mv_v) == (kEnc == 1);
+      unsigned long long act = __ballot(mk_v != 0 && mine);
+      if (!F16) others = others || __ballot(mk_v != 0 && !mine) != 0ull;
+      bool have[DEPTH];
 #pragma unroll
       for (int d = 0; d < DEPTH; d++) {
-        if (go && have[d]) {  // tiles are consumed in issue order: the first empty slot ends the round
-          tile_compute<KM, VM, F16>(ring[d], qb, scale_log2, c, o, m_run, l_run);
-          have[d] = act != 0ull;
-          if (have[d]) {
-            const int i = __builtin_ctzll(act);
-            act &= act - 1;
-            tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
+        have[d] = act != 0ull;
+        if (have[d]) {
+          const int i = __builtin_ctzll(act);
+          act &= act - 1;
+          tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
+        }
+      }
+      bool go = have[0];
+      while (go) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; d++) {
+          if (go && have[d]) {  // tiles are consumed in issue order: the first empty slot ends the round
+            tile_compute<KM, VM, F16, kEnc>(ring[d], qb, scale_log2, c, o, m_run, l_run);
+            have[d] = act != 0ull;
+            if (have[d]) {
+              const int i = __builtin_ctzll(act);
+              act &= act - 1;
+              tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
+            }
+          } else {
+            go = false;
           }
-        } else {
-          go = false;
         }
       }
     }
-  }
+    return others;
+  };
+  const bool bf16_tiles_left = sweep(std::integral_constant<int, 1>{});
+  if (!F16 && bf16_tiles_left) sweep(std::integral_constant<int, 0>{});
 
   // ---------------- combine: lane groups, hi/lo columns, then the 4 waves ----------------
   l_run += __shfl_xor(l_run, 16);

@@ -10,6 +10,8 @@
 // copied once per workgroup into an LDS ring by direct global->LDS loads issued up to 3 tiles
 // ahead.  Pools are stored in operand order, so LDS reads are conflict-free 16-byte-per-lane
 // reads and GEMM1's accumulators become GEMM2's B operand in place (no re-layout step).
+#include <type_traits>
+
 #include "hs_common.h"
 
 // Wave priority per phase.  Two waves share a SIMD; letting the one that is in its vector-ALU
@@ -18,6 +20,7 @@
 #define HS_PRIO_MFMA 0
 #define HS_PRIO_VALU 1
 #endif
+
 
 namespace {
 
@@ -99,6 +102,7 @@ __device__ __forceinline__ void stage_issue(uint32_t stage, const hs_kv_dev& kv,
                                             uint32_t lane_off) {
   const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
   const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
+  mv = hs_map_plain(mv);  // without the encoding bit
   constexpr uint32_t voff = region_bytes<KM>();
   if (k_sparse) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
@@ -148,9 +152,11 @@ union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the de
 // keys-dense / values-2:4 setting of Sec. V-A carries no dynamic dispatch).
 // NB: column blocks (of 16 queries) per wave: a wave owns a slab of 16*NB query positions of one
 // head.  NB = 2 fits 2 waves per SIMD (NB = 4, 1 wave per SIMD, measured 1.3-1.4x slower).
-// F16: element type (hs_elem).  fp16 numerators have 11 significant bits, so P enters GEMM2 as one
-// term; their reference is kept kShift = 8 binades under the running maximum (range, see decode)
-// and renewed before a numerator can reach the fp16 maximum.
+// F16: element type of the cache (hs_elem).  A V tile of a bf16 cache may be stored in fp16 encoding
+// (HS_MAP_F16 in its map entry).  Against fp16 V the numerators have 11 significant bits and enter
+// GEMM2 as one fp16 term; against bf16 V they enter as two bf16 terms.  The reference is kept
+// kShift = 8 binades under the running maximum (range, see decode) and renewed before a
+// numerator can reach the fp16 maximum.
 template <int KM, int VM, int NB, bool F16>
 __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, int Hkv, int T, int Lq, int off,
                                                                       float scale_log2, int causal,
@@ -158,19 +164,19 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
                                                                       uint16_t* __restrict__ O,
                                                                       float* __restrict__ LSE) {
   typedef hs_elem<F16> E;
-  constexpr float kShift = F16 ? 8.f : 0.f;
-  constexpr float kRedo = F16 ? 0x1p14f : 0x1p40f;  // partial row sum above which the reference is renewed
-  constexpr int NT = F16 ? 1 : 2;                   // terms of P
+  typedef hs_elem<true> E16;
+  constexpr float kShift = 8.f;
+  constexpr float kRedo = 0x1p14f;  // partial row sum above which the reference is renewed
   constexpr int QS = 16 * NB;  // query positions per slab
   constexpr int NS = n_stages<KM, VM>(), D = NS - 1;  // ring size, prefetch distance in tiles
   // MID: the per-tile barrier sits between softmax and GEMM2 instead of at the end of the
   // iteration, so that the next tile's K operands can be fetched from LDS while GEMM2 runs.  Needs
   // the next tile requested at least two iterations ahead (NS >= 3), which all-2:4 keys give.
-  constexpr bool MID = KM == 0 && VM != 2;  // (mixed V on top of the K prefetch runs out of registers)
+  constexpr bool MID = F16 && KM == 0 && VM != 2;  // (fp16 caches only: the two V encodings of a bf16 cache, or mixed V, leave no registers for the K prefetch)
   static_assert(!MID || NS >= 3, "mid-iteration barrier needs a ring of 3");
   // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
   // already holds the registers (both together spill; measured no gain there)
-  constexpr bool V_EARLY = VM == 0 && !MID;
+  constexpr bool V_EARLY = F16 && VM == 0 && !MID;
   constexpr int kStage = stage_bytes<KM, VM>();
   __shared__ __attribute__((aligned(16))) uint8_t lds[NS * kStage];
   const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
@@ -282,7 +288,13 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     }
   };
   if (MID && valid && tj[0] >= 0) k_fetch(0);
-  while (tj[0] >= 0) {
+  // One iteration = one tile.  The loop exists twice, for runs of V tiles in fp16 encoding (one fp16
+  // term of P) and in bf16 (two terms), so that each copy is straight-line code around its matrix
+  // instructions and keeps the accumulators where they are (a per-tile branch around GEMM2 made
+  // the compiler move all 64 accumulator registers in and out of the branch).  The encoding is
+  // scalar: map entries come through v_readlane.
+  auto iteration = [&](auto enc) {  // enc: 0 = bf16 V tile, 1 = fp16-encoded, 2 = look at the tile (mixed dense / 2:4 V)
+    constexpr int kEnc = decltype(enc)::value;
     const int j = tj[0], mk = tk[0], mv = tv[0];
     // END mode: request the tile D ahead now; its stage held the tile of the previous iteration,
     // which every wave has left behind (barrier at the end of that iteration)
@@ -290,6 +302,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     const bool ok = valid && j <= jmax_w;
     const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
     const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
+    const bool v_f16 = kEnc == 2 ? (F16 || hs_map_f16(mv)) : kEnc == 1;
     const uint4* kl = reinterpret_cast<const uint4*>(lds + st * kStage);
     const uint4* vl = reinterpret_cast<const uint4*>(lds + st * kStage + region_bytes<KM>());
     B16 ph[NB], pl[NB];
@@ -355,7 +368,8 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       // P goes through the matrix unit as two bf16 terms (hi + remainder): a single bf16 P alone
       // costs ~1.3e-3 mean relative error on the output, on top of the bf16 rounding of O itself.
       float psum[NB];
-      auto softmax_tile = [&]() {
+      auto softmax_as = [&](auto enc) {  // enc: std::true_type = fp16 numerators, one term
+        constexpr bool kF16 = decltype(enc)::value;
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
           float acc = 0.f;
@@ -368,9 +382,9 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
               p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
               acc += p[i];
             }
-            if (F16) {
-              ph[nb].u[2 * m] = E::pack2(p[0], p[1]);
-              ph[nb].u[2 * m + 1] = E::pack2(p[2], p[3]);
+            if (kF16) {
+              ph[nb].u[2 * m] = E16::pack2(p[0], p[1]);
+              ph[nb].u[2 * m + 1] = E16::pack2(p[2], p[3]);
             } else {
               split_hi_lo(p[0], p[1], sc, ph[nb].u[2 * m], pl[nb].u[2 * m]);
               split_hi_lo(p[2], p[3], sc, ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
@@ -378,6 +392,10 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
           }
           psum[nb] = acc;
         }
+      };
+      auto softmax_tile = [&]() {
+        if (kEnc == 2 ? v_f16 : kEnc == 1) softmax_as(std::true_type{});
+        else softmax_as(std::false_type{});
       };
       softmax_tile();
       bool redo = false;
@@ -431,29 +449,48 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
           vix = vl[512 + l];
         }
         const int vidx[4] = {(int)vix.x, (int)vix.y, (int)vix.z, (int)vix.w};
-#pragma unroll
-        for (int t2 = 0; t2 < NT; t2++)  // first the upper-half term of every block, then the remainder
+        if (v_f16) {  // one fp16 term
 #pragma unroll
           for (int nb = 0; nb < NB; nb++)
 #pragma unroll
             for (int mb = 0; mb < 8; mb++) {
-              const B16& bp = t2 == 0 ? ph[nb] : pl[nb];
               if (mb & 1)
-                o[mb][nb] = E::template smma<1>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                o[mb][nb] = E16::template smma<1>(av[mb], ph[nb].q[0], ph[nb].q[1], o[mb][nb], vidx[mb >> 1]);
               else
-                o[mb][nb] = E::template smma<0>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                o[mb][nb] = E16::template smma<0>(av[mb], ph[nb].q[0], ph[nb].q[1], o[mb][nb], vidx[mb >> 1]);
             }
+        } else {
+#pragma unroll
+          for (int t2 = 0; t2 < 2; t2++)  // first the upper-half term of every block, then the remainder
+#pragma unroll
+            for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+              for (int mb = 0; mb < 8; mb++) {
+                const B16& bp = t2 == 0 ? ph[nb] : pl[nb];
+                if (mb & 1)
+                  o[mb][nb] = E::template smma<1>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                else
+                  o[mb][nb] = E::template smma<0>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+              }
+        }
       } else {
 #pragma unroll
         for (int mb = 0; mb < 8; mb++) {
           const uint4 a0 = vl[(2 * mb) * 64 + l], a1 = vl[(2 * mb + 1) * 64 + l];
-#pragma unroll
-          for (int t2 = 0; t2 < NT; t2++)
+          if (v_f16) {
 #pragma unroll
             for (int h = 0; h < 2; h++)
 #pragma unroll
-              for (int nb = 0; nb < NB; nb++)
-                o[mb][nb] = E::mma(h == 0 ? a0 : a1, t2 == 0 ? ph[nb].q[h] : pl[nb].q[h], o[mb][nb]);
+              for (int nb = 0; nb < NB; nb++) o[mb][nb] = E16::mma(h == 0 ? a0 : a1, ph[nb].q[h], o[mb][nb]);
+          } else {
+#pragma unroll
+            for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+              for (int h = 0; h < 2; h++)
+#pragma unroll
+                for (int nb = 0; nb < NB; nb++)
+                  o[mb][nb] = E::mma(h == 0 ? a0 : a1, t2 == 0 ? ph[nb].q[h] : pl[nb].q[h], o[mb][nb]);
+          }
         }
       }
     }
@@ -469,6 +506,17 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 #pragma unroll
     for (int i = 0; i < D; i++) { tj[i] = tj[i + 1]; tk[i] = tk[i + 1]; tv[i] = tv[i + 1]; }
     st = st + 1 == NS ? 0 : st + 1;
+      };
+  while (tj[0] >= 0) {
+    if (VM == 2 && !F16) {  // four GEMM2 forms in one kernel: no second copy of the loop
+      iteration(std::integral_constant<int, 2>{});
+    } else if (F16 || hs_map_f16(tv[0])) {
+      do iteration(std::integral_constant<int, 1>{});
+      while (tj[0] >= 0 && (F16 || hs_map_f16(tv[0])));
+    } else {
+      do iteration(std::integral_constant<int, 0>{});
+      while (tj[0] >= 0 && !hs_map_f16(tv[0]));
+    }
   }
 
   // ---------------- epilogue: O = O^T / l, LSE ----------------

@@ -599,6 +599,61 @@ def test_fp16_large_logits_and_long_flat_rows():
 
 
 # ------------------------------------------------------------------ edges and errors
+@pytest.mark.parametrize("planted", ["tiny", "huge", "both"])
+@pytest.mark.parametrize("pol", [dict(), dict(sparse_frac_k=0.0, sparse_frac_v=0.0), dict(sparse_frac_v=0.5),
+                                 dict(skip_frac=0.25, sparse_frac_k=0.5, sparse_frac_v=0.7)])
+def test_bf16_cache_with_both_v_tile_encodings(pol, planted):
+    """V tiles of a bf16 cache whose stored values fp16 holds exactly carry the encoding bit and go
+    through the fp16 matrix instructions; tiles with values under fp16's subnormal step or over its
+    largest number stay bf16.  Both kinds in one row, in every kernel specialisation."""
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 14
+    T = L // 64
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=190, k_outliers=True)
+    Vf = wl.bf16_bits_to_f32(V)
+    rng = np.random.default_rng(191)
+    kind = rng.integers(0, 3, size=(B, Hkv, T))          # 0: as drawn, 1: tiny, 2: huge
+    kind[0, 0, :] = 0                                       # one row with fp16 tiles only
+    kind[1, 1, :] = 1 if planted != "huge" else 2           # one row with bf16 tiles only
+    for b in range(B):
+        for h in range(Hkv):
+            for t in range(T):
+                if kind[b, h, t] == 1 and planted in ("tiny", "both"):
+                    Vf[b, h, 64 * t:64 * t + 64] *= 2.0 ** -20
+                if kind[b, h, t] == 2 and planted in ("huge", "both"):
+                    Vf[b, h, 64 * t:64 * t + 64] *= 2.0 ** 18
+    V = wl.f32_to_bf16_bits(Vf)                             # exact: powers of two
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, **pol)
+    flagged = (np.abs(pv.map.astype(np.int64)) & orc.MAP_F16) != 0
+    live = pv.map != 0
+    assert (flagged & live).any() and (~flagged & live).any()
+    check_packed_bit_exact(sh, kv, pk, pv)
+    O, LSE = hb.prefill_attn(sh, _dev(Q), kv)
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(B, Hq, L, 200, seed=192, extra=[(0, 0, 0), (B - 1, Hq - 1, L - 1)])
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    got = _f32(O)[idx]
+    if planted == "tiny":                                   # no huge tile hides the others' error
+        assert_close(got, Or, f"prefill v encodings {sorted(pol)}")
+    else:                                                   # per (b, h) row block: scales differ by 2^18
+        for b in range(B):
+            for h in range(Hq):
+                sel = (idx[0] == b) & (idx[1] == h)
+                if sel.any():
+                    assert_close(got[sel], Or[sel], f"prefill v encodings {planted} b{b} h{h}")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill v encodings lse")
+    q = Q[:, :, -1, :].copy()
+    Odr, Ldr = orc.attention_decode(q, pk, pv)
+    for ns in (0, 3):
+        Od, LSEd = hb.decode_attn(sh, _dev(q), kv, n_splits=ns)
+        torch.cuda.synchronize()
+        for b in range(B):
+            for hk in range(Hkv):
+                g = slice(hk * (Hq // Hkv), (hk + 1) * (Hq // Hkv))
+                assert_close(_f32(Od)[b, g], Odr[b, g], f"decode v encodings {planted} splits {ns} b{b} hkv{hk}")
+        assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode v encodings lse")
+
+
 def test_single_tile_and_odd_batch_shapes():
     """L = 64 (one tile, one split), B = 3, 3 KV heads: smallest grid dimensions on every kernel."""
     for (B, Hq, Hkv, L) in ((1, 1, 1, 64), (3, 6, 3, 64 * 3), (2, 16, 2, 64 * 2)):

@@ -73,6 +73,9 @@ def test_struct_layouts_match_the_header(tmp_path):
         for f in cls._fields_:
             src.append(f'  printf(" %zu", offsetof({cname}, {f[0]}));')
         src.append('  printf("\\n");')
+    consts = {"HS_BF16": hb.BF16, "HS_FP16": hb.FP16, "HS_RULE_MAGNITUDE": hb.RULE_MAGNITUDE,
+              "HS_RULE_NONZERO": hb.RULE_NONZERO, "HS_MAP_F16": hb.MAP_F16}
+    src.append('  printf("consts' + " %d" * len(consts) + '\\n", ' + ", ".join(consts) + ');')
     src += ['  return 0;', '}']
     c_file = tmp_path / "layout.c"
     c_file.write_text("\n".join(src))
@@ -85,6 +88,7 @@ def test_struct_layouts_match_the_header(tmp_path):
         assert tok[0] == cname
         assert int(tok[1]) == C.sizeof(cls), cname
         assert [int(x) for x in tok[2:]] == [getattr(cls, f[0]).offset for f in cls._fields_], cname
+    assert [int(x) for x in out[len(fields)].split()[1:]] == list(consts.values())
 
 
 def test_argument_errors(L):

@@ -103,8 +103,10 @@ def test_mixed_states_roundtrip_and_map():
         for h in range(2):
             mp = p.map[0, h]
             assert ((mp == 0) == (st[0, h] == S)).all()
-            assert (mp[st[0, h] == Dn] == np.arange(1, 1 + (st[0, h] == Dn).sum())).all()
-            assert (mp[st[0, h] == Sp] == -np.arange(1, 1 + (st[0, h] == Sp).sum())).all()
+            signed_slot = np.sign(mp) * (np.abs(mp) & ~orc.MAP_F16)        # V entries may carry the encoding bit
+            assert (signed_slot[st[0, h] == Dn] == np.arange(1, 1 + (st[0, h] == Dn).sum())).all()
+            assert (signed_slot[st[0, h] == Sp] == -np.arange(1, 1 + (st[0, h] == Sp).sum())).all()
+            assert p.kind == "v" or (signed_slot == mp).all()
         tile_state = np.repeat(st, 16, axis=-1)[..., None]
         want = np.where(tile_state == Dn, X, np.where(tile_state == Sp, np.where(m, X, 0), 0))
         assert (orc.unpack_tensor(p) == want).all()
@@ -441,6 +443,41 @@ def test_fp16_patterns_are_read_as_ieee_binary16():
         vis = np.repeat(pk.map[0, h // 2] != 0, 16)
         ref = _sdpa(f(q)[0, h][None, None, None, :], Ku[0, h // 2][vis][None, None], Vu[0, h // 2][vis][None, None])
         assert np.allclose(O[0, h], ref[0, 0, 0], rtol=1e-12, atol=1e-13)
+
+
+def test_v_tiles_in_fp16_encoding_hold_the_same_values():
+    """A V tile of a bf16 cache is kept in fp16 encoding exactly when every stored value survives the
+    round trip; the decision and the conversion are checked value by value with Python floats / struct."""
+    import struct
+    def bf(x):        # bf16 pattern of a float that bf16 holds exactly
+        return struct.unpack("<I", struct.pack("<f", x))[0] >> 16
+    def as_f16(bits):
+        return struct.unpack("<e", struct.pack("<H", int(bits)))[0]
+    def as_bf16(bits):
+        return struct.unpack("<f", struct.pack("<I", int(bits) << 16))[0]
+    ok = [1.0, -2.5, 0.0, -0.0, 65280.0, 2.0 ** -14, 2.0 ** -24, 3 * 2.0 ** -24, 255 * 2.0 ** -24, float("inf")]
+    bad = [65536.0, 1e30, 2.0 ** -25, 129 * 2.0 ** -25, -3 * 2.0 ** -26, float("nan")]
+    bits = np.array([bf(x) for x in ok + bad], dtype=np.uint16)
+    assert orc.bf16_bits_exact_in_f16(bits).tolist() == [True] * len(ok) + [False] * len(bad)
+    conv = orc.bf16_bits_to_f16_bits(bits[:len(ok)])
+    for b, c in zip(bits[:len(ok)], conv):
+        assert as_f16(c) == as_bf16(b) and (c >> 15) == (b >> 15)
+    assert (orc.f16_bits_to_bf16_bits(conv) == bits[:len(ok)]).all()
+    # tiles: 0 plain, 1 has one value fp16 cannot hold, 2 has such a value only where 2:4 pruning removes it
+    K, V = _rand_kv(14, B=1, H=1, L=16 * 3, D=16)
+    V[0, 0, 16 + 3, 5] = bf(1e30)
+    V[0, 0, 32:36, 7] = [bf(1.0), bf(-2.0), bf(2.0 ** -30), bf(0.5)]
+    pk, pv, info = orc.compress_kv(K, V, Bt=16)
+    assert [orc.map_is_f16(m) for m in pv.map[0, 0]] == [True, False, True]
+    assert not any(orc.map_is_f16(m) for m in pk.map[0, 0])
+    assert (orc.unpack_tensor(pv) == np.where(info["mask_v"], V, 0)).all()           # values unchanged either way
+    assert (pv.nnz[0, 0, 1] == orc.pack_v_tile(V[0, 0, 16:32], info["mask_v"][0, 0, 16:32])[0]).all()   # tile 1: bf16 bits
+    assert (pv.nnz[0, 0, 0] != orc.pack_v_tile(V[0, 0, :16], info["mask_v"][0, 0, :16])[0]).any()       # tile 0: other encoding
+    pkd, pvd, _ = orc.compress_kv(K, V, Bt=16, sparse_frac_k=0.0, sparse_frac_v=0.0)
+    assert [orc.map_is_f16(m) for m in pvd.map[0, 0]] == [True, False, False]        # dense: every value is stored
+    assert (orc.unpack_tensor(pvd) == V).all()
+    pkh, pvh, _ = orc.compress_kv(K, V, Bt=16, dtype="fp16")
+    assert not any(orc.map_is_f16(m) for m in pvh.map[0, 0])                         # fp16 caches need no flag
 
 
 def test_brute_force_python_floats_tiny():
