@@ -388,6 +388,69 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
                     p.map[b, h, tile] = -((slot + 1) | flag)
 
 
+def _sparser(cur, target):
+    """Tile state after further pruning: a tile only ever moves DENSE -> SPARSE24 -> SKIP."""
+    order = {DENSE: 0, SPARSE24: 1, SKIP: 2}
+    return cur if order[cur] >= order[target] else target
+
+
+def recompress(p, target_state, element_rule="magnitude"):
+    """Prune a packed tensor further (Sec. III, overview: after the prefill phase the dense pool
+    can be pruned and compressed again, so that decode runs at another sparsity than prefill).
+    target_state: [B, Hkv, T] of SKIP / DENSE / SPARSE24.  A tile ends in the sparser of its
+    current and its target state: a tile that keeps its kind keeps its stored bits (and its
+    encoding); a DENSE tile that becomes SPARSE24 is pruned from the values it stores; a tile that
+    becomes SKIP is dropped.  Pools are refilled in sequence order (Sec. III-B).  Returns a new
+    PackedKV; `p` is left as it is."""
+    B, H, T = p.map.shape
+    target_state = np.asarray(target_state)
+    assert target_state.shape == (B, H, T)
+    cur = np.where(p.map > 0, DENSE, np.where(p.map < 0, SPARSE24, SKIP)).astype(np.int8)
+    new = np.array([[[_sparser(int(cur[b, h, t]), int(target_state[b, h, t])) for t in range(T)]
+                     for h in range(H)] for b in range(B)], dtype=np.int8).reshape(B, H, T)
+    mp = build_map(new)
+    cap_d = max(1, int((new == DENSE).sum(axis=-1).max()))
+    cap_s = max(1, int((new == SPARSE24).sum(axis=-1).max()))
+    dense = np.zeros((B, H, cap_d) + p.dense.shape[3:], dtype=np.uint16)
+    nnz = np.zeros((B, H, cap_s) + p.nnz.shape[3:], dtype=np.uint16)
+    meta = np.zeros((B, H, cap_s) + p.meta.shape[3:], dtype=np.uint32)
+    v_f16 = p.kind == "v" and p.dtype == "bf16"
+    for b in range(B):
+        for h in range(H):
+            for t in range(T):
+                m_old, m = int(p.map[b, h, t]), int(mp[b, h, t])
+                if m == 0:
+                    continue
+                old_slot, old_flag = map_slot(m_old), abs(m_old) & MAP_F16
+                if m > 0:                                   # DENSE stays DENSE
+                    dense[b, h, m - 1] = p.dense[b, h, old_slot]
+                    mp[b, h, t] = m | old_flag
+                elif m_old < 0:                             # SPARSE24 stays SPARSE24
+                    nnz[b, h, -m - 1] = p.nnz[b, h, old_slot]
+                    meta[b, h, -m - 1] = p.meta[b, h, old_slot]
+                    mp[b, h, t] = -(-m | old_flag)
+                else:                                       # DENSE -> SPARSE24: prune what is stored
+                    tile = p.dense[b, h, old_slot]
+                    if old_flag:
+                        tile = f16_bits_to_bf16_bits(tile)
+                    if p.kind == "k":
+                        tm = element_mask_k(tile[None, None], element_rule)[0, 0]
+                        nnz[b, h, -m - 1], meta[b, h, -m - 1] = pack_k_tile(tile, tm)
+                    else:
+                        tm = element_mask_v(tile[None, None], element_rule)[0, 0]
+                        vals, meta[b, h, -m - 1] = pack_v_tile(tile, tm)
+                        nnz[b, h, -m - 1], flag = _v_tile_store(vals, v_f16)
+                        mp[b, h, t] = -(-m | flag)
+    return PackedKV(p.kind, p.Bt, p.D, mp, dense, nnz, meta, dtype=p.dtype)
+
+
+def recompress_kv(pk, pv, target_k, target_v, element_rule="magnitude"):
+    """recompress for K and V together; a tile is dropped from both or from neither."""
+    target_k, target_v = np.asarray(target_k), np.asarray(target_v)
+    assert ((target_k == SKIP) == (target_v == SKIP)).all()
+    return recompress(pk, target_k, element_rule), recompress(pv, target_v, element_rule)
+
+
 def unpack_tensor(p):
     """Packed -> dense bf16 bits [B, Hkv, L, D] with zeros at pruned positions and
     in skipped tiles."""

@@ -417,6 +417,82 @@ def test_append_in_tile_order_rebuilds_the_one_shot_cache():
     assert (orc.unpack_tensor(pk2) == orc.unpack_tensor(pk1)).all()
 
 
+def _same_packed(a, b):
+    assert (a.map == b.map).all()
+    for t in np.argwhere(a.map != 0):
+        m = int(a.map[tuple(t)])
+        slot = orc.map_slot(m)
+        if m > 0:
+            assert (a.dense[t[0], t[1], slot] == b.dense[t[0], t[1], slot]).all()
+        else:
+            assert (a.nnz[t[0], t[1], slot] == b.nnz[t[0], t[1], slot]).all()
+            assert (a.meta[t[0], t[1], slot] == b.meta[t[0], t[1], slot]).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_further_pruning_of_a_packed_cache_equals_compressing_with_the_sparser_states(dtype):
+    """Pruning the packed cache again towards target states B gives, bit for bit, what compressing the
+    original tensors with the tile-wise sparser of (A, B) gives: 2:4 tiles keep what they hold, dense
+    tiles are pruned from the values they store (which are the original ones), dropped tiles vanish,
+    slots are handed out again in sequence order.  By hand on one group as well."""
+    rng = np.random.default_rng(14)
+    B, H, T, Bt, D = 2, 2, 9, 16, 16
+    to_bits = wl.f32_to_f16_bits if dtype == "fp16" else wl.f32_to_bf16_bits
+    Kf = rng.standard_normal((B, H, T * Bt, D)).astype(np.float32)
+    Vf = rng.standard_normal((B, H, T * Bt, D)).astype(np.float32)
+    if dtype == "bf16":
+        Vf = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(Vf))
+        # tile 2: one value per group of 4 tokens far under fp16's range and small enough to be pruned:
+        # the dense tile is not exact in fp16, its 2:4 form is
+        Vf[:, :, 2 * Bt:3 * Bt:4] = 2.0 ** -40
+        Vf[:, :, 3 * Bt:4 * Bt] *= 2.0 ** -22            # tile 3: stays bf16 in either form
+    K, V = to_bits(Kf), to_bits(Vf)
+    order = {orc.DENSE: 0, orc.SPARSE24: 1, orc.SKIP: 2}
+    A_k = rng.choice([1, 2], size=(B, H, T)).astype(np.int8)
+    A_v = rng.choice([1, 2], size=(B, H, T)).astype(np.int8)
+    A_v[:, :, 2:4] = orc.DENSE
+    skip_a = rng.random((B, H, T)) < 0.15
+    skip_a[:, :, 2:4] = False
+    A_k[skip_a] = 0
+    A_v[skip_a] = 0
+    B_k = rng.choice([1, 2], size=(B, H, T)).astype(np.int8)
+    B_v = rng.choice([1, 2], size=(B, H, T)).astype(np.int8)
+    B_v[:, :, 2:4] = orc.SPARSE24
+    skip_b = rng.random((B, H, T)) < 0.15
+    skip_b[:, :, 2:4] = False
+    B_k[skip_b] = 0
+    B_v[skip_b] = 0
+    pk, pv, _ = orc.compress_kv(K, V, Bt=Bt, state_k=A_k, state_v=A_v, dtype=dtype)
+    if dtype == "bf16":
+        assert not orc.map_is_f16(pv.map[0, 0, 2]) and not orc.map_is_f16(pv.map[0, 0, 3])
+    keep = (pk.map.copy(), pk.dense.copy(), pk.nnz.copy())
+    rk, rv = orc.recompress_kv(pk, pv, B_k, B_v)
+    assert (keep[0] == pk.map).all() and (keep[1] == pk.dense).all() and (keep[2] == pk.nnz).all()   # source untouched
+    merge = np.vectorize(lambda a, b: a if order[a] >= order[b] else b)
+    C_k, C_v = merge(A_k, B_k).astype(np.int8), merge(A_v, B_v).astype(np.int8)
+    assert (C_k[skip_a | skip_b] == 0).all() and (C_k[(A_k == 2) & ~skip_b] == 2).all()
+    ck, cv, _ = orc.compress_kv(K, V, Bt=Bt, state_k=C_k, state_v=C_v, dtype=dtype)
+    _same_packed(rk, ck)
+    _same_packed(rv, cv)
+    if dtype == "bf16":
+        assert orc.map_is_f16(rv.map[0, 0, 2]) and not orc.map_is_f16(rv.map[0, 0, 3])
+    # no further pruning asked for: nothing changes
+    nk, nv = orc.recompress_kv(pk, pv, np.where(A_k == 0, 0, 1), np.where(A_v == 0, 0, 1))
+    _same_packed(nk, pk)
+    _same_packed(nv, pv)
+    # by hand: a dense K tile whose first group of token 0 is (1, -3, 2, 0.5) keeps -3 and 2
+    Kh = np.zeros((1, 1, Bt, D), dtype=np.float32)
+    Kh[0, 0, 0, :4] = [1.0, -3.0, 2.0, 0.5]
+    Vh = np.zeros((1, 1, Bt, D), dtype=np.float32)
+    Vh[0, 0, :4, 5] = [0.25, 4.0, -0.125, -8.0]           # tokens 0..3 of channel 5: keeps 4 and -8
+    dense = np.ones((1, 1, 1), dtype=np.int8)
+    hk, hv, _ = orc.compress_kv(to_bits(Kh), to_bits(Vh), Bt=Bt, state_k=dense, state_v=dense, dtype=dtype)
+    hk2, hv2 = orc.recompress_kv(hk, hv, 2 * dense, 2 * dense)
+    assert hk2.map[0, 0, 0] < 0 and hv2.map[0, 0, 0] < 0
+    assert orc.to_f64(orc.unpack_tensor(hk2), dtype)[0, 0, 0, :4].tolist() == [0.0, -3.0, 2.0, 0.0]
+    assert orc.to_f64(orc.unpack_tensor(hv2), dtype)[0, 0, :4, 5].tolist() == [0.0, 4.0, 0.0, -8.0]
+
+
 def test_fp16_patterns_are_read_as_ieee_binary16():
     """The fp16 path differs from bf16 only in what the 16-bit patterns mean: same masks and packed bits,
     values per IEEE binary16 (checked on hand-written patterns and against struct's 'e' format), scores and
