@@ -105,7 +105,20 @@ def extra_legs(hb, torch, Q, K, V, qd, sh, args):
     res["sk0_sv1_same_workload"] = {"prefill_ms": t_p * 1e3, "decode_us": t_d * 1e6,
                                     "decode_GBps": packed_bytes(B, Hkv, T, cts) / t_d / 1e9,
                                     "ideal_prefill_speedup": 4.0 / 3.0, "ideal_decode_speedup": 1.0 / (1.0 - 0.21875)}
-    del kvm
+    # (1a) differentiated sparsity: that prefill cache pruned further to S_K = S_V = 1 for decode
+    # (the dense key pool is read, pruned and packed; the 2:4 value pool is copied)
+    pol1 = hb.make_policy()
+    cts1 = hb.tile_counts(sh, pol1)
+    kv_dec = [hb.recompress_kv(sh, kvm[i], pol1) for i in range(6)]
+    ws_r = torch.empty(hb.workspace_bytes(sh, 3), dtype=torch.uint8, device="cuda")
+    t_r = _time(torch, lambda i: hb.recompress_kv(sh, kvm[i % 6], pol1, out=kv_dec[i % 6], workspace=ws_r), 12, warm=2)
+    t_d2 = _time(torch, lambda i: hb.decode_attn(sh, qd, kv_dec[i % 6], n_splits=n, want_lse=False, out=Od, workspace=ws_d), 24, warm=6)
+    res["sk0_sv1_prefill_then_sk1_sv1_decode"] = {
+        "recompress_us": t_r * 1e6,
+        "recompress_GBps": (packed_bytes(B, Hkv, T, cts) + packed_bytes(B, Hkv, T, cts1)) / t_r / 1e9,
+        "decode_us": t_d2 * 1e6, "decode_GBps": packed_bytes(B, Hkv, T, cts1) / t_d2 / 1e9,
+        "note": "recompress includes one stream synchronisation (upload of the target states)"}
+    del kvm, kv_dec
     # (1b) block-sparsity sweep S_K = S_V = S with the paper's pruning-loss ranking (Eq. 2c-d), against
     # the analytical curves of Sec. III-D: decode 1/(1 - 0.4375 S), prefill 4/(4 - 2S)
     sweep_s = []

@@ -154,7 +154,7 @@ HS_API int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_
 HS_API int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t bytes[8]);
 
 /* Workspace bytes needed by each call.  [host, pure]
- *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto) */
+ *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto), 3 re-compress */
 HS_API int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes);
 
 /* Number of KV splits hs_decode_attn uses when n_splits == 0. [host, pure] */
@@ -186,6 +186,26 @@ HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
 HS_API int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, int32_t state_v,
                    int32_t element_rule, const void* K_tile, const void* V_tile,
                    const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
+
+/* Prune a packed cache further (Sec. III, overview of the workflow: after the prefill phase the
+ * dense pool can be pruned and compressed again, so that decode runs at another sparsity than
+ * prefill; Sec. V evaluates prefill at S_K = 0, S_V = 1 followed by decode at S_K = S_V = 1).
+ * Every tile of `dst` is in the sparser of its state in `src` and its target state (DENSE, then
+ * 2:4, then SKIP): a tile that keeps its kind is copied bit for bit, a DENSE tile that becomes
+ * 2:4 is pruned from the values it stores (element rule of `target`), a tile that becomes SKIP is
+ * dropped; slots of `dst` are handed out again in tile order, one counter per pool (Sec. III-B).
+ * The result equals hs_compress_kv of the original tensors with those states, bit for bit.
+ * target: explicit states (host arrays, as for hs_compress_kv), or whole-tensor fractions --
+ * skip_frac == 0 and sparse_frac_k, sparse_frac_v each 0 or 1, with dense_first_tiles /
+ * dense_last_tiles kept DENSE; other fractions would need a ranking of packed data:
+ * HS_EUNSUPPORTED.
+ * src, dst: distinct caches of the same shape (no overlap); dst's capacities are the caller's
+ * choice: a tile whose slot lies beyond one of them is left SKIP in K and V and `overflow` (device
+ * int32, set to 0 by the caller; may be NULL) is set to 1.  dst->uniform is not read.
+ * workspace: hs_workspace_bytes(op 3) device bytes.  Synchronises the stream once (upload of the
+ * target states) before its two launches. */
+HS_API int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv* src, const hs_kv* dst,
+                     void* workspace, int32_t* overflow, void* stream);
 
 /* Inverse of the packing, for tests and debugging: dense bf16 [B, Hkv, L, D]
  * (contiguous) with zeros at pruned positions and in skipped tiles. */

@@ -49,6 +49,8 @@ EXPORTS = {
     "hs_compress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
     "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_recompress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(HsKV), C.POINTER(HsKV), C.c_void_p,
+                                   C.c_void_p, C.c_void_p]),
     "hs_prefill_attn": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_float, C.c_int, C.c_void_p, C.POINTER(HsKV),
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
@@ -216,6 +218,32 @@ def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARS
     kvs = kv.struct()
     _check(lib().hs_append_tile(C.byref(shape), int(tile), int(state_k), int(state_v), int(element_rule), _ptr(K_tile),
                                 _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
+
+
+def recompress_kv(shape, kv, target, counts=None, overflow=None, out=None, workspace=None):
+    """Prune the packed cache `kv` further towards the policy `target` (make_policy: explicit states,
+    or fractions 0 / 1 with protected end tiles).  Returns a new PackedKV; counts = capacities of
+    the new pools as [_, dense K, 2:4 K, dense V, 2:4 V] (default: enough for any outcome); out: a
+    PackedKV to fill instead of a new one."""
+    T = shape.L // TILE
+    if counts is None:
+        counts = [0, kv.counts[1], min(T, kv.counts[1] + kv.counts[2]), kv.counts[3], min(T, kv.counts[3] + kv.counts[4])]
+        if not target.state_k:
+            prot = min(T, target.dense_first_tiles + target.dense_last_tiles)
+            if target.sparse_frac_k == 1.0:
+                counts[1] = min(counts[1], prot)
+            if target.sparse_frac_v == 1.0:
+                counts[3] = min(counts[3], prot)
+    if out is None:
+        out = PackedKV(shape, counts, kv.k_map.device)
+    counts = out.counts
+    # slot == tile survives when nothing was skipped before and each tensor ends up in one kind
+    out.uniform = int(bool(kv.uniform) and not target.state_k and counts[1] * counts[2] == 0 and counts[3] * counts[4] == 0
+                      and max(counts[1], counts[2]) == T and max(counts[3], counts[4]) == T)
+    ws = _workspace(workspace_bytes(shape, 3), kv.k_map.device) if workspace is None else workspace
+    a, b = kv.struct(), out.struct()
+    _check(lib().hs_recompress_kv(C.byref(shape), C.byref(target), C.byref(a), C.byref(b), _ptr(ws), _ptr(overflow), _stream()))
+    return out
 
 
 def unpack_kv(shape, kv):

@@ -201,6 +201,7 @@ int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes
       *bytes = (size_t)shape->B * shape->Hq * (size_t)n * (HS_D + 1) * sizeof(float);
       return HS_OK;
     }
+    case 3: *bytes = (2 * rows * T + 15) / 16 * 16; return HS_OK;
     default: return HS_EINVAL;
   }
 }
@@ -314,6 +315,57 @@ int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, int32_t
   const hipError_t e = hs_launch_append((const uint16_t*)K_tile, (const uint16_t*)V_tile, sb, sh, st, shape->B,
                                         shape->Hkv, T, tile, state_k, state_v, hs_make_kv_dev(kv), element_rule,
                                         shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
+int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv* src, const hs_kv* dst,
+                     void* workspace, int32_t* overflow, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  rc = check_policy(target);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, src);
+  if (rc != HS_OK) return rc;
+  rc = check_kv(shape, dst);
+  if (rc != HS_OK) return rc;
+  if (workspace == nullptr) return HS_EINVAL;
+  if (src->k_map == dst->k_map || src->v_map == dst->v_map) return HS_EINVAL;  // not in place: slots move
+  const int T = shape->L / HS_BT;
+  const int64_t rows = (int64_t)shape->B * shape->Hkv;
+  // target states on the host; [0, rows*T) keys, [rows*T, 2*rows*T) values
+  std::vector<int8_t> tgt((size_t)(2 * rows * T));
+  int8_t* tk = tgt.data();
+  int8_t* tv = tgt.data() + rows * T;
+  if (target->state_k != nullptr) {
+    int32_t c[5];
+    rc = explicit_counts(shape, target, c);  // validates the values and that K and V skip together
+    if (rc != HS_OK) return rc;
+    memcpy(tk, target->state_k, (size_t)(rows * T));
+    memcpy(tv, target->state_v, (size_t)(rows * T));
+  } else {
+    // without a ranking only whole-tensor targets are defined: S in {0, 1}, nothing skipped
+    if (target->skip_frac != 0.0) return HS_EUNSUPPORTED;
+    if ((target->sparse_frac_k != 0.0 && target->sparse_frac_k != 1.0) ||
+        (target->sparse_frac_v != 0.0 && target->sparse_frac_v != 1.0))
+      return HS_EUNSUPPORTED;
+    int n_first, n_last;
+    protected_tiles(T, target, &n_first, &n_last);
+    for (int64_t r = 0; r < rows; r++)
+      for (int t = 0; t < T; t++) {
+        const bool prot = t < n_first || t >= T - n_last;
+        tk[r * T + t] = prot || target->sparse_frac_k == 0.0 ? HS_DENSE : HS_SPARSE24;
+        tv[r * T + t] = prot || target->sparse_frac_v == 0.0 ? HS_DENSE : HS_SPARSE24;
+      }
+  }
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(workspace, tgt.data(), tgt.size(), hipMemcpyHostToDevice, s);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipStreamSynchronize(s);  // the host vector dies at return
+  if (e != hipSuccess) return hip_fail(e);
+  e = hs_launch_recompress(shape->B, shape->Hkv, T, hs_make_kv_dev(src), (const int8_t*)workspace,
+                           (const int8_t*)workspace + rows * T, hs_make_kv_dev(dst), target->element_rule,
+                           shape->dtype == HS_BF16, overflow, s);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

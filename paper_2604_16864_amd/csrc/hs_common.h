@@ -140,6 +140,9 @@ hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int6
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
                             int B, int Hkv, int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule,
                             int v_f16, int32_t* overflow, hipStream_t st);
+// packed cache -> packed cache, each tile in the sparser of its state and its target (device int8 [rows, T])
+hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,
+                                hs_kv_dev dst, int rule, int v_f16, int32_t* overflow, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 // tail_len < 0: no tail slot; tail_len >= 0: one extra partial per query head, computed from the
 // dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D])

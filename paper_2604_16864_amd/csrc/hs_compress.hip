@@ -261,6 +261,127 @@ __device__ __forceinline__ uint32_t pair_to_bf16(uint32_t f16_pair) {  // exact 
 }
 
 // ----------------------------------------------------------------------------------
+// Tile writers shared by the compress, append and re-compress kernels.  Workgroup of 4 waves;
+// wave w, lane l = 16a + r.
+// ----------------------------------------------------------------------------------
+// 2:4 K tile.  Lane (w, a, r) prunes token 16w + r, channels 64kb + 16a .. +16 for kb = 0, 1;
+// load(kb, half) returns the 8 channels 64kb + 16a + 8 half .. +8 of that token.
+template <class Load>
+__device__ __forceinline__ void k_sparse_store(uint8_t* nnz, uint8_t* meta, int w, int l, int rule, Load load) {
+  uint32_t idx = 0;
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++) {
+    const uint4 d0 = load(kb, 0);
+    const uint4 d1 = load(kb, 1);
+    const uint32_t wds[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+    uint32_t out[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
+      uint32_t nib;
+      top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, out[q], nib);
+      idx |= nib << (16 * kb + 4 * q);
+    }
+    *reinterpret_cast<uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+  }
+  *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
+}
+
+// V tile (dense if mv > 0, 2:4 if mv < 0; mv = +-(slot + 1), workgroup-uniform, != 0) from the
+// tile staged in LDS as vl[token][channel] (row stride kVStride); the caller has synchronised.
+// The words to store are built first.  v_f16 (bf16 cache): if every value the tile stores is
+// exact in fp16 (workgroup vote), the tile is written in fp16 encoding and *map_entry, which the
+// caller has set to mv, gets HS_MAP_F16, so that the attention kernels can feed the softmax
+// numerators as one fp16 term.  Every thread of the workgroup must call this.
+__device__ __forceinline__ void v_tile_store(const uint16_t* vl, int mv, int32_t* map_entry, const hs_kv_dev& kv,
+                                             int64_t row, int rule, int v_f16, int tid) {
+  const int w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
+  uint32_t words[4][4];
+  const int n_chunks = mv > 0 ? 4 : 2;  // 16-byte chunks this lane stores
+  uint32_t idx = 0;
+  if (mv > 0) {
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1;
+      const int c = 16 * mb + r;
+#pragma unroll
+      for (int p = 0; p < 4; p++) {
+        const int e0 = 2 * p, e1 = 2 * p + 1;
+        const int tok0 = 16 * (2 * hh + (e0 >> 2)) + 4 * a + (e0 & 3);
+        const int tok1 = 16 * (2 * hh + (e1 >> 2)) + 4 * a + (e1 & 3);
+        words[j][p] = (uint32_t)vl[tok0 * kVStride + c] | ((uint32_t)vl[tok1 * kVStride + c] << 16);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int mb = 2 * w + j, c = 16 * mb + r;
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int g = hs_v_group(a, q);
+        const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
+        const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
+        uint32_t nib;
+        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, words[j][q], nib);
+        idx |= nib << (16 * j + 4 * q);
+      }
+    }
+  }
+  if (v_f16) {  // workgroup-uniform
+    uint32_t conv[4][4];
+    int bad = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int p = 0; p < 4; p++)
+        if (j < n_chunks) bad |= !pair_to_f16(words[j][p], conv[j][p]);
+    if (!__syncthreads_or(bad)) {
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int p = 0; p < 4; p++)
+          if (j < n_chunks) words[j][p] = conv[j][p];
+      if (tid == 0) *map_entry = mv > 0 ? (mv | HS_MAP_F16) : -(-mv | HS_MAP_F16);
+    }
+  }
+  if (mv > 0) {
+    uint8_t* dst = const_cast<uint8_t*>(kv.v_dense) + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+      *reinterpret_cast<uint4*>(dst + ((4 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+  } else {
+    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
+    uint8_t* nnz = const_cast<uint8_t*>(kv.v_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    uint8_t* meta = const_cast<uint8_t*>(kv.v_meta) + slot * (int64_t)HS_TILE_META_BYTES;
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+      *reinterpret_cast<uint4*>(nnz + ((2 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+    *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
+  }
+}
+
+// Dense V tile in pool order -> vl[token][channel], as bf16 patterns when the tile is held in fp16
+// encoding (is_f16); the caller synchronises afterwards.
+__device__ __forceinline__ void v_dense_to_lds(const uint8_t* src, bool is_f16, uint16_t* vl, int tid) {
+  const int w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1, c = 16 * mb + r;
+    const uint4 d = *reinterpret_cast<const uint4*>(src + (ch * 64 + l) * 16);
+    uint32_t vals[4] = {d.x, d.y, d.z, d.w};
+    if (is_f16) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) vals[i] = pair_to_bf16(vals[i]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const int tok = 16 * (2 * hh + (e >> 2)) + 4 * a + (e & 3);
+      vl[tok * kVStride + c] = (uint16_t)((vals[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------
 // Fused prune + pack (Sec. IV-B): one workgroup per tile, K then V.
 // ----------------------------------------------------------------------------------
 // uni_k / uni_v: 0 = read the tile's map entries (written by an earlier launch); HS_DENSE or
@@ -301,97 +422,139 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
     }
   } else if (mk < 0) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
-    uint8_t* nnz = const_cast<uint8_t*>(kv.k_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
-    uint8_t* meta = const_cast<uint8_t*>(kv.k_meta) + slot * (int64_t)HS_TILE_META_BYTES;
     const uint16_t* src = kt + (int64_t)(16 * w + r) * st + 16 * a;
-    uint32_t idx = 0;
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-      const uint4 d0 = *reinterpret_cast<const uint4*>(src + 64 * kb);
-      const uint4 d1 = *reinterpret_cast<const uint4*>(src + 64 * kb + 8);
-      const uint32_t wds[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-      uint32_t out[4];
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
-        uint32_t nib;
-        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, out[q], nib);
-        idx |= nib << (16 * kb + 4 * q);
-      }
-      *reinterpret_cast<uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
-    }
-    *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
+    k_sparse_store(const_cast<uint8_t*>(kv.k_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES,
+                   const_cast<uint8_t*>(kv.k_meta) + slot * (int64_t)HS_TILE_META_BYTES, w, l, rule,
+                   [&](int kb, int half) { return *reinterpret_cast<const uint4*>(src + 64 * kb + 8 * half); });
   }
 
   // ---- V ----
-  // The words to store are built first.  v_f16 (bf16 cache): if every value the tile stores is
-  // exact in fp16 (workgroup vote), the tile is written in fp16 encoding and its map entry gets
-  // HS_MAP_F16, so that the attention kernels can feed the softmax numerators as one fp16 term.
   if (mv == 0) return;
   __syncthreads();
-  uint32_t words[4][4];
-  const int n_chunks = mv > 0 ? 4 : 2;  // 16-byte chunks this lane stores
-  uint32_t idx = 0;
-  if (mv > 0) {
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-      const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1;
-      const int c = 16 * mb + r;
-#pragma unroll
-      for (int p = 0; p < 4; p++) {
-        const int e0 = 2 * p, e1 = 2 * p + 1;
-        const int tok0 = 16 * (2 * hh + (e0 >> 2)) + 4 * a + (e0 & 3);
-        const int tok1 = 16 * (2 * hh + (e1 >> 2)) + 4 * a + (e1 & 3);
-        words[j][p] = (uint32_t)vl[tok0 * kVStride + c] | ((uint32_t)vl[tok1 * kVStride + c] << 16);
+  v_tile_store(vl, mv, const_cast<int32_t*>(kv.v_map) + row * T + t, kv, row, rule, v_f16, tid);
+}
+
+// ----------------------------------------------------------------------------------
+// Further pruning of a packed cache (Sec. III, overview: after the prefill phase the dense pool
+// can be pruned and compressed again, so that decode runs at another sparsity than prefill).
+// ----------------------------------------------------------------------------------
+// New state of a tile = the sparser of its current state and its target (DENSE < 2:4 < SKIP).
+__device__ __forceinline__ int sparser_state(int map_entry, int target) {
+  const int cur = map_entry > 0 ? HS_DENSE : (map_entry < 0 ? HS_SPARSE24 : HS_SKIP);
+  const int rc = cur == HS_SKIP ? 2 : cur - 1, rt = target == HS_SKIP ? 2 : target - 1;
+  const int rn = rc > rt ? rc : rt;
+  return rn == 2 ? HS_SKIP : rn + 1;
+}
+
+// Maps of the re-compressed cache: slots in ascending tile order with one counter per pool
+// (Sec. III-B); a tile that keeps its kind keeps its encoding bit.  A tile whose K or V slot
+// lies beyond the capacity of dst is left out of both tensors and *overflow is raised.
+// One workgroup per row, each thread owns a contiguous chunk of tiles.
+__global__ __launch_bounds__(256) void restate_kernel(int T, hs_kv_dev src, const int8_t* __restrict__ tgt_k,
+                                                      const int8_t* __restrict__ tgt_v, hs_kv_dev dst,
+                                                      int32_t* overflow) {
+  __shared__ int part[4][256];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int32_t* skm = src.k_map + (int64_t)row * T;
+  const int32_t* svm = src.v_map + (int64_t)row * T;
+  int32_t* km = const_cast<int32_t*>(dst.k_map) + (int64_t)row * T;
+  int32_t* vm = const_cast<int32_t*>(dst.v_map) + (int64_t)row * T;
+  const int8_t* tk = tgt_k + (int64_t)row * T;
+  const int8_t* tv = tgt_v + (int64_t)row * T;
+  const int per = (T + 255) / 256;
+  const int t0 = min(tid * per, T), t1 = min(t0 + per, T);
+  int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
+  for (int t = t0; t < t1; t++) {
+    const int sk = sparser_state(skm[t], tk[t]), sv = sparser_state(svm[t], tv[t]);
+    ndk += sk == HS_DENSE; nsk += sk == HS_SPARSE24; ndv += sv == HS_DENSE; nsv += sv == HS_SPARSE24;
+  }
+  part[0][tid] = ndk; part[1][tid] = nsk; part[2][tid] = ndv; part[3][tid] = nsv;
+  __syncthreads();
+  if (tid < 4) {
+    int acc = 0;
+    for (int i = 0; i < 256; i++) { const int v = part[tid][i]; part[tid][i] = acc; acc += v; }
+  }
+  __syncthreads();
+  ndk = part[0][tid]; nsk = part[1][tid]; ndv = part[2][tid]; nsv = part[3][tid];
+  for (int t = t0; t < t1; t++) {
+    const int mk_old = skm[t], mv_old = svm[t];
+    const int sk = sparser_state(mk_old, tk[t]), sv = sparser_state(mv_old, tv[t]);
+    int mk = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
+    int mv = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
+    const bool fits = (mk > 0 ? mk <= dst.cap_dense_k : -mk <= dst.cap_sparse_k) &&
+                      (mv > 0 ? mv <= dst.cap_dense_v : -mv <= dst.cap_sparse_v);
+    if (!fits || mk == 0 || mv == 0) {
+      if (mk != 0 || mv != 0) {
+        if (!fits && overflow != nullptr) *overflow = 1;
       }
+      mk = 0;
+      mv = 0;
+    } else if ((mv > 0) == (mv_old > 0) && hs_map_f16(mv_old)) {
+      mv = mv > 0 ? (mv | HS_MAP_F16) : -(-mv | HS_MAP_F16);
     }
+    km[t] = mk;
+    vm[t] = mv;
+  }
+}
+
+// One workgroup per tile: tiles that keep their kind are copied slot to slot; a dense tile that
+// became 2:4 is read from its dense slot (pool order) and pruned with the writers above.
+__global__ __launch_bounds__(256) void repack_kernel(int Hkv, int T, hs_kv_dev src, hs_kv_dev dst, int rule, int v_f16) {
+  __shared__ uint16_t vl[HS_BT * kVStride];
+  const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
+  const int64_t row = (int64_t)b * Hkv + h;
+  const int mk_old = src.k_map[row * T + t], mv_old_raw = src.v_map[row * T + t];
+  const int mk = dst.k_map[row * T + t], mv_raw = dst.v_map[row * T + t];
+  if (mk == 0 || mv_raw == 0) return;  // dropped (both tensors together)
+  const int mv_old = hs_map_plain(mv_old_raw), mv = hs_map_plain(mv_raw);
+  // ---- K ----
+  if (mk > 0) {
+    const uint4* s4 = reinterpret_cast<const uint4*>(src.k_dense + (row * src.cap_dense_k + (mk_old - 1)) * (int64_t)HS_TILE_DENSE_BYTES);
+    uint4* d4 = reinterpret_cast<uint4*>(const_cast<uint8_t*>(dst.k_dense) + (row * dst.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES);
+#pragma unroll
+    for (int i = 0; i < 4; i++) d4[i * 256 + tid] = s4[i * 256 + tid];
   } else {
+    const int64_t slot = row * dst.cap_sparse_k + (-mk - 1);
+    uint8_t* nnz = const_cast<uint8_t*>(dst.k_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
+    uint8_t* meta = const_cast<uint8_t*>(dst.k_meta) + slot * (int64_t)HS_TILE_META_BYTES;
+    if (mk_old < 0) {
+      const int64_t so = row * src.cap_sparse_k + (-mk_old - 1);
+      const uint4* s4 = reinterpret_cast<const uint4*>(src.k_nnz + so * (int64_t)HS_TILE_NNZ_BYTES);
+      uint4* d4 = reinterpret_cast<uint4*>(nnz);
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      const int mb = 2 * w + j, c = 16 * mb + r;
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int g = hs_v_group(a, q);
-        const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
-        const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
-        uint32_t nib;
-        top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, words[j][q], nib);
-        idx |= nib << (16 * j + 4 * q);
-      }
+      for (int i = 0; i < 2; i++) d4[i * 256 + tid] = s4[i * 256 + tid];
+      if (tid < 64)
+        reinterpret_cast<uint4*>(meta)[tid] = reinterpret_cast<const uint4*>(src.k_meta + so * (int64_t)HS_TILE_META_BYTES)[tid];
+    } else {
+      // dense pool order: chunk 4w + s of lane (a', r) = token 16w + r, channels 32s + 8a' .. +8
+      const uint8_t* sd = src.k_dense + (row * src.cap_dense_k + (mk_old - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+      k_sparse_store(nnz, meta, w, l, rule, [&](int kb, int half) {
+        const int s = 2 * kb + (a >> 1), a2 = 2 * (a & 1) + half;
+        return *reinterpret_cast<const uint4*>(sd + ((w * 4 + s) * 64 + 16 * a2 + r) * 16);
+      });
     }
   }
-  int as_f16 = 0;
-  if (v_f16) {  // workgroup-uniform
-    uint32_t conv[4][4];
-    int bad = 0;
-#pragma unroll
-    for (int j = 0; j < 4; j++)
-#pragma unroll
-      for (int p = 0; p < 4; p++)
-        if (j < n_chunks) bad |= !pair_to_f16(words[j][p], conv[j][p]);
-    as_f16 = !__syncthreads_or(bad);
-    if (as_f16) {
-#pragma unroll
-      for (int j = 0; j < 4; j++)
-#pragma unroll
-        for (int p = 0; p < 4; p++)
-          if (j < n_chunks) words[j][p] = conv[j][p];
-      if (tid == 0) const_cast<int32_t*>(kv.v_map)[row * T + t] = mv > 0 ? (mv | HS_MAP_F16) : -(-mv | HS_MAP_F16);
-    }
-  }
+  // ---- V ---- (branches are workgroup-uniform)
   if (mv > 0) {
-    uint8_t* dst = const_cast<uint8_t*>(kv.v_dense) + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
+    const uint4* s4 = reinterpret_cast<const uint4*>(src.v_dense + (row * src.cap_dense_v + (mv_old - 1)) * (int64_t)HS_TILE_DENSE_BYTES);
+    uint4* d4 = reinterpret_cast<uint4*>(const_cast<uint8_t*>(dst.v_dense) + (row * dst.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES);
 #pragma unroll
-    for (int j = 0; j < 4; j++)
-      *reinterpret_cast<uint4*>(dst + ((4 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+    for (int i = 0; i < 4; i++) d4[i * 256 + tid] = s4[i * 256 + tid];
+  } else if (mv_old < 0) {
+    const int64_t so = row * src.cap_sparse_v + (-mv_old - 1), sn = row * dst.cap_sparse_v + (-mv - 1);
+    const uint4* s4 = reinterpret_cast<const uint4*>(src.v_nnz + so * (int64_t)HS_TILE_NNZ_BYTES);
+    uint4* d4 = reinterpret_cast<uint4*>(const_cast<uint8_t*>(dst.v_nnz) + sn * (int64_t)HS_TILE_NNZ_BYTES);
+#pragma unroll
+    for (int i = 0; i < 2; i++) d4[i * 256 + tid] = s4[i * 256 + tid];
+    if (tid < 64)
+      reinterpret_cast<uint4*>(const_cast<uint8_t*>(dst.v_meta) + sn * (int64_t)HS_TILE_META_BYTES)[tid] =
+          reinterpret_cast<const uint4*>(src.v_meta + so * (int64_t)HS_TILE_META_BYTES)[tid];
   } else {
-    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
-    uint8_t* nnz = const_cast<uint8_t*>(kv.v_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
-    uint8_t* meta = const_cast<uint8_t*>(kv.v_meta) + slot * (int64_t)HS_TILE_META_BYTES;
-#pragma unroll
-    for (int j = 0; j < 2; j++)
-      *reinterpret_cast<uint4*>(nnz + ((2 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
-    *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
+    v_dense_to_lds(src.v_dense + (row * src.cap_dense_v + (mv_old - 1)) * (int64_t)HS_TILE_DENSE_BYTES,
+                   hs_map_f16(mv_old_raw), vl, tid);
+    __syncthreads();
+    v_tile_store(vl, mv, const_cast<int32_t*>(dst.v_map) + row * T + t, dst, row, rule, v_f16, tid);
   }
 }
 
@@ -452,22 +615,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
   }
   // V: rebuild the tile in LDS in [token][channel] order, then store it coalesced
   if (mv > 0) {
-    const uint8_t* src = kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-      const int ch = 4 * w + j, mb = ch >> 1, hh = ch & 1, c = 16 * mb + r;
-      const uint4 d = *reinterpret_cast<const uint4*>(src + (ch * 64 + l) * 16);
-      uint32_t vals[4] = {d.x, d.y, d.z, d.w};
-      if (v_is_f16) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) vals[i] = pair_to_bf16(vals[i]);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; e++) {
-        const int tok = 16 * (2 * hh + (e >> 2)) + 4 * a + (e & 3);
-        vl[tok * kVStride + c] = (uint16_t)((vals[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-      }
-    }
+    v_dense_to_lds(kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES, v_is_f16, vl, tid);
   } else if (mv < 0) {
     const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
     const uint8_t* nnz = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES;
@@ -543,6 +691,15 @@ hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, in
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(pack_kernel, dim3(1, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16);
+  return hipGetLastError();
+}
+
+hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,
+                                hs_kv_dev dst, int rule, int v_f16, int32_t* overflow, hipStream_t st) {
+  hipLaunchKernelGGL(restate_kernel, dim3(B * Hkv), dim3(256), 0, st, T, src, tgt_k, tgt_v, dst, overflow);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(repack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, Hkv, T, src, dst, rule, v_f16);
   return hipGetLastError();
 }
 

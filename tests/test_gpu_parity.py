@@ -654,6 +654,101 @@ def test_bf16_cache_with_both_v_tile_encodings(pol, planted):
         assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode v encodings lse")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_recompress_explicit_states_bit_exact_and_attention(dtype):
+    """Further pruning of a packed cache (dense -> 2:4, anything -> dropped, the rest carried over) against
+    the oracle, bit for bit, then attention over the result."""
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 19
+    T = L // 64
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=210, k_outliers=True, dtype=dtype)
+    if dtype == "bf16":
+        Vf = wl.bf16_bits_to_f32(V)
+        Vf[:, :, 64 * 2:64 * 3:4] = 2.0 ** -40          # dense form not exact in fp16, 2:4 form exact
+        Vf[:, :, 64 * 3:64 * 4] *= 2.0 ** -22           # never exact
+        V = wl.f32_to_bf16_bits(Vf)
+    sk, sv = _mixed_states(B, Hkv, T, seed=211, p_skip=0.15)
+    sk[:, :, 2:4], sv[:, :, 2:4] = 1, 1
+    tk, tv = _mixed_states(B, Hkv, T, seed=212, p_skip=0.15)
+    tk[:, :, 2:4], tv[:, :, 2:4] = 2, 2
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, dtype=dtype, state_k=sk, state_v=sv)
+    kv2 = hb.recompress_kv(sh, kv, hb.make_policy(state_k=tk, state_v=tv))
+    torch.cuda.synchronize()
+    rk, rv = orc.recompress_kv(pk, pv, tk, tv)
+    check_packed_bit_exact(sh, kv2, rk, rv)
+    check_packed_bit_exact(sh, kv, pk, pv)                  # the source is untouched
+    O, LSE = hb.prefill_attn(sh, _dev(Q, dtype), kv2)
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(B, Hq, L, 120, seed=213, extra=[(B - 1, Hq - 1, L - 1)])
+    Or, Lr = orc.attention_rows(Q, rk, rv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    assert_close(_f32(O)[idx], Or, f"prefill after recompress {dtype}")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill after recompress lse")
+    q = Q[:, :, -1, :].copy()
+    Od, LSEd = hb.decode_attn(sh, _dev(q, dtype), kv2, n_splits=3)
+    torch.cuda.synchronize()
+    Odr, Ldr = orc.attention_decode(q, rk, rv)
+    assert_close(_f32(Od), Odr, f"decode after recompress {dtype}")
+    assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode after recompress lse")
+
+
+@pytest.mark.parametrize("first,last", [(0, 0), (1, 3)])
+def test_recompress_prefill_policy_to_decode_policy(first, last):
+    """The paper's differentiated setting: prefill with keys dense and values 2:4, then every key tile
+    pruned for decode (optionally sink / local-window tiles kept dense).  Equals compressing the
+    original tensors with the decode policy, on the GPU and in the oracle."""
+    B, Hq, Hkv, L = 1, 8, 2, 64 * 16
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=220, k_outliers=True)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, sparse_frac_k=0.0, sparse_frac_v=1.0)
+    assert kv.uniform == 1
+    tgt = dict(sparse_frac_k=1.0, sparse_frac_v=1.0, dense_first_tiles=first, dense_last_tiles=last)
+    kv2 = hb.recompress_kv(sh, kv, hb.make_policy(**tgt))
+    torch.cuda.synchronize()
+    assert kv2.uniform == (1 if first + last == 0 else 0)
+    sh2, kv_direct, ck, cv, info = compress_both(B, Hq, Hkv, L, K, V, **tgt)
+    rk, rv = orc.recompress_kv(pk, pv, info["state_k"], info["state_v"])
+    check_packed_bit_exact(sh, kv2, rk, rv)
+    # V was 2:4 everywhere already: its protected tiles cannot go back to dense; K equals the direct result
+    assert (rv.map < 0).all() and (rk.map == ck.map).all()
+    Ku, _ = hb.unpack_kv(sh, kv2)
+    Kd, _ = hb.unpack_kv(sh, kv_direct)
+    torch.cuda.synchronize()
+    assert torch.equal(Ku.view(torch.int16), Kd.view(torch.int16))
+    q = Q[:, :, 0, :].copy()
+    Od, LSEd = hb.decode_attn(sh, _dev(q), kv2)
+    torch.cuda.synchronize()
+    Odr, Ldr = orc.attention_decode(q, rk, rv)
+    assert_close(_f32(Od), Odr, "decode after recompress to S_K=1")
+    assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode after recompress lse")
+
+
+def test_recompress_capacity_overflow_and_argument_errors():
+    B, Hq, Hkv, L = 1, 4, 1, 64 * 8
+    T = L // 64
+    _, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=230)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, sparse_frac_k=0.0, sparse_frac_v=0.0)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    # room for 5 of the 8 key tiles: the first 5 tiles survive, the rest is left out of K and V alike
+    kv2 = hb.recompress_kv(sh, kv, hb.make_policy(), counts=[0, 0, 5, 0, T], overflow=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 1
+    assert kv2.k_map.cpu().numpy().reshape(-1).tolist() == [-1, -2, -3, -4, -5, 0, 0, 0]
+    vm = kv2.v_map.cpu().numpy().reshape(-1)
+    assert ((np.abs(vm) & ~orc.MAP_F16) == [1, 2, 3, 4, 5, 0, 0, 0]).all() and (vm <= 0).all()
+    flag.zero_()
+    hb.recompress_kv(sh, kv, hb.make_policy(), overflow=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    with pytest.raises(hb.HsError):                         # needs a ranking of packed data
+        hb.recompress_kv(sh, kv, hb.make_policy(sparse_frac_k=0.5))
+    with pytest.raises(hb.HsError):
+        hb.recompress_kv(sh, kv, hb.make_policy(skip_frac=0.25))
+    import ctypes as C
+    a = kv.struct()
+    ws = torch.empty(hb.workspace_bytes(sh, 3), dtype=torch.uint8, device="cuda")
+    pol = hb.make_policy()
+    assert hb.lib().hs_recompress_kv(C.byref(sh), C.byref(pol), C.byref(a), C.byref(a), ws.data_ptr(), None, None) == -1
+
+
 def test_single_tile_and_odd_batch_shapes():
     """L = 64 (one tile, one split), B = 3, 3 KV heads: smallest grid dimensions on every kernel."""
     for (B, Hq, Hkv, L) in ((1, 1, 1, 64), (3, 6, 3, 64 * 3), (2, 16, 2, 64 * 2)):
