@@ -365,6 +365,44 @@ def test_decode_cfg3_shape_one_batch_row_skip75():
     assert_lse_close(LSE.cpu().numpy(), Lr, "decode cfg3 lse")
 
 
+@pytest.mark.parametrize("pol", [dict(skip_frac=0.25), dict(sparse_frac_k=0.0, sparse_frac_v=1.0)])
+def test_decode_cfg3_full_batch_sampled_rows(pol):
+    """The hierarchical decode workload at its full size (B = 8, L = 131072: 4.3 GB of K and V, pools past
+    2^31 bytes), default launch configuration.  Inputs are drawn on the device (seeded); the oracle
+    compresses and attends three sampled (batch, kv head) rows, each of which is ranked on its own."""
+    B, Hq, Hkv, L = 8, 32, 8, 131072
+    g = torch.Generator(device="cuda")
+    g.manual_seed(300)
+    K = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    V = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    q = torch.randn((B, Hq, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv = hb.compress_kv(sh, hb.make_policy(**pol), K, V)
+    O, LSE = hb.decode_attn(sh, q, kv)
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    for b, h in ((0, 0), (3, 5), (7, 7)):
+        print(f"[cfg3 full batch {sorted(pol)}] row b={b} hkv={h}", flush=True)
+        Kb, Vb = hb.bf16_tensor_to_bits(K[b:b + 1, h:h + 1]), hb.bf16_tensor_to_bits(V[b:b + 1, h:h + 1])
+        pk, pv, _ = orc.compress_kv(Kb, Vb, Bt=64, **pol)
+        assert (kv.k_map[b, h].cpu().numpy() == pk.map[0, 0]).all() and (kv.v_map[b, h].cpu().numpy() == pv.map[0, 0]).all()
+        for p, dense, nnz, meta, cd, cs in ((pk, kv.k_dense, kv.k_nnz, kv.k_meta, kv.counts[1], kv.counts[2]),
+                                            (pv, kv.v_dense, kv.v_nnz, kv.v_meta, kv.counts[3], kv.counts[4])):
+            ph = hl.physical_pools(p)
+            nd, ns = int(ph["n_dense"][0, 0]), int(ph["n_sparse"][0, 0])
+            for slot in {0, nd // 2, nd - 1} - {-1}:           # first, middle and last used slot
+                if nd:
+                    assert (dense.view(B, Hkv, cd, 16384)[b, h, slot].cpu().numpy() == ph["dense"][0, 0, slot]).all()
+            for slot in {0, ns // 2, ns - 1} - {-1}:
+                if ns:
+                    assert (nnz.view(B, Hkv, cs, 8192)[b, h, slot].cpu().numpy() == ph["nnz"][0, 0, slot]).all()
+                    assert (meta.view(B, Hkv, cs, 1024)[b, h, slot].cpu().numpy() == ph["meta"][0, 0, slot]).all()
+        qb = hb.bf16_tensor_to_bits(q[b:b + 1, G * h:G * (h + 1)])
+        Or, Lr = orc.attention_decode(qb, pk, pv)
+        assert_close(_f32(O[b:b + 1, G * h:G * (h + 1)]), Or, f"decode cfg3 full batch b{b} hkv{h}")
+        assert_lse_close(LSE[b:b + 1, G * h:G * (h + 1)].cpu().numpy(), Lr, "decode cfg3 full batch lse")
+
+
 def test_prefill_cfg4_full_size_skip75_sampled_rows():
     """Long causal prefill at the highest hierarchical sparsity (L = 65536, 75 % of the tiles
     skipped, 2:4 in the rest): seeded sampled rows plus rows that see no token at all."""
