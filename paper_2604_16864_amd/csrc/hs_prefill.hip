@@ -172,11 +172,11 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   // MID: the per-tile barrier sits between softmax and GEMM2 instead of at the end of the
   // iteration, so that the next tile's K operands can be fetched from LDS while GEMM2 runs.  Needs
   // the next tile requested at least two iterations ahead (NS >= 3), which all-2:4 keys give.
-  constexpr bool MID = F16 && KM == 0 && VM != 2;  // (fp16 caches only: the two V encodings of a bf16 cache, or mixed V, leave no registers for the K prefetch)
-  static_assert(!MID || NS >= 3, "mid-iteration barrier needs a ring of 3");
-  // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
-  // already holds the registers (both together spill; measured no gain there)
-  constexpr bool V_EARLY = F16 && VM == 0 && !MID;
+  // It is used where every V tile the workgroup meets takes one fp16 term of P (fp16 caches; rows
+  // of a bf16 cache whose V tiles are all in fp16 encoding): with both GEMM2 forms in the loop,
+  // or mixed V, no registers are left for the K prefetch.
+  constexpr bool MID_OK = KM == 0 && VM != 2;
+  static_assert(!MID_OK || NS >= 3, "mid-iteration barrier needs a ring of 3");
   constexpr int kStage = stage_bytes<KM, VM>();
   __shared__ __attribute__((aligned(16))) uint8_t lds[NS * kStage];
   const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
@@ -287,6 +287,12 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       stage_issue<KM, VM>(lds_base + sd * kStage, kv, row, tk[D], tv[D], w, lane_off);
     }
   };
+  // mid_tag: MID mode; only16_tag: every V tile ahead is known to be in fp16 encoding
+  auto main_loop = [&](auto mid_tag, auto only16_tag) {
+  constexpr bool MID = decltype(mid_tag)::value, ONLY16 = F16 || decltype(only16_tag)::value;
+  // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
+  // already holds the registers (both together spill; measured no gain there)
+  constexpr bool V_EARLY = F16 && VM == 0 && !MID;
   if (MID && valid && tj[0] >= 0) k_fetch(0);
   // One iteration = one tile.  The loop exists twice, for runs of V tiles in fp16 encoding (one fp16
   // term of P) and in bf16 (two terms), so that each copy is straight-line code around its matrix
@@ -508,15 +514,36 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     st = st + 1 == NS ? 0 : st + 1;
       };
   while (tj[0] >= 0) {
-    if (VM == 2 && !F16) {  // four GEMM2 forms in one kernel: no second copy of the loop
+    if constexpr (ONLY16) {
+      iteration(std::integral_constant<int, 1>{});
+    } else if constexpr (VM == 2) {  // four GEMM2 forms in one kernel: no second copy of the loop
       iteration(std::integral_constant<int, 2>{});
-    } else if (F16 || hs_map_f16(tv[0])) {
-      do iteration(std::integral_constant<int, 1>{});
-      while (tj[0] >= 0 && (F16 || hs_map_f16(tv[0])));
     } else {
-      do iteration(std::integral_constant<int, 0>{});
-      while (tj[0] >= 0 && !hs_map_f16(tv[0]));
+      if (hs_map_f16(tv[0])) {
+        do iteration(std::integral_constant<int, 1>{});
+        while (tj[0] >= 0 && hs_map_f16(tv[0]));
+      } else {
+        do iteration(std::integral_constant<int, 0>{});
+        while (tj[0] >= 0 && !hs_map_f16(tv[0]));
+      }
     }
+  }
+  };
+  if constexpr (F16) {
+    main_loop(std::integral_constant<bool, MID_OK>{}, std::true_type{});
+  } else if constexpr (MID_OK) {
+    // bf16 cache: are all V tiles this workgroup can meet in fp16 encoding?  (every wave scans the
+    // same entries, so the workgroup agrees; the answer is scalar)
+    bool all16 = true;
+    for (int base = 0; base <= jmax_wg; base += 64) {
+      const int t = base + l;
+      const int32_t m = t <= jmax_wg ? vm[t] : 0;
+      all16 = all16 && !__any(m != 0 && !hs_map_f16(m));
+    }
+    if (all16) main_loop(std::true_type{}, std::true_type{});
+    else main_loop(std::false_type{}, std::false_type{});
+  } else {
+    main_loop(std::false_type{}, std::false_type{});
   }
 
   // ---------------- epilogue: O = O^T / l, LSE ----------------
