@@ -289,245 +289,245 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   };
   // mid_tag: MID mode; only16_tag: every V tile ahead is known to be in fp16 encoding
   auto main_loop = [&](auto mid_tag, auto only16_tag) {
-  constexpr bool MID = decltype(mid_tag)::value, ONLY16 = F16 || decltype(only16_tag)::value;
-  // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
-  // already holds the registers (both together spill; measured no gain there)
-  constexpr bool V_EARLY = F16 && VM == 0 && !MID;
-  if (MID && valid && tj[0] >= 0) k_fetch(0);
-  // One iteration = one tile.  The loop exists twice, for runs of V tiles in fp16 encoding (one fp16
-  // term of P) and in bf16 (two terms), so that each copy is straight-line code around its matrix
-  // instructions and keeps the accumulators where they are (a per-tile branch around GEMM2 made
-  // the compiler move all 64 accumulator registers in and out of the branch).  The encoding is
-  // scalar: map entries come through v_readlane.
-  auto iteration = [&](auto enc) {  // enc: 0 = bf16 V tile, 1 = fp16-encoded, 2 = look at the tile (mixed dense / 2:4 V)
-    constexpr int kEnc = decltype(enc)::value;
-    const int j = tj[0], mk = tk[0], mv = tv[0];
-    // END mode: request the tile D ahead now; its stage held the tile of the previous iteration,
-    // which every wave has left behind (barrier at the end of that iteration)
-    if (!MID) request();
-    const bool ok = valid && j <= jmax_w;
-    const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
-    const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
-    const bool v_f16 = kEnc == 2 ? (F16 || hs_map_f16(mv)) : kEnc == 1;
-    const uint4* kl = reinterpret_cast<const uint4*>(lds + st * kStage);
-    const uint4* vl = reinterpret_cast<const uint4*>(lds + st * kStage + region_bytes<KM>());
-    B16 ph[NB], pl[NB];
-    if (ok) {
-      // ---------------- GEMM1: S^T[64 tokens x 16 NB queries] ----------------
-      __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
-      f32x4_t s[4][NB];
+    constexpr bool MID = decltype(mid_tag)::value, ONLY16 = F16 || decltype(only16_tag)::value;
+    // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
+    // already holds the registers (both together spill; measured no gain there)
+    constexpr bool V_EARLY = F16 && VM == 0 && !MID;
+    if (MID && valid && tj[0] >= 0) k_fetch(0);
+    // One iteration = one tile.  The loop exists twice, for runs of V tiles in fp16 encoding (one fp16
+    // term of P) and in bf16 (two terms), so that each copy is straight-line code around its matrix
+    // instructions and keeps the accumulators where they are (a per-tile branch around GEMM2 made
+    // the compiler move all 64 accumulator registers in and out of the branch).  The encoding is
+    // scalar: map entries come through v_readlane.
+    auto iteration = [&](auto enc) {  // enc: 0 = bf16 V tile, 1 = fp16-encoded, 2 = look at the tile (mixed dense / 2:4 V)
+      constexpr int kEnc = decltype(enc)::value;
+      const int j = tj[0], mk = tk[0], mv = tv[0];
+      // END mode: request the tile D ahead now; its stage held the tile of the previous iteration,
+      // which every wave has left behind (barrier at the end of that iteration)
+      if (!MID) request();
+      const bool ok = valid && j <= jmax_w;
+      const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
+      const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
+      const bool v_f16 = kEnc == 2 ? (F16 || hs_map_f16(mv)) : kEnc == 1;
+      const uint4* kl = reinterpret_cast<const uint4*>(lds + st * kStage);
+      const uint4* vl = reinterpret_cast<const uint4*>(lds + st * kStage + region_bytes<KM>());
+      B16 ph[NB], pl[NB];
+      if (ok) {
+        // ---------------- GEMM1: S^T[64 tokens x 16 NB queries] ----------------
+        __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
+        f32x4_t s[4][NB];
 #pragma unroll
-      for (int m = 0; m < 4; m++)
+        for (int m = 0; m < 4; m++)
 #pragma unroll
-        for (int nb = 0; nb < NB; nb++) s[m][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      if (k_sparse) {
-        if (!MID) k_fetch(st);
-        const int kidx[4] = {(int)kix.x, (int)kix.y, (int)kix.z, (int)kix.w};
-        // 4 NB independent accumulators between the two instructions that share one
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-          for (int m = 0; m < 4; m++)
-            s[m][nb] = E::template smma<0>(ak[2 * m], qb[nb][0].q[0], qb[nb][0].q[1], s[m][nb], kidx[m]);
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-          for (int m = 0; m < 4; m++)
-            s[m][nb] = E::template smma<1>(ak[2 * m + 1], qb[nb][1].q[0], qb[nb][1].q[1], s[m][nb], kidx[m]);
-      } else {
-#pragma unroll
-        for (int m = 0; m < 4; m++) {
-          uint4 ak[4];
-#pragma unroll
-          for (int st = 0; st < 4; st++) ak[st] = kl[(4 * m + st) * 64 + l];
-#pragma unroll
-          for (int st = 0; st < 4; st++)
-#pragma unroll
-            for (int nb = 0; nb < NB; nb++)
-              s[m][nb] = E::mma(ak[st], qb[nb][st >> 1].q[st & 1], s[m][nb]);
-        }
-      }
-      if (V_EARLY) {  // V operands: on their way while the softmax runs
-#pragma unroll
-        for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
-        vix = vl[512 + l];
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
-      // causal mask inside a tile that reaches past the slab's first query
-      if (causal && HS_BT * j + HS_BT - 1 > qpos + off) {
-        const int lim = qpos + off - HS_BT * j + c;  // query 16nb+c sees in-tile tokens <= lim + 16nb
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-          for (int m = 0; m < 4; m++)
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-              if (16 * m + 4 * a + i > lim + 16 * nb) s[m][nb][i] = -INFINITY;
-      }
-      // ---------------- P = exp2(S*scale - m_run), reference m_run updated lazily ----------------
-      // P is first computed against the current reference of each query column, with no look at
-      // the tile's maximum.  Only if a partial row sum comes out huge (or the column has no
-      // reference yet) is the exact running maximum taken, O and l rescaled, and P recomputed.
-      // With a stale reference P merely holds larger numbers (harmless in fp32 / bf16); the final
-      // O / l and LSE = m_run + log2(l) do not depend on which reference was used.
-      // P goes through the matrix unit as two bf16 terms (hi + remainder): a single bf16 P alone
-      // costs ~1.3e-3 mean relative error on the output, on top of the bf16 rounding of O itself.
-      float psum[NB];
-      auto softmax_as = [&](auto enc) {  // enc: std::true_type = fp16 numerators, one term
-        constexpr bool kF16 = decltype(enc)::value;
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++) {
-          float acc = 0.f;
-          const float mref = m_run[nb] > -INFINITY ? m_run[nb] : 0.f;
-#pragma unroll
-          for (int m = 0; m < 4; m++) {
-            float p[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-              p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
-              acc += p[i];
-            }
-            if (kF16) {
-              ph[nb].u[2 * m] = E16::pack2(p[0], p[1]);
-              ph[nb].u[2 * m + 1] = E16::pack2(p[2], p[3]);
-            } else {
-              split_hi_lo(p[0], p[1], sc, ph[nb].u[2 * m], pl[nb].u[2 * m]);
-              split_hi_lo(p[2], p[3], sc, ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
-            }
-          }
-          psum[nb] = acc;
-        }
-      };
-      auto softmax_tile = [&]() {
-        if (kEnc == 2 ? v_f16 : kEnc == 1) softmax_as(std::true_type{});
-        else softmax_as(std::false_type{});
-      };
-      softmax_tile();
-      bool redo = false;
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) redo = redo || !(psum[nb] <= kRedo) || !(m_run[nb] > -INFINITY);
-      if (__any(redo)) {
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++) {
-          float mx = s[0][nb][0];
-#pragma unroll
-          for (int m = 0; m < 4; m++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][nb][i]);
-          mx = mx * scale_log2 - kShift;
-          mx = fmaxf(mx, __shfl_xor(mx, 16));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
-          // a column with nothing visible in this tile keeps its reference
-          const float m_new = fmaxf(m_run[nb], mx);
-          const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run[nb] - m_new) : 1.0f;
-          m_run[nb] = m_new;
-          l_run[nb] *= alpha;
-#pragma unroll
-          for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
-        }
-        softmax_tile();
-      }
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) l_run[nb] += psum[nb];
-    }
-    if (MID) {
-      // The next tile must have landed in full (own loads, then everybody's: barrier) before its K
-      // operands are fetched; tiles requested after it may still be in flight.  The stage of the
-      // previous tile is free from here on (all of its reads precede this barrier).
-      int later = 0;
-#pragma unroll
-      for (int i = 2; i < D; i++) later += tj[i] >= 0;
-      stage_wait<min_loads_per_tile<KM, VM>()>(later);
-      __syncthreads();
-      request();
-      if (valid && tj[1] >= 0) {
-        k_fetch(st + 1 == NS ? 0 : st + 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    if (ok) {
-      __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
-      if (v_sparse) {
-        if (!V_EARLY) {
-#pragma unroll
-          for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
-          vix = vl[512 + l];
-        }
-        const int vidx[4] = {(int)vix.x, (int)vix.y, (int)vix.z, (int)vix.w};
-        if (v_f16) {  // one fp16 term
+          for (int nb = 0; nb < NB; nb++) s[m][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (k_sparse) {
+          if (!MID) k_fetch(st);
+          const int kidx[4] = {(int)kix.x, (int)kix.y, (int)kix.z, (int)kix.w};
+          // 4 NB independent accumulators between the two instructions that share one
 #pragma unroll
           for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-            for (int mb = 0; mb < 8; mb++) {
-              if (mb & 1)
-                o[mb][nb] = E16::template smma<1>(av[mb], ph[nb].q[0], ph[nb].q[1], o[mb][nb], vidx[mb >> 1]);
-              else
-                o[mb][nb] = E16::template smma<0>(av[mb], ph[nb].q[0], ph[nb].q[1], o[mb][nb], vidx[mb >> 1]);
-            }
+            for (int m = 0; m < 4; m++)
+              s[m][nb] = E::template smma<0>(ak[2 * m], qb[nb][0].q[0], qb[nb][0].q[1], s[m][nb], kidx[m]);
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+            for (int m = 0; m < 4; m++)
+              s[m][nb] = E::template smma<1>(ak[2 * m + 1], qb[nb][1].q[0], qb[nb][1].q[1], s[m][nb], kidx[m]);
         } else {
 #pragma unroll
-          for (int t2 = 0; t2 < 2; t2++)  // first the upper-half term of every block, then the remainder
+          for (int m = 0; m < 4; m++) {
+            uint4 ak[4];
+#pragma unroll
+            for (int st = 0; st < 4; st++) ak[st] = kl[(4 * m + st) * 64 + l];
+#pragma unroll
+            for (int st = 0; st < 4; st++)
+#pragma unroll
+              for (int nb = 0; nb < NB; nb++)
+                s[m][nb] = E::mma(ak[st], qb[nb][st >> 1].q[st & 1], s[m][nb]);
+          }
+        }
+        if (V_EARLY) {  // V operands: on their way while the softmax runs
+#pragma unroll
+          for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
+          vix = vl[512 + l];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
+        // causal mask inside a tile that reaches past the slab's first query
+        if (causal && HS_BT * j + HS_BT - 1 > qpos + off) {
+          const int lim = qpos + off - HS_BT * j + c;  // query 16nb+c sees in-tile tokens <= lim + 16nb
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+            for (int m = 0; m < 4; m++)
+#pragma unroll
+              for (int i = 0; i < 4; i++)
+                if (16 * m + 4 * a + i > lim + 16 * nb) s[m][nb][i] = -INFINITY;
+        }
+        // ---------------- P = exp2(S*scale - m_run), reference m_run updated lazily ----------------
+        // P is first computed against the current reference of each query column, with no look at
+        // the tile's maximum.  Only if a partial row sum comes out huge (or the column has no
+        // reference yet) is the exact running maximum taken, O and l rescaled, and P recomputed.
+        // With a stale reference P merely holds larger numbers (harmless in fp32 / bf16); the final
+        // O / l and LSE = m_run + log2(l) do not depend on which reference was used.
+        // P goes through the matrix unit as two bf16 terms (hi + remainder): a single bf16 P alone
+        // costs ~1.3e-3 mean relative error on the output, on top of the bf16 rounding of O itself.
+        float psum[NB];
+        auto softmax_as = [&](auto enc) {  // enc: std::true_type = fp16 numerators, one term
+          constexpr bool kF16 = decltype(enc)::value;
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++) {
+            float acc = 0.f;
+            const float mref = m_run[nb] > -INFINITY ? m_run[nb] : 0.f;
+#pragma unroll
+            for (int m = 0; m < 4; m++) {
+              float p[4];
+#pragma unroll
+              for (int i = 0; i < 4; i++) {
+                p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[m][nb][i], scale_log2, -mref));
+                acc += p[i];
+              }
+              if (kF16) {
+                ph[nb].u[2 * m] = E16::pack2(p[0], p[1]);
+                ph[nb].u[2 * m + 1] = E16::pack2(p[2], p[3]);
+              } else {
+                split_hi_lo(p[0], p[1], sc, ph[nb].u[2 * m], pl[nb].u[2 * m]);
+                split_hi_lo(p[2], p[3], sc, ph[nb].u[2 * m + 1], pl[nb].u[2 * m + 1]);
+              }
+            }
+            psum[nb] = acc;
+          }
+        };
+        auto softmax_tile = [&]() {
+          if (kEnc == 2 ? v_f16 : kEnc == 1) softmax_as(std::true_type{});
+          else softmax_as(std::false_type{});
+        };
+        softmax_tile();
+        bool redo = false;
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) redo = redo || !(psum[nb] <= kRedo) || !(m_run[nb] > -INFINITY);
+        if (__any(redo)) {
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++) {
+            float mx = s[0][nb][0];
+#pragma unroll
+            for (int m = 0; m < 4; m++)
+#pragma unroll
+              for (int i = 0; i < 4; i++) mx = fmaxf(mx, s[m][nb][i]);
+            mx = mx * scale_log2 - kShift;
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // a column with nothing visible in this tile keeps its reference
+            const float m_new = fmaxf(m_run[nb], mx);
+            const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run[nb] - m_new) : 1.0f;
+            m_run[nb] = m_new;
+            l_run[nb] *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < 8; mb++) o[mb][nb] *= alpha;
+          }
+          softmax_tile();
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) l_run[nb] += psum[nb];
+      }
+      if (MID) {
+        // The next tile must have landed in full (own loads, then everybody's: barrier) before its K
+        // operands are fetched; tiles requested after it may still be in flight.  The stage of the
+        // previous tile is free from here on (all of its reads precede this barrier).
+        int later = 0;
+#pragma unroll
+        for (int i = 2; i < D; i++) later += tj[i] >= 0;
+        stage_wait<min_loads_per_tile<KM, VM>()>(later);
+        __syncthreads();
+        request();
+        if (valid && tj[1] >= 0) {
+          k_fetch(st + 1 == NS ? 0 : st + 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      if (ok) {
+        __builtin_amdgcn_s_setprio(HS_PRIO_MFMA);
+        if (v_sparse) {
+          if (!V_EARLY) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) av[i] = vl[i * 64 + l];
+            vix = vl[512 + l];
+          }
+          const int vidx[4] = {(int)vix.x, (int)vix.y, (int)vix.z, (int)vix.w};
+          if (v_f16) {  // one fp16 term
 #pragma unroll
             for (int nb = 0; nb < NB; nb++)
 #pragma unroll
               for (int mb = 0; mb < 8; mb++) {
-                const B16& bp = t2 == 0 ? ph[nb] : pl[nb];
                 if (mb & 1)
-                  o[mb][nb] = E::template smma<1>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                  o[mb][nb] = E16::template smma<1>(av[mb], ph[nb].q[0], ph[nb].q[1], o[mb][nb], vidx[mb >> 1]);
                 else
-                  o[mb][nb] = E::template smma<0>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                  o[mb][nb] = E16::template smma<0>(av[mb], ph[nb].q[0], ph[nb].q[1], o[mb][nb], vidx[mb >> 1]);
               }
-        }
-      } else {
-#pragma unroll
-        for (int mb = 0; mb < 8; mb++) {
-          const uint4 a0 = vl[(2 * mb) * 64 + l], a1 = vl[(2 * mb + 1) * 64 + l];
-          if (v_f16) {
-#pragma unroll
-            for (int h = 0; h < 2; h++)
-#pragma unroll
-              for (int nb = 0; nb < NB; nb++) o[mb][nb] = E16::mma(h == 0 ? a0 : a1, ph[nb].q[h], o[mb][nb]);
           } else {
 #pragma unroll
-            for (int t2 = 0; t2 < 2; t2++)
+            for (int t2 = 0; t2 < 2; t2++)  // first the upper-half term of every block, then the remainder
+#pragma unroll
+              for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+                for (int mb = 0; mb < 8; mb++) {
+                  const B16& bp = t2 == 0 ? ph[nb] : pl[nb];
+                  if (mb & 1)
+                    o[mb][nb] = E::template smma<1>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                  else
+                    o[mb][nb] = E::template smma<0>(av[mb], bp.q[0], bp.q[1], o[mb][nb], vidx[mb >> 1]);
+                }
+          }
+        } else {
+#pragma unroll
+          for (int mb = 0; mb < 8; mb++) {
+            const uint4 a0 = vl[(2 * mb) * 64 + l], a1 = vl[(2 * mb + 1) * 64 + l];
+            if (v_f16) {
 #pragma unroll
               for (int h = 0; h < 2; h++)
 #pragma unroll
-                for (int nb = 0; nb < NB; nb++)
-                  o[mb][nb] = E::mma(h == 0 ? a0 : a1, t2 == 0 ? ph[nb].q[h] : pl[nb].q[h], o[mb][nb]);
+                for (int nb = 0; nb < NB; nb++) o[mb][nb] = E16::mma(h == 0 ? a0 : a1, ph[nb].q[h], o[mb][nb]);
+            } else {
+#pragma unroll
+              for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+                for (int h = 0; h < 2; h++)
+#pragma unroll
+                  for (int nb = 0; nb < NB; nb++)
+                    o[mb][nb] = E::mma(h == 0 ? a0 : a1, t2 == 0 ? ph[nb].q[h] : pl[nb].q[h], o[mb][nb]);
+            }
           }
         }
       }
-    }
-    __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
-    if (!MID) {
-      // the next tile must have landed; the ones requested after it may still be in flight
-      int later = 0;
+      __builtin_amdgcn_s_setprio(HS_PRIO_VALU);
+      if (!MID) {
+        // the next tile must have landed; the ones requested after it may still be in flight
+        int later = 0;
 #pragma unroll
-      for (int i = 2; i <= D; i++) later += tj[i] >= 0;
-      stage_wait<min_loads_per_tile<KM, VM>()>(later);
-      __syncthreads();
-    }
+        for (int i = 2; i <= D; i++) later += tj[i] >= 0;
+        stage_wait<min_loads_per_tile<KM, VM>()>(later);
+        __syncthreads();
+      }
 #pragma unroll
-    for (int i = 0; i < D; i++) { tj[i] = tj[i + 1]; tk[i] = tk[i + 1]; tv[i] = tv[i + 1]; }
-    st = st + 1 == NS ? 0 : st + 1;
-      };
-  while (tj[0] >= 0) {
-    if constexpr (ONLY16) {
-      iteration(std::integral_constant<int, 1>{});
-    } else if constexpr (VM == 2) {  // four GEMM2 forms in one kernel: no second copy of the loop
-      iteration(std::integral_constant<int, 2>{});
-    } else {
-      if (hs_map_f16(tv[0])) {
-        do iteration(std::integral_constant<int, 1>{});
-        while (tj[0] >= 0 && hs_map_f16(tv[0]));
+      for (int i = 0; i < D; i++) { tj[i] = tj[i + 1]; tk[i] = tk[i + 1]; tv[i] = tv[i + 1]; }
+      st = st + 1 == NS ? 0 : st + 1;
+    };
+    while (tj[0] >= 0) {
+      if constexpr (ONLY16) {
+        iteration(std::integral_constant<int, 1>{});
+      } else if constexpr (VM == 2) {  // four GEMM2 forms in one kernel: no second copy of the loop
+        iteration(std::integral_constant<int, 2>{});
       } else {
-        do iteration(std::integral_constant<int, 0>{});
-        while (tj[0] >= 0 && !hs_map_f16(tv[0]));
+        if (hs_map_f16(tv[0])) {
+          do iteration(std::integral_constant<int, 1>{});
+          while (tj[0] >= 0 && hs_map_f16(tv[0]));
+        } else {
+          do iteration(std::integral_constant<int, 0>{});
+          while (tj[0] >= 0 && !hs_map_f16(tv[0]));
+        }
       }
     }
-  }
   };
   if constexpr (F16) {
     main_loop(std::integral_constant<bool, MID_OK>{}, std::true_type{});
