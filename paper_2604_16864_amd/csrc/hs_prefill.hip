@@ -171,12 +171,11 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   constexpr int NS = n_stages<KM, VM>(), D = NS - 1;  // ring size, prefetch distance in tiles
   // MID: the per-tile barrier sits between softmax and GEMM2 instead of at the end of the
   // iteration, so that the next tile's K operands can be fetched from LDS while GEMM2 runs.  Needs
-  // the next tile requested at least two iterations ahead (NS >= 3), which all-2:4 keys give.
+  // the next tile requested at least two iterations ahead (NS >= 3: at least one tensor all 2:4).
   // It is used where every V tile the workgroup meets takes one fp16 term of P (fp16 caches; rows
   // of a bf16 cache whose V tiles are all in fp16 encoding): with both GEMM2 forms in the loop,
   // or mixed V, no registers are left for the K prefetch.
-  constexpr bool MID_OK = KM == 0 && VM != 2;
-  static_assert(!MID_OK || NS >= 3, "mid-iteration barrier needs a ring of 3");
+  constexpr bool MID_OK = KM != 2 && VM != 2 && NS >= 3;
   constexpr int kStage = stage_bytes<KM, VM>();
   __shared__ __attribute__((aligned(16))) uint8_t lds[NS * kStage];
   const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
@@ -274,8 +273,8 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   auto k_fetch = [&](int stage) {
     const uint4* kl = reinterpret_cast<const uint4*>(lds + stage * kStage);
 #pragma unroll
-    for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];
-    kix = kl[512 + l];
+    for (int i = 0; i < 8; i++) ak[i] = kl[i * 64 + l];  // a 2:4 tile in full; the first two row blocks of a dense one
+    if (KM != 1) kix = kl[512 + l];
   };
   auto request = [&]() {  // look up the tile D ahead and start its copy into the stage D ahead
     tj[D] = tj[D - 1] >= 0 ? next_visible(tj[D - 1]) : -1;
@@ -337,14 +336,14 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         } else {
 #pragma unroll
           for (int m = 0; m < 4; m++) {
-            uint4 ak[4];
+            uint4 a4[4];
 #pragma unroll
-            for (int st = 0; st < 4; st++) ak[st] = kl[(4 * m + st) * 64 + l];
+            for (int st = 0; st < 4; st++) a4[st] = MID && m < 2 ? ak[4 * m + st] : kl[(4 * m + st) * 64 + l];
 #pragma unroll
             for (int st = 0; st < 4; st++)
 #pragma unroll
               for (int nb = 0; nb < NB; nb++)
-                s[m][nb] = E::mma(ak[st], qb[nb][st >> 1].q[st & 1], s[m][nb]);
+                s[m][nb] = E::mma(a4[st], qb[nb][st >> 1].q[st & 1], s[m][nb]);
           }
         }
         if (V_EARLY) {  // V operands: on their way while the softmax runs
