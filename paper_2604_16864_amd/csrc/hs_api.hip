@@ -95,7 +95,7 @@ int check_kv(const hs_shape* s, const hs_kv* kv) {
   return HS_OK;
 }
 
-constexpr int kSelectMaxTiles = 65536;  // O(T^2) ranking: 4M tokens per row
+constexpr int kSelectMaxTiles = 65536;  // one workgroup per row walks its tiles: 4M tokens per row
 
 // shared body of the decode entry points; tail_len < 0: no dense tail
 int decode_common(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
@@ -278,8 +278,10 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
     } else {
       if (workspace == nullptr || ((uintptr_t)workspace & 7u)) return HS_EINVAL;
       if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
+      // energies rank the skipped tiles; losses split the kept ones unless they all end up alike
+      const int what = (c[0] > 0 ? 1 : 0) | ((c[2] != 0 && c[2] != n_keep) || (c[4] != 0 && c[4] != n_keep) ? 2 : 0);
       e = hs_launch_score((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv, T,
-                          policy->element_rule, shape->dtype, (double*)workspace, s);
+                          policy->element_rule, shape->dtype, what, (double*)workspace, s);
       if (e != hipSuccess) return hip_fail(e);
       e = hs_launch_select((const double*)workspace, rows, T, c[0], c[2], c[4], n_first, n_last, out->k_map,
                            out->v_map, s);

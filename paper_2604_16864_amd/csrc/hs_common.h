@@ -130,8 +130,9 @@ __host__ __device__ static inline int hs_v_group(int a, int q) {
 }
 
 // launchers implemented in the kernel translation units; all return a hipError_t
+// what: 1 = tile energies only, 2 = pruning losses only, 3 = both (the other planes are zero)
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                           int B, int Hkv, int T, int rule, int dtype, double* scores, hipStream_t st);
+                           int B, int Hkv, int T, int rule, int dtype, int what, double* scores, hipStream_t st);
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
                             int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st);
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,

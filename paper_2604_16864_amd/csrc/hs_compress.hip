@@ -55,51 +55,82 @@ __device__ __forceinline__ void stage_v_tile(const uint16_t* vt, int64_t tok_str
 
 // ----------------------------------------------------------------------------------
 // Tile scores: energy = sum K^2 + sum V^2 (skip ranking), loss_x = L1 norm of what the
-// 2:4 mask removes (Eq. 2c).  fp64, fixed reduction order.  scores = [3][rows][T].
+// 2:4 mask removes (Eq. 2c).  fp64 (every term exact), fixed reduction order.
+// scores = [3][rows][T].  WHAT: bit 0 = the policy ranks by energy, bit 1 = by the losses; a
+// plane that is not asked for is written as zeros (the selection then falls back to tile order
+// there, which is all it needs when a count is 0 or everything).
 // ----------------------------------------------------------------------------------
+template <bool F16> __device__ __forceinline__ double sum_sq8(uint4 d) {  // sum of squares of 8 elements
+  const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+  double e = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const double f0 = elem_val<F16>(w[i] & 0xffffu), f1 = elem_val<F16>(w[i] >> 16);
+    e += f0 * f0 + f1 * f1;
+  }
+  return e;
+}
+
+// sum of the magnitudes of the two elements of a group that the 2:4 mask drops
 template <bool F16>
+__device__ __forceinline__ double dropped_l1(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3, int rule) {
+  const uint32_t drop = ~top2_mask(x0, x1, x2, x3, rule) & 15u;
+  uint32_t pair, nib;
+  top2_emit(drop, x0, x1, x2, x3, pair, nib);
+  return fabs(elem_val<F16>(pair & 0xffffu)) + fabs(elem_val<F16>(pair >> 16));
+}
+
+template <bool F16, int WHAT>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                     int64_t sb, int64_t sh, int64_t st, int Hkv, int T, int rule,
                                                     double* __restrict__ scores) {
-  __shared__ uint16_t vl[HS_BT * kVStride];
+  constexpr bool ENERGY = (WHAT & 1) != 0, LOSS = (WHAT & 2) != 0;
+  __shared__ uint16_t vl[LOSS ? HS_BT * kVStride : 8];
   __shared__ double red[3][4];
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
   const uint16_t* kt = K + b * sb + h * sh + (int64_t)t * HS_BT * st;
   const uint16_t* vt = V + b * sb + h * sh + (int64_t)t * HS_BT * st;
-  stage_v_tile(vt, st, vl);
   double e = 0.0, lk = 0.0, lv = 0.0;
-  {  // K: this thread owns token 16w+r, channels 64kb+16a .. +15
-    const uint16_t* row = kt + (int64_t)(16 * w + r) * st;
+  if (!LOSS) {
+    // energy alone does not care which thread sees which element: coalesced 16-byte reads
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-      const uint4 d0 = *reinterpret_cast<const uint4*>(row + 64 * kb + 16 * a);
-      const uint4 d1 = *reinterpret_cast<const uint4*>(row + 64 * kb + 16 * a + 8);
-      const uint32_t wds[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+    for (int i = 0; i < 4; i++) {
+      const int q = tid + 256 * i, tok = q >> 4, c8 = q & 15;
+      e += sum_sq8<F16>(*reinterpret_cast<const uint4*>(kt + tok * st + 8 * c8));
+      e += sum_sq8<F16>(*reinterpret_cast<const uint4*>(vt + tok * st + 8 * c8));
+    }
+  } else {
+    stage_v_tile(vt, st, vl);
+    {  // K: this thread owns token 16w+r, channels 64kb+16a .. +15
+      const uint16_t* row = kt + (int64_t)(16 * w + r) * st;
 #pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const uint32_t x0 = wds[2 * q] & 0xffffu, x1 = wds[2 * q] >> 16, x2 = wds[2 * q + 1] & 0xffffu, x3 = wds[2 * q + 1] >> 16;
-        const uint32_t m = top2_mask(x0, x1, x2, x3, rule);
-        const double f0 = elem_val<F16>(x0), f1 = elem_val<F16>(x1), f2 = elem_val<F16>(x2), f3 = elem_val<F16>(x3);
-        e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
-        lk += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
+      for (int kb = 0; kb < 2; kb++) {
+        const uint4 d0 = *reinterpret_cast<const uint4*>(row + 64 * kb + 16 * a);
+        const uint4 d1 = *reinterpret_cast<const uint4*>(row + 64 * kb + 16 * a + 8);
+        if (ENERGY) e += sum_sq8<F16>(d0) + sum_sq8<F16>(d1);
+        const uint32_t wds[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+          lk += dropped_l1<F16>(wds[2 * q] & 0xffffu, wds[2 * q] >> 16, wds[2 * q + 1] & 0xffffu, wds[2 * q + 1] >> 16, rule);
       }
     }
-  }
-  __syncthreads();
-  {  // V: channel 16mb+r for mb = 2w, 2w+1; token groups of lane group a
+    __syncthreads();
+    {  // V: channel 16mb+r for mb = 2w, 2w+1; token groups of lane group a
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      const int c = 16 * (2 * w + j) + r;
+      for (int j = 0; j < 2; j++) {
+        const int c = 16 * (2 * w + j) + r;
 #pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int g = hs_v_group(a, q);
-        const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
-        const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
-        const uint32_t m = top2_mask(x0, x1, x2, x3, rule);
-        const double f0 = elem_val<F16>(x0), f1 = elem_val<F16>(x1), f2 = elem_val<F16>(x2), f3 = elem_val<F16>(x3);
-        e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
-        lv += ((m & 1u) ? 0.0 : fabs(f0)) + ((m & 2u) ? 0.0 : fabs(f1)) + ((m & 4u) ? 0.0 : fabs(f2)) + ((m & 8u) ? 0.0 : fabs(f3));
+        for (int q = 0; q < 4; q++) {
+          const int g = hs_v_group(a, q);
+          const uint32_t x0 = vl[(4 * g + 0) * kVStride + c], x1 = vl[(4 * g + 1) * kVStride + c];
+          const uint32_t x2 = vl[(4 * g + 2) * kVStride + c], x3 = vl[(4 * g + 3) * kVStride + c];
+          if (ENERGY) {
+            const double f0 = elem_val<F16>(x0), f1 = elem_val<F16>(x1), f2 = elem_val<F16>(x2), f3 = elem_val<F16>(x3);
+            e += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
+          }
+          lv += dropped_l1<F16>(x0, x1, x2, x3, rule);
+        }
       }
     }
   }
@@ -107,8 +138,10 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     e += __shfl_xor(e, off);
-    lk += __shfl_xor(lk, off);
-    lv += __shfl_xor(lv, off);
+    if (LOSS) {
+      lk += __shfl_xor(lk, off);
+      lv += __shfl_xor(lv, off);
+    }
   }
   if (l == 0) { red[0][w] = e; red[1][w] = lk; red[2][w] = lv; }
   __syncthreads();
@@ -120,97 +153,167 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 }
 
 // ----------------------------------------------------------------------------------
-// Tile selection per (b, kv head) row (Eq. 2d + the skip extension) and slot assignment
-// (the two sequential counters of Sec. III-B, done as an exclusive prefix count).
-// Ranks are found by counting: rank(t) = #{u : (score_u, u) < (score_t, t)}.  One thread per
-// tile; the row's scores pass through LDS in chunks, so the O(T^2) compares read LDS only.
-// Three launches because each phase needs the previous one's result for the whole row.
+// Tile selection per (b, kv head) row (Eq. 2d + the skip extension) and slot assignment (the two
+// sequential counters of Sec. III-B, done as an exclusive prefix count), one workgroup per row.
+// "The n tiles with the lowest (score, tile index)" is found by radix selection instead of by
+// ranking every tile: scores are non-negative doubles, whose bit patterns order like unsigned
+// integers; eight rounds of a 256-bin histogram over one byte each, from the top, pin down the
+// key of the n-th smallest eligible tile (thr) and how many tiles with exactly that key belong
+// to the set (take, by ascending tile index; see mark_lowest).  Every thread owns a contiguous run of tiles, so
+// "ascending tile index" is thread order, and a thread only re-reads map entries it wrote itself.
 // ----------------------------------------------------------------------------------
-constexpr int kRankChunk = 2048;
+struct SelectShared {
+  int hist[256];
+  int wsum[4];
+  int bin, want;
+};
 
-// phase 1: km[t] = 1 if tile t is kept, 0 if it is among the n_skip lowest-energy tiles
+__device__ __forceinline__ int block_exclusive_scan(int v, int* wsum, int tid) {  // 256 threads; contains barriers
+  const int l = tid & 63, w = tid >> 6;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int n = __shfl_up(incl, off);
+    if (l >= off) incl += n;
+  }
+  __syncthreads();  // wsum may still be read from the previous call
+  if (l == 63) wsum[w] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int i = 0; i < w; i++) base += wsum[i];
+  return base + incl - v;
+}
+
+// The keys of this thread's tiles [t0, t1) that take part (eligible), held in registers when the
+// run is short (kCache tiles: rows up to 2048 tiles), else re-read from memory on every pass.
+constexpr int kCache = 8;
+struct TileKeys {
+  const double* keys;
+  int t0, t1;
+  bool cached;
+  unsigned long long k[kCache];
+  unsigned elig;  // bit i: tile t0 + i takes part (cached form)
+};
+
+template <class Eligible>
+__device__ __forceinline__ TileKeys load_keys(const double* __restrict__ keys, int t0, int t1, int per, Eligible eligible) {
+  TileKeys tk;
+  tk.keys = keys; tk.t0 = t0; tk.t1 = t1; tk.cached = per <= kCache; tk.elig = 0;
+#pragma unroll
+  for (int i = 0; i < kCache; i++) {
+    const int t = t0 + i;
+    const bool e = tk.cached && t < t1 && eligible(t);
+    tk.k[i] = e ? (unsigned long long)__double_as_longlong(keys[t]) : 0ull;
+    tk.elig |= (unsigned)e << i;
+  }
+  return tk;
+}
+
+// f(t, key) for every eligible tile of the thread, ascending t
+template <class Eligible, class F>
+__device__ __forceinline__ void for_each_key(const TileKeys& tk, Eligible eligible, F f) {
+  if (tk.cached) {
+#pragma unroll
+    for (int i = 0; i < kCache; i++)
+      if ((tk.elig >> i) & 1u) f(tk.t0 + i, tk.k[i]);
+  } else {
+    for (int t = tk.t0; t < tk.t1; t++)
+      if (eligible(t)) f(t, (unsigned long long)__double_as_longlong(tk.keys[t]));
+  }
+}
+
+// Marks the n eligible tiles with the lowest (key, tile index): key < thr, or key == thr and among
+// the first `take` such tiles.  `per` = tiles per thread (uniform).
+template <class Eligible, class Mark>
+__device__ __forceinline__ void mark_lowest(const double* __restrict__ keys, int t0, int t1, int per, Eligible eligible,
+                                            int n, SelectShared& sm, int tid, Mark mark) {
+  if (n <= 0) return;  // uniform: nobody is in the set
+  const TileKeys tk = load_keys(keys, t0, t1, per, eligible);
+  unsigned long long prefix = 0;
+  int want = n;
+  for (int d = 7; d >= 0; d--) {
+    sm.hist[tid] = 0;
+    __syncthreads();
+    for_each_key(tk, eligible, [&](int, unsigned long long k) {
+      if (d == 7 || (k >> (8 * (d + 1))) == (prefix >> (8 * (d + 1)))) atomicAdd(&sm.hist[(k >> (8 * d)) & 255], 1);
+    });
+    __syncthreads();
+    const int h = sm.hist[tid];
+    const int excl = block_exclusive_scan(h, sm.wsum, tid);
+    if (excl < want && want <= excl + h) { sm.bin = tid; sm.want = want - excl; }
+    __syncthreads();
+    prefix |= (unsigned long long)sm.bin << (8 * d);
+    want = sm.want;
+  }
+  const unsigned long long thr = prefix;
+  const int take = want;
+  int ties = 0;
+  for_each_key(tk, eligible, [&](int, unsigned long long k) { ties += k == thr; });
+  int tie_rank = block_exclusive_scan(ties, sm.wsum, tid);
+  for_each_key(tk, eligible, [&](int t, unsigned long long k) {
+    if (k < thr || (k == thr && tie_rank++ < take)) mark(t);
+  });
+}
+
 // Tiles t < n_first or t >= T - n_last are protected: always kept dense, outside both rankings.
-__global__ __launch_bounds__(256) void rank_skip_kernel(const double* __restrict__ scores, int T, int n_skip,
-                                                        int n_first, int n_last, int32_t* km_all) {
-  __shared__ double se[kRankChunk];
-  const int row = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
-  const double* en = scores + (int64_t)row * T;  // plane 0 = energy
-  const double e = t < T ? en[t] : 0.0;
-  int rank = 0;
-  for (int c0 = 0; c0 < T; c0 += kRankChunk) {
-    const int n = min(kRankChunk, T - c0);
-    __syncthreads();
-    for (int i = threadIdx.x; i < n; i += 256) se[i] = en[c0 + i];
-    __syncthreads();
-    for (int i = 0; i < n; i++) {
-      const int u = c0 + i;
-      if (u < n_first || u >= T - n_last) continue;
-      const double eu = se[i];
-      rank += (eu < e) || (eu == e && u < t);
-    }
-  }
-  if (t < T) km_all[(int64_t)row * T + t] = (t < n_first || t >= T - n_last) ? 2 : (rank >= n_skip);  // 2 = protected
-}
-
-// phase 2: vm[t] = state_k | state_v << 8: among kept tiles the n_sparse_x with the lowest
-// pruning loss are 2:4, the others dense
-__global__ __launch_bounds__(256) void rank_state_kernel(const double* __restrict__ scores, int rows, int T,
-                                                         int n_sparse_k, int n_sparse_v, const int32_t* km_all,
-                                                         int32_t* vm_all) {  // km: 0 skipped, 1 kept, 2 protected
-  __shared__ double sk_[kRankChunk], sv_[kRankChunk];
-  __shared__ int skept[kRankChunk];
-  const int row = blockIdx.y, t = blockIdx.x * 256 + threadIdx.x;
-  const double* lk = scores + ((int64_t)1 * rows + row) * T;
-  const double* lv = scores + ((int64_t)2 * rows + row) * T;
-  const int32_t* km = km_all + (int64_t)row * T;
-  const double a = t < T ? lk[t] : 0.0, c = t < T ? lv[t] : 0.0;
-  int rk = 0, rv = 0;
-  for (int c0 = 0; c0 < T; c0 += kRankChunk) {
-    const int n = min(kRankChunk, T - c0);
-    __syncthreads();
-    for (int i = threadIdx.x; i < n; i += 256) { sk_[i] = lk[c0 + i]; sv_[i] = lv[c0 + i]; skept[i] = km[c0 + i]; }
-    __syncthreads();
-    for (int i = 0; i < n; i++) {
-      if (skept[i] != 1) continue;
-      const double au = sk_[i], cu = sv_[i];
-      rk += (au < a) || (au == a && c0 + i < t);
-      rv += (cu < c) || (cu == c && c0 + i < t);
-    }
-  }
-  if (t < T) {
-    int st = 0;
-    if (km[t] == 1) st = (rk < n_sparse_k ? HS_SPARSE24 : HS_DENSE) | ((rv < n_sparse_v ? HS_SPARSE24 : HS_DENSE) << 8);
-    if (km[t] == 2) st = HS_DENSE | (HS_DENSE << 8);
-    vm_all[(int64_t)row * T + t] = st;
-  }
-}
-
-// phase 3: slots in ascending tile order; one workgroup per row, each thread owns a contiguous chunk
-__global__ __launch_bounds__(256) void slots_kernel(int T, int32_t* k_map, int32_t* v_map) {
-  __shared__ int part[4][256];
+// Tile states live in registers while the selection runs (2 bits per tile) when a thread's run is
+// short, else in the map arrays themselves; the maps are written once, at the end.
+__global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ scores, int rows, int T, int n_skip,
+                                                     int n_sparse_k, int n_sparse_v, int n_first, int n_last,
+                                                     int32_t* __restrict__ k_map, int32_t* __restrict__ v_map) {
+  __shared__ SelectShared sm;
   const int row = blockIdx.x, tid = threadIdx.x;
+  const double* en = scores + (int64_t)row * T;                // plane 0 = energy
+  const double* lk = scores + ((int64_t)1 * rows + row) * T;   // planes 1, 2 = pruning losses
+  const double* lv = scores + ((int64_t)2 * rows + row) * T;
   int32_t* km = k_map + (int64_t)row * T;
   int32_t* vm = v_map + (int64_t)row * T;
   const int per = (T + 255) / 256;
   const int t0 = min(tid * per, T), t1 = min(t0 + per, T);
-  int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
-  for (int t = t0; t < t1; t++) {
-    const int s = vm[t], sk = s & 0xff, sv = s >> 8;
-    ndk += sk == HS_DENSE; nsk += sk == HS_SPARSE24; ndv += sv == HS_DENSE; nsv += sv == HS_SPARSE24;
+  const bool in_regs = per <= kCache;
+  unsigned rk = 0x5555u, rv = 0x5555u;  // HS_DENSE everywhere
+  static_assert(HS_DENSE == 1 && 2 * kCache <= 32, "packed tile states");
+  auto state_k = [&](int t) -> int { return in_regs ? (rk >> (2 * (t - t0))) & 3u : km[t]; };
+  auto state_v = [&](int t) -> int { return in_regs ? (rv >> (2 * (t - t0))) & 3u : vm[t]; };
+  auto set_k = [&](int t, int v) {
+    if (in_regs) rk = (rk & ~(3u << (2 * (t - t0)))) | ((unsigned)v << (2 * (t - t0)));
+    else km[t] = v;
+  };
+  auto set_v = [&](int t, int v) {
+    if (in_regs) rv = (rv & ~(3u << (2 * (t - t0)))) | ((unsigned)v << (2 * (t - t0)));
+    else vm[t] = v;
+  };
+  auto is_protected = [&](int t) { return t < n_first || t >= T - n_last; };
+  if (!in_regs)
+    for (int t = t0; t < t1; t++) km[t] = vm[t] = HS_DENSE;
+  // the n_skip lowest-energy tiles are skipped
+  mark_lowest(en, t0, t1, per, [&](int t) { return !is_protected(t); }, n_skip, sm, tid,
+              [&](int t) { set_k(t, HS_SKIP); set_v(t, HS_SKIP); });
+  // of the kept ones, the n_sparse_x with the lowest pruning loss are 2:4 (all of them: no ranking)
+  auto kept = [&](int t) { return !is_protected(t) && state_k(t) != HS_SKIP; };
+  const int n_keep = T - n_first - n_last - n_skip;
+  if (n_sparse_k >= n_keep) {
+    for (int t = t0; t < t1; t++) if (kept(t)) set_k(t, HS_SPARSE24);
+  } else {
+    mark_lowest(lk, t0, t1, per, kept, n_sparse_k, sm, tid, [&](int t) { set_k(t, HS_SPARSE24); });
   }
-  // exclusive scan of the four counters over threads (4 threads walk the 256 partials)
-  part[0][tid] = ndk; part[1][tid] = nsk; part[2][tid] = ndv; part[3][tid] = nsv;
-  __syncthreads();
-  if (tid < 4) {
-    int acc = 0;
-    for (int i = 0; i < 256; i++) { const int v = part[tid][i]; part[tid][i] = acc; acc += v; }
+  if (n_sparse_v >= n_keep) {
+    for (int t = t0; t < t1; t++) if (kept(t)) set_v(t, HS_SPARSE24);
+  } else {
+    mark_lowest(lv, t0, t1, per, kept, n_sparse_v, sm, tid, [&](int t) { set_v(t, HS_SPARSE24); });
   }
-  __syncthreads();
-  ndk = part[0][tid]; nsk = part[1][tid]; ndv = part[2][tid]; nsv = part[3][tid];
+  // slots in ascending tile order
+  int n[4] = {0, 0, 0, 0};  // dense K, 2:4 K, dense V, 2:4 V
   for (int t = t0; t < t1; t++) {
-    const int s = vm[t], sk = s & 0xff, sv = s >> 8;
-    km[t] = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
-    vm[t] = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
+    const int sk = state_k(t), sv = state_v(t);
+    n[0] += sk == HS_DENSE; n[1] += sk == HS_SPARSE24; n[2] += sv == HS_DENSE; n[3] += sv == HS_SPARSE24;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; i++) n[i] = block_exclusive_scan(n[i], sm.wsum, tid);
+  for (int t = t0; t < t1; t++) {
+    const int sk = state_k(t), sv = state_v(t);
+    km[t] = sk == HS_DENSE ? ++n[0] : (sk == HS_SPARSE24 ? -(++n[1]) : 0);
+    vm[t] = sv == HS_DENSE ? ++n[2] : (sv == HS_SPARSE24 ? -(++n[3]) : 0);
   }
 }
 
@@ -661,20 +764,23 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
 }  // namespace
 
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                           int T, int rule, int dtype, double* scores, hipStream_t st) {
-  if (dtype == HS_FP16)
-    hipLaunchKernelGGL(score_kernel<true>, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);
-  else
-    hipLaunchKernelGGL(score_kernel<false>, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);
+                           int T, int rule, int dtype, int what, double* scores, hipStream_t st) {
+  const dim3 grid(T, Hkv, B), block(256);
+#define HS_SCORE(F16_, WHAT_) \
+  hipLaunchKernelGGL((score_kernel<F16_, WHAT_>), grid, block, 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores)
+  if (dtype == HS_FP16) {
+    if (what == 1) HS_SCORE(true, 1); else if (what == 2) HS_SCORE(true, 2); else HS_SCORE(true, 3);
+  } else {
+    if (what == 1) HS_SCORE(false, 1); else if (what == 2) HS_SCORE(false, 2); else HS_SCORE(false, 3);
+  }
+#undef HS_SCORE
   return hipGetLastError();
 }
 
 hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, int n_sparse_k, int n_sparse_v,
                             int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st) {
-  const dim3 grid((T + 255) / 256, rows);
-  hipLaunchKernelGGL(rank_skip_kernel, grid, dim3(256), 0, st, scores, T, n_skip, n_first, n_last, k_map);
-  hipLaunchKernelGGL(rank_state_kernel, grid, dim3(256), 0, st, scores, rows, T, n_sparse_k, n_sparse_v, k_map, v_map);
-  hipLaunchKernelGGL(slots_kernel, dim3(rows), dim3(256), 0, st, T, k_map, v_map);
+  hipLaunchKernelGGL(select_kernel, dim3(rows), dim3(256), 0, st, scores, rows, T, n_skip, n_sparse_k, n_sparse_v, n_first,
+                     n_last, k_map, v_map);
   return hipGetLastError();
 }
 

@@ -403,6 +403,28 @@ def test_decode_cfg3_full_batch_sampled_rows(pol):
         assert_lse_close(LSE[b:b + 1, G * h:G * (h + 1)].cpu().numpy(), Lr, "decode cfg3 full batch lse")
 
 
+def test_selection_on_a_row_longer_than_the_register_cache():
+    """Tile selection with more than 8 tiles per thread (rows over 2048 tiles take the path that re-reads
+    the scores instead of holding them in registers): maps against the oracle, with planted equal tiles
+    so that ties on the cut are broken by tile index."""
+    B, Hq, Hkv, T = 1, 1, 1, 2304
+    L = 64 * T
+    rng = np.random.default_rng(240)
+    K = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, L, 128)).astype(np.float32))
+    V = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, L, 128)).astype(np.float32))
+    for t in (7, 900, 2200):                                 # the three quietest tiles are identical
+        K[0, 0, 64 * t:64 * t + 64] = K[0, 0, 64 * 7:64 * 7 + 64] & 0x8000 | 0x3000
+        V[0, 0, 64 * t:64 * t + 64] = V[0, 0, 64 * 7:64 * 7 + 64] & 0x8000 | 0x3000
+    pol = dict(skip_frac=2 / (T - 4) + 1e-9, sparse_frac_k=0.5, sparse_frac_v=0.7, dense_first_tiles=1, dense_last_tiles=3)
+    sh, kv, pk, pv, info = compress_both(B, Hq, Hkv, L, K, V, **pol)
+    assert int((pk.map == 0).sum()) == 2 and pk.map[0, 0, 7] == 0 and pk.map[0, 0, 900] == 0 and pk.map[0, 0, 2200] != 0
+    assert (kv.k_map.cpu().numpy() == pk.map).all() and (kv.v_map.cpu().numpy() == pv.map).all()
+    Ku, Vu = hb.unpack_kv(sh, kv)
+    torch.cuda.synchronize()
+    assert (hb.bf16_tensor_to_bits(Ku) == orc.unpack_tensor(pk)).all()
+    assert (hb.bf16_tensor_to_bits(Vu) == orc.unpack_tensor(pv)).all()
+
+
 def test_prefill_cfg4_full_size_skip75_sampled_rows():
     """Long causal prefill at the highest hierarchical sparsity (L = 65536, 75 % of the tiles
     skipped, 2:4 in the rest): seeded sampled rows plus rows that see no token at all."""
