@@ -221,6 +221,16 @@ HS_API int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int c
                     const void* Q, const hs_kv* kv, void* O, float* LSE,
                     void* workspace, void* stream);
 
+/* The same with the queries anywhere in the cache: query i stands at token position q_start + i
+ * (0 <= q_start <= L - Lq, any value) and, when causal, sees token j iff tile(j) is not skipped
+ * and j <= q_start + i.  hs_prefill_attn is the case q_start = L - Lq.  For caches allocated
+ * for a capacity (shape->L) beyond the tokens held so far -- the tiles not filled yet are SKIP --
+ * and for chunked prefill (Sec. V-B runs 32K-token chunks), where each chunk's queries sit at the
+ * end of what has been compressed so far, not at the end of the capacity. */
+HS_API int hs_prefill_attn_at(const hs_shape* shape, int32_t Lq, int32_t q_start, float scale, int causal,
+                       const void* Q, const hs_kv* kv, void* O, float* LSE,
+                       void* workspace, void* stream);
+
 /* Decode attention (split-KV kernel + merge, Sec. IV-C): one query token per
  * (b, query head) against all L cached tokens.  Q, O: bf16 [B, Hq, D];
  * LSE: fp32 [B, Hq] or NULL.  n_splits == 0 picks hs_decode_auto_splits.

@@ -53,6 +53,8 @@ EXPORTS = {
                                    C.c_void_p, C.c_void_p]),
     "hs_prefill_attn": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_float, C.c_int, C.c_void_p, C.POINTER(HsKV),
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_prefill_attn_at": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_int32, C.c_float, C.c_int, C.c_void_p,
+                                     C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_append_tile": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
@@ -254,16 +256,21 @@ def unpack_kv(shape, kv):
     return K, V
 
 
-def prefill_attn(shape, Q, kv, causal=True, scale=0.0, want_lse=True, out=None, lse=None):
-    """Q: bf16 [B, Hq, Lq, D] contiguous.  Returns (O bf16 [B, Hq, Lq, D], LSE fp32 [B, Hq, Lq] or None)."""
+def prefill_attn(shape, Q, kv, causal=True, scale=0.0, want_lse=True, out=None, lse=None, q_start=None):
+    """Q: bf16 [B, Hq, Lq, D] contiguous.  Returns (O bf16 [B, Hq, Lq, D], LSE fp32 [B, Hq, Lq] or None).
+    q_start: position in the cache of the first query (default: the queries are the last Lq tokens)."""
     assert Q.dtype == torch_dtype(shape) and Q.is_contiguous() and Q.is_cuda
     Lq = Q.shape[2]
     O = torch.empty_like(Q) if out is None else out
     if lse is None and want_lse:
         lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
     kvs = kv.struct()
-    _check(lib().hs_prefill_attn(C.byref(shape), Lq, float(scale), int(bool(causal)), _ptr(Q), C.byref(kvs), _ptr(O),
-                                 _ptr(lse), None, _stream()))
+    if q_start is None:
+        _check(lib().hs_prefill_attn(C.byref(shape), Lq, float(scale), int(bool(causal)), _ptr(Q), C.byref(kvs), _ptr(O),
+                                     _ptr(lse), None, _stream()))
+    else:
+        _check(lib().hs_prefill_attn_at(C.byref(shape), Lq, int(q_start), float(scale), int(bool(causal)), _ptr(Q),
+                                        C.byref(kvs), _ptr(O), _ptr(lse), None, _stream()))
     return O, lse
 
 

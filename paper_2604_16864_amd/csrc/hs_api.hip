@@ -386,6 +386,12 @@ int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, void* V_ou
 
 int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal, const void* Q, const hs_kv* kv,
                     void* O, float* LSE, void* workspace, void* stream) {
+  if (shape == nullptr) return HS_EINVAL;
+  return hs_prefill_attn_at(shape, Lq, shape->L - Lq, scale, causal, Q, kv, O, LSE, workspace, stream);
+}
+
+int hs_prefill_attn_at(const hs_shape* shape, int32_t Lq, int32_t q_start, float scale, int causal, const void* Q,
+                       const hs_kv* kv, void* O, float* LSE, void* workspace, void* stream) {
   (void)workspace;
   int rc = check_shape(shape);
   if (rc != HS_OK) return rc;
@@ -393,10 +399,11 @@ int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal, 
   if (rc != HS_OK) return rc;
   if (Q == nullptr || O == nullptr || (((uintptr_t)Q | (uintptr_t)O) & 15u)) return HS_EINVAL;
   if (Lq <= 0 || Lq > shape->L) return HS_EINVAL;
+  if (q_start < 0 || q_start > shape->L - Lq) return HS_EINVAL;
   if (Lq % HS_BT != 0) return HS_EUNSUPPORTED;
   if (!(scale >= 0.f)) return HS_EINVAL;
   if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
-  const hipError_t e = hs_launch_prefill(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, Lq / HS_BT, scale,
+  const hipError_t e = hs_launch_prefill(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, Lq / HS_BT, q_start, scale,
                                          causal != 0, (const uint16_t*)Q, hs_make_kv_dev(kv), (uint16_t*)O, LSE,
                                          (hipStream_t)stream, shape->dtype);
   if (e != hipSuccess) return hip_fail(e);

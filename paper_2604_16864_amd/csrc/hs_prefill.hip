@@ -569,27 +569,27 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
 }  // namespace
 
 template <int KM, int VM, int NB>
-static hipError_t launch_prefill(int B, int Hq, int Hkv, int T, int Lq, float sl2, int causal, const uint16_t* Q,
+static hipError_t launch_prefill(int B, int Hq, int Hkv, int T, int Lq, int q_start, float sl2, int causal, const uint16_t* Q,
                                  const hs_kv_dev& kv, uint16_t* O, float* LSE, hipStream_t st, bool f16) {
   const int G = Hq / Hkv;
   const int n_groups = ((Lq / (16 * NB)) * G + 3) / 4;
   if (f16)
     hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, true>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
-                       T * HS_BT - Lq, sl2, causal, Q, kv, O, LSE);
+                       q_start, sl2, causal, Q, kv, O, LSE);
   else
     hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, false>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
-                       T * HS_BT - Lq, sl2, causal, Q, kv, O, LSE);
+                       q_start, sl2, causal, Q, kv, O, LSE);
   return hipGetLastError();
 }
 
-hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, float scale, int causal, const uint16_t* Q,
+hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, int q_start, float scale, int causal, const uint16_t* Q,
                              hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st, int dtype) {
   const bool f16 = dtype == HS_FP16;
   const float sl2 = scale * kLog2e;
   const int Lq = Tq * HS_BT;
   const int km = kv.cap_dense_k == 0 ? 0 : (kv.cap_sparse_k == 0 ? 1 : 2);
   const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
-#define HS_GO(KM_, VM_) return launch_prefill<KM_, VM_, 2>(B, Hq, Hkv, T, Lq, sl2, causal, Q, kv, O, LSE, st, f16)
+#define HS_GO(KM_, VM_) return launch_prefill<KM_, VM_, 2>(B, Hq, Hkv, T, Lq, q_start, sl2, causal, Q, kv, O, LSE, st, f16)
   switch (km * 3 + vm) {
     case 0: HS_GO(0, 0);
     case 1: HS_GO(0, 1);

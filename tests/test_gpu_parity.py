@@ -325,6 +325,30 @@ def test_prefill_chunk_lq_less_than_l():
     assert_lse_close(LSE, Lr, "prefill Lq<L lse")
 
 
+@pytest.mark.parametrize("q_start,Lq", [(0, 64 * 7), (64 * 5, 64 * 2), (64 * 3 + 17, 64 * 2), (64 * 12 - 64, 64)])
+def test_prefill_queries_placed_inside_a_capacity_cache(q_start, Lq):
+    """A cache allocated for 12 tiles that holds 7 so far (the rest SKIP): queries stand where the caller
+    says (chunked prefill, growing caches), not at the end of the capacity.  Positions that are not a
+    multiple of the tile, and queries beyond the filled part (they see everything filled), included."""
+    B, Hq, Hkv, T_cap, T_now = 2, 8, 2, 12, 7
+    L = 64 * T_cap
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, Lq, seed=250, k_outliers=True)
+    sk, sv = _mixed_states(B, Hkv, T_cap, seed=251, p_skip=0.1)
+    sk[:, :, T_now:], sv[:, :, T_now:] = 0, 0
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, state_k=sk, state_v=sv)
+    O, LSE = hb.prefill_attn(sh, _dev(Q), kv, q_start=q_start)
+    torch.cuda.synchronize()
+    rows = [(b, h, i) for b in range(B) for h in range(Hq) for i in range(Lq)]
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True, q_offset=q_start)
+    idx = tuple(np.array(rows).T)
+    assert_close(_f32(O)[idx], Or, f"prefill at {q_start}")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, f"prefill at {q_start} lse")
+    if q_start == 0:
+        for bad in (-1, L - Lq + 1):
+            with pytest.raises(hb.HsError):
+                hb.prefill_attn(sh, _dev(Q), kv, q_start=bad)
+
+
 def test_decode_equals_last_prefill_row():
     B, Hq, Hkv, L = 1, 8, 2, 64 * 6
     Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=120)
