@@ -187,6 +187,38 @@ def extra_legs(hb, torch, Q, K, V, qd, sh, args):
     res["prefill_64k"] = pf
     del K4, V4, Q4, O4, ws4
     torch.cuda.empty_cache()
+    # (3b) chunked prefill as in the paper's end-to-end runs (Sec. V-B: 32K-token chunks): a cache allocated
+    # for 128K tokens; per chunk one append (compress the chunk's K, V into the next pool slots) and one
+    # causal attention call with the chunk's queries at their position
+    Lc, chunk = 131072, 32768
+    shc = hb.make_shape(1, Hq, Hkv, Lc)
+    Tc, nct = Lc // 64, chunk // 64
+    Kc = torch.randn((1, Hkv, Lc, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Vc = torch.randn((1, Hkv, Lc, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Qc = torch.randn((1, Hq, chunk, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Oc = torch.empty_like(Qc)
+    flops_c = 4.0 * 128 * Hq * (Lc * (Lc + 1) / 2.0)
+    cp = []
+    for name_c, stk, stv in (("dense", hb.DENSE, hb.DENSE), ("sk0_sv1", hb.DENSE, hb.SPARSE24), ("2:4", hb.SPARSE24, hb.SPARSE24)):
+        kvc = hb.PackedKV(shc, [0, Tc if stk == hb.DENSE else 0, Tc if stk == hb.SPARSE24 else 0,
+                                Tc if stv == hb.DENSE else 0, Tc if stv == hb.SPARSE24 else 0])
+        kvc.uniform = 0
+
+        def run_chunks(_):
+            kvc.k_map.zero_()
+            kvc.v_map.zero_()
+            for c in range(Lc // chunk):
+                hb.append_tile(shc, kvc, nct * c, Kc[:, :, chunk * c:chunk * (c + 1)], Vc[:, :, chunk * c:chunk * (c + 1)],
+                               state_k=stk, state_v=stv)
+                hb.prefill_attn(shc, Qc, kvc, causal=True, want_lse=False, out=Oc, q_start=chunk * c)
+        t = _time(torch, run_chunks, 2)
+        cp.append({"case": name_c, "total_ms": t * 1e3, "dense_equiv_TFLOPs_of_full_causal": flops_c / t / 1e12})
+        del kvc
+    for r in cp:
+        r["speedup_vs_dense"] = cp[0]["total_ms"] / r["total_ms"]
+    res["chunked_prefill_128k_in_32k_chunks"] = cp
+    del Kc, Vc, Qc, Oc
+    torch.cuda.empty_cache()
     # (4) the shape of the paper's own kernel benchmarks (Sec. V-B: batch 8, 32K tokens), 32/8 heads: context only
     B5, L5 = 8, 32768
     sh5 = hb.make_shape(B5, Hq, Hkv, L5)

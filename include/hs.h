@@ -187,6 +187,14 @@ HS_API int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, 
                    int32_t element_rule, const void* K_tile, const void* V_tile,
                    const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
 
+/* The same for n_tiles consecutive tiles tile .. tile + n_tiles - 1 in one call (a prefill chunk,
+ * Sec. V-B: 32K-token chunks): K_tile, V_tile are [B, Hkv, 64 n_tiles, D]; all of them take
+ * state_k / state_v and consecutive slots.  Tiles that no longer fit a pool stay SKIP (overflow
+ * as above).  1 <= n_tiles <= 65535, tile + n_tiles <= L / 64. */
+HS_API int hs_append_tiles(const hs_shape* shape, int32_t tile, int32_t n_tiles, int32_t state_k, int32_t state_v,
+                    int32_t element_rule, const void* K_tile, const void* V_tile,
+                    const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
+
 /* Prune a packed cache further (Sec. III, overview of the workflow: after the prefill phase the
  * dense pool can be pruned and compressed again, so that decode runs at another sparsity than
  * prefill; Sec. V evaluates prefill at S_K = 0, S_V = 1 followed by decode at S_K = S_V = 1).

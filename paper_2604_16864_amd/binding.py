@@ -48,6 +48,8 @@ EXPORTS = {
     "hs_decode_auto_splits": (C.c_int, [C.POINTER(HsShape)]),
     "hs_compress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
+    "hs_append_tiles": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                  C.c_void_p, C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
     "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_recompress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(HsKV), C.POINTER(HsKV), C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
@@ -212,14 +214,19 @@ def compress_kv(shape, policy, K, V, out=None, workspace=None):
 
 def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARSE24, element_rule=RULE_MAGNITUDE,
                 overflow=None):
-    """K_tile, V_tile: bf16 device tensors [B, Hkv, 64, D] (last dim contiguous); fills tile `tile` of kv.
-    overflow: optional int32 device tensor (1 element) raised when a row's pool is full."""
+    """K_tile, V_tile: bf16 device tensors [B, Hkv, 64 n, D] (last dim contiguous); fills tiles tile .. tile + n - 1
+    of kv.  overflow: optional int32 device tensor (1 element) raised when a row's pool is full."""
     assert K_tile.dtype == torch_dtype(shape) and V_tile.dtype == K_tile.dtype and K_tile.stride() == V_tile.stride()
-    assert K_tile.stride(-1) == 1 and tuple(K_tile.shape) == (shape.B, shape.Hkv, TILE, shape.D)
+    n = K_tile.shape[2] // TILE
+    assert K_tile.stride(-1) == 1 and tuple(K_tile.shape) == (shape.B, shape.Hkv, TILE * n, shape.D) and n >= 1
     strides = (C.c_int64 * 3)(K_tile.stride(0), K_tile.stride(1), K_tile.stride(2))
     kvs = kv.struct()
-    _check(lib().hs_append_tile(C.byref(shape), int(tile), int(state_k), int(state_v), int(element_rule), _ptr(K_tile),
-                                _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
+    if n == 1:
+        _check(lib().hs_append_tile(C.byref(shape), int(tile), int(state_k), int(state_v), int(element_rule), _ptr(K_tile),
+                                    _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
+    else:
+        _check(lib().hs_append_tiles(C.byref(shape), int(tile), n, int(state_k), int(state_v), int(element_rule),
+                                     _ptr(K_tile), _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
 
 
 def recompress_kv(shape, kv, target, counts=None, overflow=None, out=None, workspace=None):

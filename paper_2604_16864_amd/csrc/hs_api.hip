@@ -297,25 +297,32 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
 int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, int32_t state_v, int32_t element_rule,
                    const void* K_tile, const void* V_tile, const int64_t tile_strides[3], const hs_kv* kv,
                    int32_t* overflow, void* stream) {
+  return hs_append_tiles(shape, tile, 1, state_k, state_v, element_rule, K_tile, V_tile, tile_strides, kv, overflow,
+                         stream);
+}
+
+int hs_append_tiles(const hs_shape* shape, int32_t tile, int32_t n_tiles, int32_t state_k, int32_t state_v,
+                    int32_t element_rule, const void* K_tile, const void* V_tile, const int64_t tile_strides[3],
+                    const hs_kv* kv, int32_t* overflow, void* stream) {
   int rc = check_shape(shape);
   if (rc != HS_OK) return rc;
   rc = check_kv(shape, kv);
   if (rc != HS_OK) return rc;
   const int T = shape->L / HS_BT;
-  if (tile < 0 || tile >= T || kv->uniform) return HS_EINVAL;
+  if (tile < 0 || n_tiles < 1 || n_tiles > 65535 || tile > T - n_tiles || kv->uniform) return HS_EINVAL;
   if ((state_k != HS_DENSE && state_k != HS_SPARSE24) || (state_v != HS_DENSE && state_v != HS_SPARSE24)) return HS_EINVAL;
   if (element_rule != HS_RULE_MAGNITUDE && element_rule != HS_RULE_NONZERO) return HS_EINVAL;
   if (K_tile == nullptr || V_tile == nullptr || (((uintptr_t)K_tile | (uintptr_t)V_tile) & 15u)) return HS_EINVAL;
   // a pool this call may write to has to exist
   if ((state_k == HS_DENSE ? kv->cap_dense_k : kv->cap_sparse_k) < 1) return HS_EINVAL;
   if ((state_v == HS_DENSE ? kv->cap_dense_v : kv->cap_sparse_v) < 1) return HS_EINVAL;
-  int64_t sb = (int64_t)shape->Hkv * HS_BT * HS_D, sh = (int64_t)HS_BT * HS_D, st = HS_D;
+  int64_t sb = (int64_t)shape->Hkv * n_tiles * HS_BT * HS_D, sh = (int64_t)n_tiles * HS_BT * HS_D, st = HS_D;
   if (tile_strides != nullptr) {
     sb = tile_strides[0]; sh = tile_strides[1]; st = tile_strides[2];
     if (st < HS_D || sh < 0 || sb < 0 || ((sb | sh | st) & 7)) return HS_EINVAL;
   }
   const hipError_t e = hs_launch_append((const uint16_t*)K_tile, (const uint16_t*)V_tile, sb, sh, st, shape->B,
-                                        shape->Hkv, T, tile, state_k, state_v, hs_make_kv_dev(kv), element_rule,
+                                        shape->Hkv, T, tile, n_tiles, state_k, state_v, hs_make_kv_dev(kv), element_rule,
                                         shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;

@@ -137,9 +137,9 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
                             int n_first, int n_last, int32_t* k_map, int32_t* v_map, hipStream_t st);
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
                           int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, int v_f16, hipStream_t st);
-// one tile [B, Hkv, 64, D] into tile index `tile` of a cache of T tiles per row
+// n_tiles tiles [B, Hkv, 64 n_tiles, D] into tile indices tile .. of a cache of T tiles per row
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                            int B, int Hkv, int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule,
+                            int B, int Hkv, int T, int tile, int n_tiles, int state_k, int state_v, hs_kv_dev kv, int rule,
                             int v_f16, int32_t* overflow, hipStream_t st);
 // packed cache -> packed cache, each tile in the sparser of its state and its target (device int8 [rows, T])
 hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,

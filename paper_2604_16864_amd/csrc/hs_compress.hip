@@ -317,18 +317,19 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
   }
 }
 
-// Appending (Sec. III-B counters): map entries of tile `tile` of every row = next slot of the
-// pool its state names = how many tiles of that kind the row holds; a full pool leaves the
-// tile skipped and raises *overflow.  One workgroup per row.
-__global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int state_k, int state_v, hs_kv_dev kv,
-                                                           int32_t* overflow) {
+// Appending (Sec. III-B counters): map entries of tiles [tile, tile + n_tiles) of every row = the
+// next slots of the pool their state names, counted from how many tiles of that kind the row
+// holds; tiles for which a pool has no slot left stay skipped and raise *overflow.  One workgroup
+// per row.
+__global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int n_tiles, int state_k, int state_v,
+                                                           hs_kv_dev kv, int32_t* overflow) {
   __shared__ int part[4][4];
   const int row = blockIdx.x, tid = threadIdx.x;
   int32_t* km = const_cast<int32_t*>(kv.k_map) + (int64_t)row * T;
   int32_t* vm = const_cast<int32_t*>(kv.v_map) + (int64_t)row * T;
   int n[4] = {0, 0, 0, 0};  // dense K, 2:4 K, dense V, 2:4 V
   for (int t = tid; t < T; t += 256) {
-    if (t == tile) continue;
+    if (t >= tile && t < tile + n_tiles) continue;
     const int a = km[t], c = vm[t];
     n[0] += a > 0; n[1] += a < 0; n[2] += c > 0; n[3] += c < 0;
   }
@@ -339,14 +340,16 @@ __global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int 
     if ((tid & 63) == 0) part[i][tid >> 6] = n[i];
   }
   __syncthreads();
-  if (tid == 0) {
-    int c[4];
+  int c[4];
 #pragma unroll
-    for (int i = 0; i < 4; i++) c[i] = part[i][0] + part[i][1] + part[i][2] + part[i][3];
-    const bool fits = (state_k == HS_DENSE ? c[0] < kv.cap_dense_k : c[1] < kv.cap_sparse_k) &&
-                      (state_v == HS_DENSE ? c[2] < kv.cap_dense_v : c[3] < kv.cap_sparse_v);
-    km[tile] = !fits ? 0 : (state_k == HS_DENSE ? c[0] + 1 : -(c[1] + 1));
-    vm[tile] = !fits ? 0 : (state_v == HS_DENSE ? c[2] + 1 : -(c[3] + 1));
+  for (int i = 0; i < 4; i++) c[i] = part[i][0] + part[i][1] + part[i][2] + part[i][3];
+  const int ck = state_k == HS_DENSE ? c[0] : c[1], cv = state_v == HS_DENSE ? c[2] : c[3];
+  const int room_k = (state_k == HS_DENSE ? kv.cap_dense_k : kv.cap_sparse_k) - ck;
+  const int room_v = (state_v == HS_DENSE ? kv.cap_dense_v : kv.cap_sparse_v) - cv;
+  for (int i = tid; i < n_tiles; i += 256) {  // the i-th appended tile takes the i-th free slot of each pool
+    const bool fits = i < room_k && i < room_v;
+    km[tile + i] = !fits ? 0 : (state_k == HS_DENSE ? ck + i + 1 : -(ck + i + 1));
+    vm[tile + i] = !fits ? 0 : (state_v == HS_DENSE ? cv + i + 1 : -(cv + i + 1));
     if (!fits && overflow != nullptr) *overflow = 1;
   }
 }
@@ -791,12 +794,12 @@ hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int6
 }
 
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                            int T, int tile, int state_k, int state_v, hs_kv_dev kv, int rule, int v_f16,
+                            int T, int tile, int n_tiles, int state_k, int state_v, hs_kv_dev kv, int rule, int v_f16,
                             int32_t* overflow, hipStream_t st) {
-  hipLaunchKernelGGL(append_slots_kernel, dim3(B * Hkv), dim3(256), 0, st, T, tile, state_k, state_v, kv, overflow);
+  hipLaunchKernelGGL(append_slots_kernel, dim3(B * Hkv), dim3(256), 0, st, T, tile, n_tiles, state_k, state_v, kv, overflow);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(pack_kernel, dim3(1, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16);
+  hipLaunchKernelGGL(pack_kernel, dim3(n_tiles, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16);
   return hipGetLastError();
 }
 

@@ -561,6 +561,52 @@ def test_append_tiles_during_decode():
     assert hb.lib().hs_append_tile(C.byref(sh), 5, 2, 2, 7, *args) == -1          # unknown element rule
 
 
+def test_chunked_prefill_appends_a_chunk_then_attends_from_its_position():
+    """Chunked prefill (the paper's long-context runs use chunks): a cache allocated for the whole sequence
+    starts empty; each chunk of 3 tiles is appended in one call (keys dense, values 2:4) and its queries attend
+    from their position.  Outputs equal the oracle's causal attention over the one-shot cache; the final
+    pools equal one-shot compression; a pool that runs out mid-chunk keeps the tiles that fit."""
+    B, Hq, Hkv, T, n = 2, 8, 2, 12, 3
+    L = 64 * T
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=260, k_outliers=True)
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv = hb.PackedKV(sh, [0, T, 0, 0, T])
+    kv.uniform = 0
+    kv.k_map.zero_()
+    kv.v_map.zero_()
+    sk = np.full((B, Hkv, T), orc.DENSE, dtype=np.int8)
+    sv = np.full((B, Hkv, T), orc.SPARSE24, dtype=np.int8)
+    pk, pv, _ = orc.compress_kv(K, V, state_k=sk, state_v=sv)
+    Kd, Vd, Qd = _dev(K), _dev(V), _dev(Q)
+    ovf = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for c in range(T // n):
+        lo, hi = 64 * n * c, 64 * n * (c + 1)
+        hb.append_tile(sh, kv, n * c, Kd[:, :, lo:hi], Vd[:, :, lo:hi], state_k=hb.DENSE, state_v=hb.SPARSE24, overflow=ovf)
+        O, LSE = hb.prefill_attn(sh, Qd[:, :, lo:hi].contiguous(), kv, q_start=lo)
+        torch.cuda.synchronize()
+        rows = [(b, h, i) for b in range(B) for h in range(Hq) for i in range(lo, hi, 5)]
+        Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True, q_offset=0)
+        got = _f32(O)[:, :, ::5].reshape(-1, 128)
+        assert_close(got, Or, f"chunk {c}")
+        assert_lse_close(LSE.cpu().numpy()[:, :, ::5].reshape(-1), Lr, f"chunk {c} lse")
+    assert int(ovf.item()) == 0
+    check_packed_bit_exact(sh, kv, pk, pv)
+    small = hb.PackedKV(sh, [0, 4, 0, 0, 5])                # room for 4 dense K tiles and 5 2:4 V tiles
+    small.uniform = 0
+    small.k_map.zero_()
+    small.v_map.zero_()
+    hb.append_tile(sh, small, 2, Kd[:, :, :64 * 6], Vd[:, :, :64 * 6], state_k=hb.DENSE, state_v=hb.SPARSE24, overflow=ovf)
+    torch.cuda.synchronize()
+    assert int(ovf.item()) == 1
+    assert (small.k_map.cpu().numpy()[0, 0] == [0, 0, 1, 2, 3, 4, 0, 0, 0, 0, 0, 0]).all()
+    assert ((np.abs(small.v_map.cpu().numpy()[1, 1]) & ~orc.MAP_F16) == [0, 0, 1, 2, 3, 4, 0, 0, 0, 0, 0, 0]).all()
+    import ctypes as C
+    kvs = small.struct()
+    args = (hb._ptr(Kd), hb._ptr(Vd), None, C.byref(kvs), None, None)
+    assert hb.lib().hs_append_tiles(C.byref(sh), 10, 3, 1, 2, 0, *args) == -1      # runs past the capacity
+    assert hb.lib().hs_append_tiles(C.byref(sh), 0, 0, 1, 2, 0, *args) == -1
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shapes_and_policies(seed):
     """Seeded sweep over shapes (batch, heads, GQA group, tiles, query chunk) and policies (fractions with
