@@ -14,7 +14,7 @@
  *     IEEE fp16 (the paper's type), chosen by hs_shape.dtype for all four; "bf16" in the
  *     descriptions below stands for that type.  D (head dim) is contiguous.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
- *     the default stream).  The library allocates nothing, frees nothing and
+ *     the default stream), except where a call says that it synchronises.  The library allocates nothing, frees nothing and
  *     keeps no pointer after a call returns; the caller owns every buffer.
  *   - Return value: HS_OK (0) or a negative hs_status.  Arguments are checked
  *     on the host before anything is launched; nothing is launched when an
@@ -166,7 +166,10 @@ HS_API int hs_decode_auto_splits(const hs_shape* shape);
  * magnitudes of every 4 consecutive channels of a token, V of every 4
  * consecutive tokens of a channel (magnitude = bits & 0x7fff, ties to the lower
  * position; with HS_RULE_NONZERO the key is magnitude != 0 instead).  Writes maps and pools of `out`; slots beyond the used count are
- * left untouched.  workspace: hs_workspace_bytes(op 0). */
+ * left untouched.  workspace: hs_workspace_bytes(op 0).
+ * When the tile states are known on the host (explicit states; protected end tiles with every
+ * other tile in one state) the maps are built there, copied over, and the stream is synchronised
+ * once before the pack kernel is launched; every other policy runs without a synchronisation. */
 HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],
                    const hs_kv* out, void* workspace, void* stream);
