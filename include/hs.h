@@ -167,9 +167,9 @@ HS_API int hs_decode_auto_splits(const hs_shape* shape);
  * consecutive tokens of a channel (magnitude = bits & 0x7fff, ties to the lower
  * position; with HS_RULE_NONZERO the key is magnitude != 0 instead).  Writes maps and pools of `out`; slots beyond the used count are
  * left untouched.  workspace: hs_workspace_bytes(op 0).
- * When the tile states are known on the host (explicit states; protected end tiles with every
- * other tile in one state) the maps are built there, copied over, and the stream is synchronised
- * once before the pack kernel is launched; every other policy runs without a synchronisation. */
+ * With explicit states the maps are built on the host, copied over, and the stream is
+ * synchronised once before the pack kernel is launched; fraction policies run without a
+ * synchronisation. */
 HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],
                    const hs_kv* out, void* workspace, void* stream);

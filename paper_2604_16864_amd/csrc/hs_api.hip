@@ -266,15 +266,11 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
       uni_k = c[2] ? HS_SPARSE24 : HS_DENSE;
       uni_v = c[4] ? HS_SPARSE24 : HS_DENSE;
     } else if (c[0] == 0 && (c[2] == 0 || c[2] == n_keep) && (c[4] == 0 || c[4] == n_keep)) {
-      // no ranking needed either: protected end tiles dense, every tile in between in one state
-      std::vector<int8_t> sk(T), sv(T);
-      for (int t = 0; t < T; t++) {
-        const bool prot = t < n_first || t >= T - n_last;
-        sk[t] = prot || c[2] == 0 ? HS_DENSE : HS_SPARSE24;
-        sv[t] = prot || c[4] == 0 ? HS_DENSE : HS_SPARSE24;
-      }
-      rc = maps_from_states(sk.data(), sv.data(), 0);
-      if (rc != HS_OK) return rc;
+      // no ranking needed either: protected end tiles dense, every tile in between in one state;
+      // the selection kernel never looks at the scores then
+      if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
+      e = hs_launch_select(nullptr, rows, T, 0, c[2], c[4], n_first, n_last, out->k_map, out->v_map, s);
+      if (e != hipSuccess) return hip_fail(e);
     } else {
       if (workspace == nullptr || ((uintptr_t)workspace & 7u)) return HS_EINVAL;
       if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
