@@ -360,15 +360,21 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
     to the dense or the sparse pool in sequence order, one counter per pool).  The tile must be
     SKIP (not filled yet) in every row; it takes the next slot of its pool, i.e. the number of
     tiles of the same kind the row already holds.  K_tile_bits, V_tile_bits: [B, Hkv, Bt, D];
-    state_k, state_v: DENSE or SPARSE24, the same for every row.  Works in place."""
+    state_k, state_v: DENSE or SPARSE24, the same for every row.  Works in place.
+    tile: one index, or one per batch row (sequences of a batch differ in length; a negative
+    entry leaves that batch row as it is)."""
     K_tile_bits = np.asarray(K_tile_bits, dtype=np.uint16)
     V_tile_bits = np.asarray(V_tile_bits, dtype=np.uint16)
     B, H, Bt, D = K_tile_bits.shape
     assert Bt == pk.Bt and state_k in (DENSE, SPARSE24) and state_v in (DENSE, SPARSE24)
     masks = (element_mask_k(K_tile_bits, element_rule), element_mask_v(V_tile_bits, element_rule))
+    tiles = np.broadcast_to(np.asarray(tile, dtype=np.int64), (B,))
     for p, X, mask, state in ((pk, K_tile_bits, masks[0], state_k), (pv, V_tile_bits, masks[1], state_v)):
-        assert (p.map[:, :, tile] == 0).all()
         for b in range(B):
+            t_b = int(tiles[b])
+            if t_b < 0:
+                continue
+            assert (p.map[b, :, t_b] == 0).all()
             for h in range(H):
                 v_f16 = p.kind == "v" and p.dtype == "bf16"
                 if state == DENSE:
@@ -376,7 +382,7 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
                     if slot >= p.dense.shape[2]:
                         p.dense = np.concatenate([p.dense, np.zeros_like(p.dense[:, :, :1])], axis=2)
                     p.dense[b, h, slot], flag = _v_tile_store(X[b, h], v_f16)
-                    p.map[b, h, tile] = (slot + 1) | flag
+                    p.map[b, h, t_b] = (slot + 1) | flag
                 else:
                     slot = int((p.map[b, h] < 0).sum())
                     if slot >= p.nnz.shape[2]:
@@ -385,7 +391,7 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
                     pack = pack_k_tile if p.kind == "k" else pack_v_tile
                     vals, p.meta[b, h, slot] = pack(X[b, h], mask[b, h])
                     p.nnz[b, h, slot], flag = _v_tile_store(vals, v_f16)
-                    p.map[b, h, tile] = -((slot + 1) | flag)
+                    p.map[b, h, t_b] = -((slot + 1) | flag)
 
 
 def _sparser(cur, target):
@@ -556,11 +562,13 @@ def attention_decode(q_bits, pk, pv, scale=None, tail_k=None, tail_v=None, tail_
 
     tail_k, tail_v (bf16 bits [B, Hkv, >= tail_len, D]): recent tokens that are not in the
     packed cache yet; they are kept as they are (the local window stays dense, Sec. V-A)
-    and the query sees the first tail_len of them after the cache.
+    and the query sees the first tail_len of them after the cache.  tail_len: one number, or
+    one per batch row (sequences of a batch differ in length).
     """
     q_bits = np.asarray(q_bits, dtype=np.uint16)
     B, Hq, D = q_bits.shape
-    if tail_len == 0:
+    tail_lens = np.broadcast_to(np.asarray(tail_len, dtype=np.int64), (B,))
+    if not tail_lens.any():
         rows = [(b, h, 0) for b in range(B) for h in range(Hq)]
         O, LSE = attention_rows(q_bits[:, :, None, :], pk, pv, rows, causal=False, scale=scale)
         return O.reshape(B, Hq, D), LSE.reshape(B, Hq)
@@ -570,8 +578,8 @@ def attention_decode(q_bits, pk, pv, scale=None, tail_k=None, tail_v=None, tail_
         scale = 1.0 / np.sqrt(D)
     Kd = to_f64(unpack_tensor(pk), pk.dtype)
     Vd = to_f64(unpack_tensor(pv), pk.dtype)
-    Kt = to_f64(np.asarray(tail_k, dtype=np.uint16)[:, :, :tail_len], pk.dtype)
-    Vt = to_f64(np.asarray(tail_v, dtype=np.uint16)[:, :, :tail_len], pk.dtype)
+    Kt = to_f64(np.asarray(tail_k, dtype=np.uint16), pk.dtype)
+    Vt = to_f64(np.asarray(tail_v, dtype=np.uint16), pk.dtype)
     tok_visible = np.repeat(pk.map != 0, pk.Bt, axis=-1)
     O = np.zeros((B, Hq, D), dtype=np.float64)
     LSE = np.zeros((B, Hq), dtype=np.float64)
@@ -579,8 +587,9 @@ def attention_decode(q_bits, pk, pv, scale=None, tail_k=None, tail_v=None, tail_
         for hq in range(Hq):
             h = hq // G
             vis = tok_visible[b, h]
-            Kall = np.concatenate([Kd[b, h][vis], Kt[b, h]], axis=0)
-            Vall = np.concatenate([Vd[b, h][vis], Vt[b, h]], axis=0)
+            n = int(tail_lens[b])
+            Kall = np.concatenate([Kd[b, h][vis], Kt[b, h, :n]], axis=0)
+            Vall = np.concatenate([Vd[b, h][vis], Vt[b, h, :n]], axis=0)
             s = (Kall @ to_f64(q_bits[b, hq], pk.dtype)) * scale
             O[b, hq], LSE[b, hq] = _softmax_av(s, Vall)
     return O, LSE

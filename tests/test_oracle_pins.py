@@ -493,6 +493,43 @@ def test_further_pruning_of_a_packed_cache_equals_compressing_with_the_sparser_s
     assert orc.to_f64(orc.unpack_tensor(hv2), dtype)[0, 0, :4, 5].tolist() == [0.0, 4.0, 0.0, -8.0]
 
 
+def test_batch_rows_of_different_length_equal_separate_sequences():
+    """Sequences of a batch differ in length: per-row tail lengths in decode and per-row append positions
+    give, row by row, what each sequence gives on its own (the one-sequence forms are pinned above)."""
+    rng = np.random.default_rng(15)
+    B, H, Hq, Bt, D, T = 3, 2, 4, 16, 16, 6
+    K, V = _rand_kv(15, B=B, H=H, L=Bt * T, D=D)
+    held = [2, 5, 3]                                         # tiles each sequence holds so far
+    sk = np.full((B, H, T), orc.SPARSE24, dtype=np.int8)
+    sv = np.full((B, H, T), orc.DENSE, dtype=np.int8)
+    for b in range(B):
+        sk[b, :, held[b]:] = 0
+        sv[b, :, held[b]:] = 0
+    pk, pv, _ = orc.compress_kv(K, V, Bt=Bt, state_k=sk, state_v=sv)
+    q = wl.f32_to_bf16_bits(rng.standard_normal((B, Hq, D)).astype(np.float32))
+    tail_k = wl.f32_to_bf16_bits(rng.standard_normal((B, H, Bt, D)).astype(np.float32))
+    tail_v = wl.f32_to_bf16_bits(rng.standard_normal((B, H, Bt, D)).astype(np.float32))
+    lens = np.array([5, 0, 16])
+    O, LSE = orc.attention_decode(q, pk, pv, tail_k=tail_k, tail_v=tail_v, tail_len=lens)
+    for b in range(B):
+        pkb, pvb, _ = orc.compress_kv(K[b:b + 1], V[b:b + 1], Bt=Bt, state_k=sk[b:b + 1], state_v=sv[b:b + 1])
+        Ob, Lb = orc.attention_decode(q[b:b + 1], pkb, pvb, tail_k=tail_k[b:b + 1], tail_v=tail_v[b:b + 1], tail_len=int(lens[b]))
+        assert np.array_equal(O[b], Ob[0]) and np.array_equal(LSE[b], Lb[0])
+    # sequences 0 and 2 move their (full) tail into the cache at their own position, sequence 1 does not
+    where = np.array([held[0], -1, held[2]])
+    orc.append_tile(pk, pv, where, tail_k, tail_v, orc.SPARSE24, orc.DENSE)
+    for b in range(B):
+        Kb, Vb, skb, svb = K[b:b + 1].copy(), V[b:b + 1].copy(), sk[b:b + 1].copy(), sv[b:b + 1].copy()
+        if where[b] >= 0:
+            t = int(where[b])
+            Kb[:, :, Bt * t:Bt * (t + 1)], Vb[:, :, Bt * t:Bt * (t + 1)] = tail_k[b:b + 1], tail_v[b:b + 1]
+            skb[:, :, t], svb[:, :, t] = orc.SPARSE24, orc.DENSE
+        pkb, pvb, _ = orc.compress_kv(Kb, Vb, Bt=Bt, state_k=skb, state_v=svb)
+        assert (pk.map[b] == pkb.map[0]).all() and (pv.map[b] == pvb.map[0]).all()
+        assert (orc.unpack_tensor(pk)[b] == orc.unpack_tensor(pkb)[0]).all()
+        assert (orc.unpack_tensor(pv)[b] == orc.unpack_tensor(pvb)[0]).all()
+
+
 def test_fp16_patterns_are_read_as_ieee_binary16():
     """The fp16 path differs from bf16 only in what the 16-bit patterns mean: same masks and packed bits,
     values per IEEE binary16 (checked on hand-written patterns and against struct's 'e' format), scores and
