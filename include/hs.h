@@ -198,6 +198,13 @@ HS_API int hs_append_tiles(const hs_shape* shape, int32_t tile, int32_t n_tiles,
                     int32_t element_rule, const void* K_tile, const void* V_tile,
                     const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
 
+/* hs_append_tile for a batch whose sequences differ in length: tiles = device int32 [B], the tile
+ * index that batch row b fills (in all of its kv heads), or any value outside 0 .. L/64 - 1 to
+ * leave that batch row as it is (its part of K_tile, V_tile is not read). */
+HS_API int hs_append_tile_rows(const hs_shape* shape, const int32_t* tiles, int32_t state_k, int32_t state_v,
+                        int32_t element_rule, const void* K_tile, const void* V_tile,
+                        const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
+
 /* Prune a packed cache further (Sec. III, overview of the workflow: after the prefill phase the
  * dense pool can be pruned and compressed again, so that decode runs at another sparsity than
  * prefill; Sec. V evaluates prefill at S_K = 0, S_V = 1 followed by decode at S_K = S_V = 1).
@@ -263,6 +270,14 @@ HS_API int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
 HS_API int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_splits,
                         const void* Q, const hs_kv* kv, const void* tail_k, const void* tail_v,
                         int32_t tail_len, void* O, float* LSE, void* workspace, void* stream);
+
+/* The same for a batch whose sequences differ in length: tail_lens = device int32 [B], the number
+ * of valid tail tokens of batch row b (values outside 0 .. HS_TILE are clamped into that range).
+ * Rows that hold fewer tiles than others have the rest SKIP in their maps.  tail_k, tail_v,
+ * tail_lens must not be NULL. */
+HS_API int hs_decode_attn_tail_rows(const hs_shape* shape, float scale, int32_t n_splits,
+                             const void* Q, const hs_kv* kv, const void* tail_k, const void* tail_v,
+                             const int32_t* tail_lens, void* O, float* LSE, void* workspace, void* stream);
 
 /* hs_decode_attn in separable phases, for benchmarking and profiling: `phases` bit 0 launches
  * the split-KV kernel (reads Q and the cache, writes the partials into `workspace`), bit 1

@@ -50,6 +50,10 @@ EXPORTS = {
                                  C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
     "hs_append_tiles": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                   C.c_void_p, C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
+    "hs_append_tile_rows": (C.c_int, [C.POINTER(HsShape), C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
+    "hs_decode_attn_tail_rows": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_recompress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(HsKV), C.POINTER(HsKV), C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
@@ -221,7 +225,11 @@ def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARS
     assert K_tile.stride(-1) == 1 and tuple(K_tile.shape) == (shape.B, shape.Hkv, TILE * n, shape.D) and n >= 1
     strides = (C.c_int64 * 3)(K_tile.stride(0), K_tile.stride(1), K_tile.stride(2))
     kvs = kv.struct()
-    if n == 1:
+    if torch.is_tensor(tile):        # one tile index per batch row (int32 device tensor [B])
+        assert n == 1 and tile.dtype == torch.int32 and tile.is_cuda and tile.numel() == shape.B and tile.is_contiguous()
+        _check(lib().hs_append_tile_rows(C.byref(shape), _ptr(tile), int(state_k), int(state_v), int(element_rule),
+                                         _ptr(K_tile), _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
+    elif n == 1:
         _check(lib().hs_append_tile(C.byref(shape), int(tile), int(state_k), int(state_v), int(element_rule), _ptr(K_tile),
                                     _ptr(V_tile), strides, C.byref(kvs), _ptr(overflow), _stream()))
     else:
@@ -298,6 +306,12 @@ def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, ls
             workspace = _workspace(workspace_bytes(shape, 2, n + 1), Q.device)
         for t in (tail_k, tail_v):
             assert t is None or (t.dtype == Q.dtype and t.is_contiguous() and tuple(t.shape) == (shape.B, shape.Hkv, 64, shape.D))
+        if torch.is_tensor(tail_len):    # one length per batch row (int32 device tensor [B])
+            assert tail_len.dtype == torch.int32 and tail_len.is_cuda and tail_len.numel() == shape.B and tail_len.is_contiguous()
+            _check(lib().hs_decode_attn_tail_rows(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs),
+                                                  _ptr(tail_k), _ptr(tail_v), _ptr(tail_len), _ptr(O), _ptr(lse),
+                                                  _ptr(workspace), _stream()))
+            return O, lse
         _check(lib().hs_decode_attn_tail(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(tail_k),
                                          _ptr(tail_v), int(tail_len), _ptr(O), _ptr(lse), _ptr(workspace), _stream()))
         return O, lse

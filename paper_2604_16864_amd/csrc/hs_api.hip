@@ -95,12 +95,16 @@ int check_kv(const hs_shape* s, const hs_kv* kv) {
   return HS_OK;
 }
 
+int append_common(const hs_shape* shape, int32_t tile, int32_t n_tiles, const int32_t* tile_rows, int32_t state_k,
+                  int32_t state_v, int32_t element_rule, const void* K_tile, const void* V_tile,
+                  const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream);
+
 constexpr int kSelectMaxTiles = 65536;  // one workgroup per row walks its tiles: 4M tokens per row
 
 // shared body of the decode entry points; tail_len < 0: no dense tail
 int decode_common(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
-                  const void* tail_k, const void* tail_v, int tail_len, void* O, float* LSE, void* workspace,
-                  void* stream, int phases) {
+                  const void* tail_k, const void* tail_v, int tail_len, const int32_t* tail_lens, void* O, float* LSE,
+                  void* workspace, void* stream, int phases) {
   if (phases < 1 || phases > 3) return HS_EINVAL;
   int rc = check_shape(shape);
   if (rc != HS_OK) return rc;
@@ -120,7 +124,7 @@ int decode_common(const hs_shape* shape, float scale, int32_t n_splits, const vo
   }
   const hipError_t e = hs_launch_decode(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, scale, n_splits,
                                         (const uint16_t*)Q, hs_make_kv_dev(kv), (const uint16_t*)tail_k,
-                                        (const uint16_t*)tail_v, tail_len, (uint16_t*)O, LSE, (float*)workspace,
+                                        (const uint16_t*)tail_v, tail_len, tail_lens, (uint16_t*)O, LSE, (float*)workspace,
                                         (hipStream_t)stream, phases, shape->dtype);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
@@ -300,6 +304,24 @@ int hs_append_tile(const hs_shape* shape, int32_t tile, int32_t state_k, int32_t
 int hs_append_tiles(const hs_shape* shape, int32_t tile, int32_t n_tiles, int32_t state_k, int32_t state_v,
                     int32_t element_rule, const void* K_tile, const void* V_tile, const int64_t tile_strides[3],
                     const hs_kv* kv, int32_t* overflow, void* stream) {
+  return append_common(shape, tile, n_tiles, nullptr, state_k, state_v, element_rule, K_tile, V_tile, tile_strides, kv,
+                       overflow, stream);
+}
+
+int hs_append_tile_rows(const hs_shape* shape, const int32_t* tiles, int32_t state_k, int32_t state_v,
+                        int32_t element_rule, const void* K_tile, const void* V_tile, const int64_t tile_strides[3],
+                        const hs_kv* kv, int32_t* overflow, void* stream) {
+  if (tiles == nullptr) return HS_EINVAL;
+  return append_common(shape, 0, 1, tiles, state_k, state_v, element_rule, K_tile, V_tile, tile_strides, kv, overflow,
+                       stream);
+}
+
+}  // extern "C"
+
+namespace {
+int append_common(const hs_shape* shape, int32_t tile, int32_t n_tiles, const int32_t* tile_rows, int32_t state_k,
+                  int32_t state_v, int32_t element_rule, const void* K_tile, const void* V_tile,
+                  const int64_t tile_strides[3], const hs_kv* kv, int32_t* overflow, void* stream) {
   int rc = check_shape(shape);
   if (rc != HS_OK) return rc;
   rc = check_kv(shape, kv);
@@ -318,11 +340,14 @@ int hs_append_tiles(const hs_shape* shape, int32_t tile, int32_t n_tiles, int32_
     if (st < HS_D || sh < 0 || sb < 0 || ((sb | sh | st) & 7)) return HS_EINVAL;
   }
   const hipError_t e = hs_launch_append((const uint16_t*)K_tile, (const uint16_t*)V_tile, sb, sh, st, shape->B,
-                                        shape->Hkv, T, tile, n_tiles, state_k, state_v, hs_make_kv_dev(kv), element_rule,
-                                        shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
+                                        shape->Hkv, T, tile, n_tiles, tile_rows, state_k, state_v, hs_make_kv_dev(kv),
+                                        element_rule, shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }
+}  // namespace
+
+extern "C" {
 
 int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv* src, const hs_kv* dst,
                      void* workspace, int32_t* overflow, void* stream) {
@@ -420,7 +445,7 @@ int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const v
 
 int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
                           float* LSE, void* workspace, void* stream, int phases) {
-  return decode_common(shape, scale, n_splits, Q, kv, nullptr, nullptr, -1, O, LSE, workspace, stream, phases);
+  return decode_common(shape, scale, n_splits, Q, kv, nullptr, nullptr, -1, nullptr, O, LSE, workspace, stream, phases);
 }
 
 int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
@@ -429,7 +454,15 @@ int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_splits, co
   if (tail_len < 0 || tail_len > HS_BT) return HS_EINVAL;
   if (tail_len > 0 && (tail_k == nullptr || tail_v == nullptr)) return HS_EINVAL;
   if (((uintptr_t)tail_k | (uintptr_t)tail_v) & 15u) return HS_EINVAL;
-  return decode_common(shape, scale, n_splits, Q, kv, tail_k, tail_v, tail_len, O, LSE, workspace, stream, 3);
+  return decode_common(shape, scale, n_splits, Q, kv, tail_k, tail_v, tail_len, nullptr, O, LSE, workspace, stream, 3);
+}
+
+int hs_decode_attn_tail_rows(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
+                             const void* tail_k, const void* tail_v, const int32_t* tail_lens, void* O, float* LSE,
+                             void* workspace, void* stream) {
+  if (tail_k == nullptr || tail_v == nullptr || tail_lens == nullptr) return HS_EINVAL;
+  if (((uintptr_t)tail_k | (uintptr_t)tail_v) & 15u) return HS_EINVAL;
+  return decode_common(shape, scale, n_splits, Q, kv, tail_k, tail_v, 0, tail_lens, O, LSE, workspace, stream, 3);
 }
 
 }  // extern "C"

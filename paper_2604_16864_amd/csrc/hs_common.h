@@ -139,16 +139,17 @@ hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int6
                           int B, int Hkv, int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, int v_f16, hipStream_t st);
 // n_tiles tiles [B, Hkv, 64 n_tiles, D] into tile indices tile .. of a cache of T tiles per row
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_,
-                            int B, int Hkv, int T, int tile, int n_tiles, int state_k, int state_v, hs_kv_dev kv, int rule,
+                            int B, int Hkv, int T, int tile, int n_tiles, const int32_t* tile_rows, int state_k, int state_v, hs_kv_dev kv, int rule,
                             int v_f16, int32_t* overflow, hipStream_t st);
 // packed cache -> packed cache, each tile in the sparser of its state and its target (device int8 [rows, T])
 hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,
                                 hs_kv_dev dst, int rule, int v_f16, int32_t* overflow, hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 // tail_len < 0: no tail slot; tail_len >= 0: one extra partial per query head, computed from the
-// dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D])
+// dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D]); tail_lens (device, [B]) replaces
+// tail_len per batch row when not NULL
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
-                            hs_kv_dev kv, const uint16_t* tail_k, const uint16_t* tail_v, int tail_len,
+                            hs_kv_dev kv, const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, const int32_t* tail_lens,
                             uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases, int dtype);
 // q_start: position in the cache of the first query (query i sees tokens <= q_start + i when causal)
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, int q_start, float scale, int causal, const uint16_t* Q,

@@ -321,10 +321,17 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
 // next slots of the pool their state names, counted from how many tiles of that kind the row
 // holds; tiles for which a pool has no slot left stay skipped and raise *overflow.  One workgroup
 // per row.
-__global__ __launch_bounds__(256) void append_slots_kernel(int T, int tile, int n_tiles, int state_k, int state_v,
-                                                           hs_kv_dev kv, int32_t* overflow) {
+// tile_rows (or NULL): one tile index per batch row instead of `tile` (then n_tiles = 1); a batch
+// row whose entry is not a tile index is left as it is.
+__global__ __launch_bounds__(256) void append_slots_kernel(int Hkv, int T, int tile, int n_tiles,
+                                                           const int32_t* __restrict__ tile_rows, int state_k,
+                                                           int state_v, hs_kv_dev kv, int32_t* overflow) {
   __shared__ int part[4][4];
   const int row = blockIdx.x, tid = threadIdx.x;
+  if (tile_rows != nullptr) {
+    tile = tile_rows[row / Hkv];
+    if (tile < 0 || tile >= T) return;  // the whole workgroup
+  }
   int32_t* km = const_cast<int32_t*>(kv.k_map) + (int64_t)row * T;
   int32_t* vm = const_cast<int32_t*>(kv.v_map) + (int64_t)row * T;
   int n[4] = {0, 0, 0, 0};  // dense K, 2:4 K, dense V, 2:4 V
@@ -495,10 +502,17 @@ __device__ __forceinline__ void v_dense_to_lds(const uint8_t* src, bool is_f16, 
 // kernel writes it (saves the separate map-fill launch of the unranked policies).
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv,
-                                                   int uni_k, int uni_v, int rule, int t0, int v_f16) {
+                                                   int uni_k, int uni_v, int rule, int t0, int v_f16,
+                                                   const int32_t* __restrict__ t0_rows) {
   __shared__ uint16_t vl[HS_BT * kVStride];
-  // source tile blockIdx.x of K, V goes to tile t of the cache (t0 = 0 except when appending)
-  const int ts = blockIdx.x, t = ts + t0, h = blockIdx.y, b = blockIdx.z;
+  // source tile blockIdx.x of K, V goes to tile t of the cache (t0 = 0 except when appending;
+  // t0_rows: one t0 per batch row, entries that are not a tile index leave the row out)
+  const int ts = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (t0_rows != nullptr) {
+    t0 = t0_rows[b];
+    if (t0 < 0 || t0 >= T) return;  // the whole workgroup
+  }
+  const int t = ts + t0;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, a = l >> 4, r = l & 15;
   const int64_t row = (int64_t)b * Hkv + h;
   int mk, mv;
@@ -789,17 +803,20 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
 
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
                           int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, int v_f16, hipStream_t st) {
-  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0, v_f16);
+  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0, v_f16,
+                     (const int32_t*)nullptr);
   return hipGetLastError();
 }
 
 hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
-                            int T, int tile, int n_tiles, int state_k, int state_v, hs_kv_dev kv, int rule, int v_f16,
-                            int32_t* overflow, hipStream_t st) {
-  hipLaunchKernelGGL(append_slots_kernel, dim3(B * Hkv), dim3(256), 0, st, T, tile, n_tiles, state_k, state_v, kv, overflow);
+                            int T, int tile, int n_tiles, const int32_t* tile_rows, int state_k, int state_v,
+                            hs_kv_dev kv, int rule, int v_f16, int32_t* overflow, hipStream_t st) {
+  hipLaunchKernelGGL(append_slots_kernel, dim3(B * Hkv), dim3(256), 0, st, Hkv, T, tile, n_tiles, tile_rows, state_k, state_v,
+                     kv, overflow);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(pack_kernel, dim3(n_tiles, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16);
+  hipLaunchKernelGGL(pack_kernel, dim3(n_tiles, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16,
+                     tile_rows);
   return hipGetLastError();
 }
 

@@ -388,7 +388,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(int n_splits, const f
 // phase 3 channel t%128 for heads t/128, t/128 + 2, ...
 template <bool F16>
 __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float scale_log2, int n_slots, int slot,
-                                                          int tail_len, const uint16_t* __restrict__ Q,
+                                                          int tail_len, const int32_t* __restrict__ tail_lens,
+                                                          const uint16_t* __restrict__ Q,
                                                           const uint16_t* __restrict__ TK,
                                                           const uint16_t* __restrict__ TV, float* __restrict__ ws_o,
                                                           float* __restrict__ ws_l) {
@@ -397,6 +398,7 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float
   __shared__ float sl_[8];
   const int tid = threadIdx.x, hkv = blockIdx.x, b = blockIdx.y;
   const int G = Hq / Hkv;
+  if (tail_lens != nullptr) tail_len = min(max(tail_lens[b], 0), HS_BT);  // one per batch row, kept inside the tail buffer
   const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;
   const uint16_t* tk = TK + ((int64_t)b * Hkv + hkv) * HS_BT * HS_D;
   const uint16_t* tv = TV + ((int64_t)b * Hkv + hkv) * HS_BT * HS_D;
@@ -461,8 +463,8 @@ static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T
 }
 
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_work, const uint16_t* Q, hs_kv_dev kv,
-                            const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, uint16_t* O, float* LSE,
-                            float* ws, hipStream_t st, int phases, int dtype) {
+                            const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, const int32_t* tail_lens,
+                            uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases, int dtype) {
   const dim3 grid(n_work, Hkv, B);
   const bool f16 = dtype == HS_FP16;
   const float sl2 = scale * kLog2e;
@@ -498,10 +500,10 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_wo
   if (e == hipSuccess && (phases & 1) && tail_len >= 0) {
     if (f16)
       hipLaunchKernelGGL(decode_tail_kernel<true>, dim3(Hkv, B), dim3(256), 0, st, Hq, Hkv, sl2, n_splits, n_work,
-                         tail_len, Q, tail_k, tail_v, wo, wl);
+                         tail_len, tail_lens, Q, tail_k, tail_v, wo, wl);
     else
       hipLaunchKernelGGL(decode_tail_kernel<false>, dim3(Hkv, B), dim3(256), 0, st, Hq, Hkv, sl2, n_splits, n_work,
-                         tail_len, Q, tail_k, tail_v, wo, wl);
+                         tail_len, tail_lens, Q, tail_k, tail_v, wo, wl);
     e = hipGetLastError();
   }
   if (e != hipSuccess || !(phases & 2)) return e;

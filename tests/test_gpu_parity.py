@@ -561,6 +561,50 @@ def test_append_tiles_during_decode():
     assert hb.lib().hs_append_tile(C.byref(sh), 5, 2, 2, 7, *args) == -1          # unknown element rule
 
 
+def test_batch_rows_of_different_length_decode_and_append():
+    """A batch whose sequences hold 3, 9 and 6 tiles and 17, 0 and 64 tail tokens: decode with one tail
+    length per batch row; the row with the full tail (and only that one) appends it at its own position;
+    decode again.  Against the oracle throughout, packed state bit for bit."""
+    B, Hq, Hkv, T = 3, 8, 2, 10
+    L = 64 * T
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=270, k_outliers=True)
+    q = Q[:, :, 0, :].copy()
+    held = [3, 9, 6]
+    sk = np.full((B, Hkv, T), orc.DENSE, dtype=np.int8)
+    sv = np.full((B, Hkv, T), orc.SPARSE24, dtype=np.int8)
+    for b in range(B):
+        sk[b, :, held[b]:] = 0
+        sv[b, :, held[b]:] = 0
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv = hb.PackedKV(sh, [0, T, 0, 0, T])
+    kv.uniform = 0
+    hb.compress_kv(sh, hb.make_policy(state_k=sk, state_v=sv), _dev(K), _dev(V), out=kv)
+    pk, pv, _ = orc.compress_kv(K, V, state_k=sk, state_v=sv)
+    _, tk, tv = wl.make_qkv(B, Hq, Hkv, 64, 128, 1, seed=271)
+    lens = np.array([17, 0, 64], dtype=np.int32)
+    lens_d = torch.from_numpy(lens).cuda()
+    O, LSE = hb.decode_attn(sh, _dev(q), kv, tail_k=_dev(tk), tail_v=_dev(tv), tail_len=lens_d, n_splits=2)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, pk, pv, tail_k=tk, tail_v=tv, tail_len=lens)
+    for b in range(B):
+        assert_close(_f32(O)[b], Or[b], f"decode ragged batch row {b}")
+    assert_lse_close(LSE.cpu().numpy(), Lr, "decode ragged batch lse")
+    where = np.array([-1, -1, held[2]], dtype=np.int32)
+    ovf = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hb.append_tile(sh, kv, torch.from_numpy(where).cuda(), _dev(tk), _dev(tv), state_k=hb.DENSE, state_v=hb.SPARSE24, overflow=ovf)
+    orc.append_tile(pk, pv, where, tk, tv, orc.DENSE, orc.SPARSE24)
+    torch.cuda.synchronize()
+    assert int(ovf.item()) == 0
+    check_packed_bit_exact(sh, kv, pk, pv)
+    lens2 = np.array([18, 1, 0], dtype=np.int32)            # one more token each; row 2 starts a new tail
+    O, LSE = hb.decode_attn(sh, _dev(q), kv, tail_k=_dev(tk), tail_v=_dev(tv), tail_len=torch.from_numpy(lens2).cuda())
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, pk, pv, tail_k=tk, tail_v=tv, tail_len=lens2)
+    for b in range(B):
+        assert_close(_f32(O)[b], Or[b], f"decode ragged batch after append row {b}")
+    assert_lse_close(LSE.cpu().numpy(), Lr, "decode ragged batch after append lse")
+
+
 def test_chunked_prefill_appends_a_chunk_then_attends_from_its_position():
     """Chunked prefill (the paper's long-context runs use chunks): a cache allocated for the whole sequence
     starts empty; each chunk of 3 tiles is appended in one call (keys dense, values 2:4) and its queries attend
