@@ -298,7 +298,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     // instructions and keeps the accumulators where they are (a per-tile branch around GEMM2 made
     // the compiler move all 64 accumulator registers in and out of the branch).  The encoding is
     // scalar: map entries come through v_readlane.
-    auto iteration = [&](auto enc) {  // enc: 0 = bf16 V tile, 1 = fp16-encoded, 2 = look at the tile (mixed dense / 2:4 V)
+    auto iteration = [&](auto enc, auto vkind) {  // vkind: 0 = V tile 2:4, 1 = dense, 2 = look at the tile  // enc: 0 = bf16 V tile, 1 = fp16-encoded, 2 = look at the tile (mixed dense / 2:4 V)
       constexpr int kEnc = decltype(enc)::value;
       const int j = tj[0], mk = tk[0], mv = tv[0];
       // END mode: request the tile D ahead now; its stage held the tile of the previous iteration,
@@ -306,7 +306,8 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       if (!MID) request();
       const bool ok = valid && j <= jmax_w;
       const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
-      const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
+      constexpr int kVK = decltype(vkind)::value;
+      const bool v_sparse = kVK == 2 ? (VM == 0 || (VM == 2 && mv < 0)) : kVK == 0;
       const bool v_f16 = kEnc == 2 ? (F16 || hs_map_f16(mv)) : kEnc == 1;
       const uint4* kl = reinterpret_cast<const uint4*>(lds + st * kStage);
       const uint4* vl = reinterpret_cast<const uint4*>(lds + st * kStage + region_bytes<KM>());
@@ -513,16 +514,27 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       st = st + 1 == NS ? 0 : st + 1;
     };
     while (tj[0] >= 0) {
-      if constexpr (ONLY16) {
-        iteration(std::integral_constant<int, 1>{});
+      typedef std::integral_constant<int, 0> I0;
+      typedef std::integral_constant<int, 1> I1;
+      typedef std::integral_constant<int, 2> I2;
+      if constexpr (ONLY16 && VM == 2) {  // runs of dense / of 2:4 V tiles
+        if (tv[0] > 0) {
+          do iteration(I1{}, I1{});
+          while (tj[0] >= 0 && tv[0] > 0);
+        } else {
+          do iteration(I1{}, I0{});
+          while (tj[0] >= 0 && tv[0] < 0);
+        }
+      } else if constexpr (ONLY16) {
+        iteration(I1{}, I2{});
       } else if constexpr (VM == 2) {  // four GEMM2 forms in one kernel: no second copy of the loop
-        iteration(std::integral_constant<int, 2>{});
+        iteration(I2{}, I2{});
       } else {
         if (hs_map_f16(tv[0])) {
-          do iteration(std::integral_constant<int, 1>{});
+          do iteration(I1{}, I2{});
           while (tj[0] >= 0 && hs_map_f16(tv[0]));
         } else {
-          do iteration(std::integral_constant<int, 0>{});
+          do iteration(I0{}, I2{});
           while (tj[0] >= 0 && !hs_map_f16(tv[0]));
         }
       }
@@ -530,7 +542,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   };
   if constexpr (F16) {
     main_loop(std::integral_constant<bool, MID_OK>{}, std::true_type{});
-  } else if constexpr (MID_OK) {
+  } else if constexpr (MID_OK || VM == 2) {
     // bf16 cache: are all V tiles this workgroup can meet in fp16 encoding?  (every wave scans the
     // same entries, so the workgroup agrees; the answer is scalar)
     bool all16 = true;
@@ -539,7 +551,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       const int32_t m = t <= jmax_wg ? vm[t] : 0;
       all16 = all16 && !__any(m != 0 && !hs_map_f16(m));
     }
-    if (all16) main_loop(std::true_type{}, std::true_type{});
+    if (all16) main_loop(std::integral_constant<bool, MID_OK>{}, std::true_type{});
     else main_loop(std::false_type{}, std::false_type{});
   } else {
     main_loop(std::false_type{}, std::false_type{});
@@ -596,7 +608,7 @@ hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, int q_start,
     case 2: HS_GO(0, 2);
     case 3: HS_GO(1, 0);
     case 4: HS_GO(1, 1);
-    case 5: HS_GO(1, 2);
+    case 5: HS_GO(2, 2);  // dense K beside mixed V: the instantiation that looks at each K tile's kind measured faster than <1, 2>
     case 6: HS_GO(2, 0);
     case 7: HS_GO(2, 1);
     default: HS_GO(2, 2);
