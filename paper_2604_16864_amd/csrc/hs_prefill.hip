@@ -234,14 +234,16 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   // wbase + t; entries are picked out with readlane and the next visible tile is found on the
   // ballot of "entry != 0".  This keeps map reads (vector loads, which complete in order with
   // the tile loads and would otherwise have to wait for them) off the per-tile path.
-  int wbase = 0;
+  // vfilter: 0 = every tile that is not skipped; -1 / +1 = of those only the ones whose V tile is
+  // 2:4 / dense (a pass over one kind of V tile, see main_loop).
+  int wbase = 0, vfilter = 0;
   int32_t wk = 0, wv = 0;
   uint64_t wact = 0;
   auto window_load = [&](int base) {
     const int t = base + l;
     wk = t <= jmax_wg ? km[t] : 0;
     wv = t <= jmax_wg ? vm[t] : 0;
-    wact = __ballot(wk != 0);
+    wact = __ballot(wk != 0 && (vfilter == 0 || (vfilter > 0) == (wv > 0)));
     wbase = base;
   };
   auto next_visible = [&](int j) -> int {  // first tile > j (and <= jmax_wg) that is not skipped, or -1
@@ -254,19 +256,26 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       j = wbase - 1;
     }
   };
-  window_load(0);
-#pragma unroll
-  for (int i = 0; i < D; i++) {
-    tj[i] = i == 0 ? next_visible(-1) : (tj[i - 1] >= 0 ? next_visible(tj[i - 1]) : -1);
-    tk[i] = tv[i] = 0;
-    if (tj[i] >= 0) {
-      tk[i] = __builtin_amdgcn_readlane(wk, tj[i] - wbase); tv[i] = __builtin_amdgcn_readlane(wv, tj[i] - wbase);
-      stage_issue<KM, VM>(lds_base + i * kStage, kv, row, tk[i], tv[i], w, lane_off);
-    }
-  }
-  stage_wait<1>(0);
-  __syncthreads();
   int st = 0;
+  // Start of a pass over the tiles that `filter` lets through: the first D of them are requested
+  // into stages 0 .. D-1 and the first one is waited for.  (A second pass must not start before
+  // every wave has left the LDS reads of the first: the caller puts a barrier in between.)
+  auto start_pass = [&](int filter) {
+    vfilter = filter;
+    st = 0;
+    window_load(0);
+#pragma unroll
+    for (int i = 0; i < D; i++) {
+      tj[i] = i == 0 ? next_visible(-1) : (tj[i - 1] >= 0 ? next_visible(tj[i - 1]) : -1);
+      tk[i] = tv[i] = 0;
+      if (tj[i] >= 0) {
+        tk[i] = __builtin_amdgcn_readlane(wk, tj[i] - wbase); tv[i] = __builtin_amdgcn_readlane(wv, tj[i] - wbase);
+        stage_issue<KM, VM>(lds_base + i * kStage, kv, row, tk[i], tv[i], w, lane_off);
+      }
+    }
+    stage_wait<1>(0);
+    __syncthreads();
+  };
   // 2:4 operands of the sparse instruction are fetched from LDS a phase ahead of their use:
   // V of the current tile before the softmax, K of the next tile before GEMM2 (MID mode).
   uint4 ak[8], kix, av[8], vix;
@@ -292,7 +301,6 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
     // already holds the registers (both together spill; measured no gain there)
     constexpr bool V_EARLY = F16 && VM == 0 && !MID;
-    if (MID && valid && tj[0] >= 0) k_fetch(0);
     // One iteration = one tile.  The loop exists twice, for runs of V tiles in fp16 encoding (one fp16
     // term of P) and in bf16 (two terms), so that each copy is straight-line code around its matrix
     // instructions and keeps the accumulators where they are (a per-tile branch around GEMM2 made
@@ -513,19 +521,27 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       for (int i = 0; i < D; i++) { tj[i] = tj[i + 1]; tk[i] = tk[i + 1]; tv[i] = tv[i + 1]; }
       st = st + 1 == NS ? 0 : st + 1;
     };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    typedef std::integral_constant<int, 2> I2;
+    if constexpr (ONLY16 && VM == 2) {
+      // Mixed V tiles of one encoding: two passes, first over the tiles whose V tile is 2:4, then
+      // over those whose V tile is dense (softmax does not care about the order of the tiles; the
+      // causal mask goes by the tile's index).  Each pass is one loop with one GEMM2 form.  Going
+      // back and forth between the two loops tile by tile costs a move of all accumulators at
+      // every change (the two loops hold them in different registers): measured 19 % at S = 0.75.
+      static_assert(!MID, "passes are written for the end-of-iteration barrier");
+      start_pass(-1);
+      while (tj[0] >= 0) iteration(I1{}, I0{});
+      __syncthreads();
+      start_pass(+1);
+      while (tj[0] >= 0) iteration(I1{}, I1{});
+      return;
+    }
+    start_pass(0);
+    if (MID && valid && tj[0] >= 0) k_fetch(0);
     while (tj[0] >= 0) {
-      typedef std::integral_constant<int, 0> I0;
-      typedef std::integral_constant<int, 1> I1;
-      typedef std::integral_constant<int, 2> I2;
-      if constexpr (ONLY16 && VM == 2) {  // runs of dense / of 2:4 V tiles
-        if (tv[0] > 0) {
-          do iteration(I1{}, I1{});
-          while (tj[0] >= 0 && tv[0] > 0);
-        } else {
-          do iteration(I1{}, I0{});
-          while (tj[0] >= 0 && tv[0] < 0);
-        }
-      } else if constexpr (ONLY16) {
+      if constexpr (ONLY16) {
         iteration(I1{}, I2{});
       } else if constexpr (VM == 2) {  // four GEMM2 forms in one kernel: no second copy of the loop
         iteration(I2{}, I2{});
