@@ -155,8 +155,8 @@ union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the de
 // F16: element type of the cache (hs_elem).  A V tile of a bf16 cache may be stored in fp16 encoding
 // (HS_MAP_F16 in its map entry).  Against fp16 V the numerators have 11 significant bits and enter
 // GEMM2 as one fp16 term; against bf16 V they enter as two bf16 terms.  The reference is kept
-// kShift = 8 binades under the running maximum (range, see decode) and renewed before a
-// numerator can reach the fp16 maximum.
+// kShift binades under the running maximum and renewed before a numerator can reach the fp16
+// maximum (constants below).
 template <int KM, int VM, int NB, bool F16>
 __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, int Hkv, int T, int Lq, int off,
                                                                       float scale_log2, int causal,
@@ -165,8 +165,14 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
                                                                       float* __restrict__ LSE) {
   typedef hs_elem<F16> E;
   typedef hs_elem<true> E16;
-  constexpr float kShift = 8.f;
-  constexpr float kRedo = 0x1p14f;  // partial row sum above which the reference is renewed
+  // Reference = running maximum - kShift at the time it was last renewed; it is renewed when a lane's
+  // partial row sum passes kRedo, i.e. before a numerator can pass 2^15 (fp16 holds 65504).  A new
+  // score may thus exceed the maximum seen so far by 15 - kShift = 11 binades before the tile has
+  // to be redone; with 8 / 2^14 (6 binades) keys with large channels redid 5 % of the work.
+  // What fp16 flushes to zero lies 24 + kShift binades under the largest numerator: a context of
+  // 2^17 tokens loses < 2^-11 of a row sum even if every other token sits just under that level.
+  constexpr float kShift = 4.f;
+  constexpr float kRedo = 0x1p15f;
   constexpr int QS = 16 * NB;  // query positions per slab
   constexpr int NS = n_stages<KM, VM>(), D = NS - 1;  // ring size, prefetch distance in tiles
   // MID: the per-tile barrier sits between softmax and GEMM2 instead of at the end of the
