@@ -605,6 +605,74 @@ def test_batch_rows_of_different_length_decode_and_append():
     assert_lse_close(LSE.cpu().numpy(), Lr, "decode ragged batch after append lse")
 
 
+def test_serving_loop_two_sequences_of_different_length():
+    """The calls in the order a serving loop issues them, for a batch of two sequences of different length:
+    compress the whole tiles of each prompt (keys dense, values 2:4), prune the keys further for decode,
+    then 70 decode steps in which every new token goes to the dense tail and a full tail moves into the
+    cache of its own sequence.  Oracle state and outputs are checked along the way."""
+    B, Hq, Hkv, T = 2, 8, 2, 8
+    L = 64 * T
+    prompt = [64 * 5 + 17, 64 * 3 + 40]
+    steps = 70
+    total = max(prompt) + steps
+    rng = np.random.default_rng(280)
+    Kall = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, total, 128)).astype(np.float32))
+    Vall = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, total, 128)).astype(np.float32))
+    Qall = wl.f32_to_bf16_bits(rng.standard_normal((B, Hq, steps, 128)).astype(np.float32))
+    held = [p // 64 for p in prompt]
+    tail_n = [p % 64 for p in prompt]
+    K0, V0 = np.zeros((B, Hkv, L, 128), dtype=np.uint16), np.zeros((B, Hkv, L, 128), dtype=np.uint16)
+    sk, sv = np.zeros((B, Hkv, T), dtype=np.int8), np.zeros((B, Hkv, T), dtype=np.int8)
+    tk, tv = np.zeros((B, Hkv, 64, 128), dtype=np.uint16), np.zeros((B, Hkv, 64, 128), dtype=np.uint16)
+    for b in range(B):
+        n = 64 * held[b]
+        K0[b, :, :n], V0[b, :, :n] = Kall[b, :, :n], Vall[b, :, :n]
+        sk[b, :, :held[b]], sv[b, :, :held[b]] = orc.DENSE, orc.SPARSE24
+        tk[b, :, :tail_n[b]], tv[b, :, :tail_n[b]] = Kall[b, :, n:prompt[b]], Vall[b, :, n:prompt[b]]
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv_prefill = hb.PackedKV(sh, [0, T, 0, 0, T])
+    kv_prefill.uniform = 0
+    hb.compress_kv(sh, hb.make_policy(state_k=sk, state_v=sv), _dev(K0), _dev(V0), out=kv_prefill)
+    pk, pv, _ = orc.compress_kv(K0, V0, state_k=sk, state_v=sv)
+    # decode policy: every key tile 2:4 as well
+    kv = hb.recompress_kv(sh, kv_prefill, hb.make_policy(), counts=[0, 0, T, 0, T])
+    pk, pv = orc.recompress_kv(pk, pv, np.where(sk == 0, 0, 2), np.where(sv == 0, 0, 2))
+    torch.cuda.synchronize()
+    check_packed_bit_exact(sh, kv, pk, pv)
+    tk_d, tv_d = _dev(tk), _dev(tv)
+    ovf = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pos = list(prompt)
+    checked = 0
+    for s_ in range(steps):
+        for b in range(B):                                   # the new token's K, V join the tail of its sequence
+            tk[b, :, tail_n[b]], tv[b, :, tail_n[b]] = Kall[b, :, pos[b]], Vall[b, :, pos[b]]
+            tk_d[b, :, tail_n[b]] = _dev(Kall[b, :, pos[b]])
+            tv_d[b, :, tail_n[b]] = _dev(Vall[b, :, pos[b]])
+            tail_n[b] += 1
+            pos[b] += 1
+        q = Qall[:, :, s_, :].copy()
+        lens = np.array(tail_n, dtype=np.int32)
+        O, LSE = hb.decode_attn(sh, _dev(q), kv, tail_k=tk_d, tail_v=tv_d, tail_len=torch.from_numpy(lens).cuda(), n_splits=2)
+        if s_ in (0, 23, 24, 46, 47, 48, steps - 1):
+            torch.cuda.synchronize()
+            Or, Lr = orc.attention_decode(q, pk, pv, tail_k=tk, tail_v=tv, tail_len=lens)
+            for b in range(B):
+                assert_close(_f32(O)[b], Or[b], f"serving step {s_} sequence {b}")
+            assert_lse_close(LSE.cpu().numpy(), Lr, f"serving step {s_} lse")
+            checked += 1
+        where = np.array([held[b] if tail_n[b] == 64 else -1 for b in range(B)], dtype=np.int32)
+        if (where >= 0).any():                               # a full tail becomes the next tile of its sequence
+            hb.append_tile(sh, kv, torch.from_numpy(where).cuda(), tk_d, tv_d, state_k=hb.SPARSE24, state_v=hb.SPARSE24, overflow=ovf)
+            orc.append_tile(pk, pv, where, tk, tv, orc.SPARSE24, orc.SPARSE24)
+            for b in range(B):
+                if where[b] >= 0:
+                    held[b] += 1
+                    tail_n[b] = 0
+    torch.cuda.synchronize()
+    assert checked == 7 and int(ovf.item()) == 0 and held == [6, 4] and tail_n == [23, 46]
+    check_packed_bit_exact(sh, kv, pk, pv)
+
+
 def test_chunked_prefill_appends_a_chunk_then_attends_from_its_position():
     """Chunked prefill (the paper's long-context runs use chunks): a cache allocated for the whole sequence
     starts empty; each chunk of 3 tiles is appended in one call (keys dense, values 2:4) and its queries attend
