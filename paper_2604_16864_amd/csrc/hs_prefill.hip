@@ -237,51 +237,60 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds);
   const uint32_t lane_off = 16 * l;
   // The maps are read 64 tiles at a time, lane t of the window holding the entries of tile
-  // wbase + t; entries are picked out with readlane and the next visible tile is found on the
-  // ballot of "entry != 0".  This keeps map reads (vector loads, which complete in order with
-  // the tile loads and would otherwise have to wait for them) off the per-tile path.
-  // vfilter: 0 = every tile that is not skipped; -1 / +1 = of those only the ones whose V tile is
-  // 2:4 / dense (a pass over one kind of V tile, see main_loop).
-  int wbase = 0, vfilter = 0;
+  // wbase + t; entries are picked out with readlane and the next tile is found on a ballot.
+  // This keeps map reads (vector loads, which complete in order with the tile loads and would
+  // otherwise have to wait for them) off the per-tile path.
+  // Order of the tiles: up to three groups, one after the other over the whole range, ascending
+  // inside a group: V tile in fp16 encoding and 2:4 (or of the tensor's only kind); in fp16 encoding
+  // and dense (mixed V tensors); V tile in bf16 encoding (bf16 caches: tiles with a value that fp16
+  // does not hold, e.g. ~5 % of dense N(0,1) tiles, which contain a number under 2^-17).  Softmax
+  // does not care about the order and the causal mask goes by the tile's index.  The loop below
+  // exists once per GEMM2 form; with this order a workgroup changes form at most twice.  (A change
+  // is not cheap: the loops hold the accumulators in different registers, and the spill reloads
+  // the compiler puts on the way wait for the tile loads in flight as well.)
+  int wbase = 0, wgroup = 0;
   int32_t wk = 0, wv = 0;
-  uint64_t wact = 0;
+  uint64_t wrem = 0;  // tiles of the window still to hand out
   auto window_load = [&](int base) {
     const int t = base + l;
     wk = t <= jmax_wg ? km[t] : 0;
     wv = t <= jmax_wg ? vm[t] : 0;
-    wact = __ballot(wk != 0 && (vfilter == 0 || (vfilter > 0) == (wv > 0)));
+    const bool g2 = !F16 && !hs_map_f16(wv);
+    const bool g1 = !g2 && VM == 2 && wv > 0;
+    const int grp = g2 ? 2 : (g1 ? 1 : 0);
+    wrem = __ballot(wk != 0 && grp == wgroup);
     wbase = base;
   };
-  auto next_visible = [&](int j) -> int {  // first tile > j (and <= jmax_wg) that is not skipped, or -1
+  auto next_tile = [&]() -> int {  // next tile (<= jmax_wg, not skipped) in the order above, or -1
     for (;;) {
-      const int rel = j + 1 - wbase;  // 0 .. 64
-      const uint64_t m = rel < 64 ? (wact >> rel) : 0;
-      if (m != 0) return j + 1 + __builtin_ctzll(m);
-      if (wbase + 64 > jmax_wg) return -1;
-      window_load(wbase + 64);
-      j = wbase - 1;
+      if (wrem != 0) {
+        const int t = __builtin_ctzll(wrem);
+        wrem &= wrem - 1;
+        return wbase + t;
+      }
+      if (wbase + 64 <= jmax_wg) {
+        window_load(wbase + 64);
+        continue;
+      }
+      do wgroup++;
+      while ((wgroup == 1 && VM != 2) || (wgroup == 2 && F16));  // groups this kernel cannot meet
+      if (wgroup > 2) return -1;
+      window_load(0);
     }
   };
   int st = 0;
-  // Start of a pass over the tiles that `filter` lets through: the first D of them are requested
-  // into stages 0 .. D-1 and the first one is waited for.  (A second pass must not start before
-  // every wave has left the LDS reads of the first: the caller puts a barrier in between.)
-  auto start_pass = [&](int filter) {
-    vfilter = filter;
-    st = 0;
-    window_load(0);
+  window_load(0);
 #pragma unroll
-    for (int i = 0; i < D; i++) {
-      tj[i] = i == 0 ? next_visible(-1) : (tj[i - 1] >= 0 ? next_visible(tj[i - 1]) : -1);
-      tk[i] = tv[i] = 0;
-      if (tj[i] >= 0) {
-        tk[i] = __builtin_amdgcn_readlane(wk, tj[i] - wbase); tv[i] = __builtin_amdgcn_readlane(wv, tj[i] - wbase);
-        stage_issue<KM, VM>(lds_base + i * kStage, kv, row, tk[i], tv[i], w, lane_off);
-      }
+  for (int i = 0; i < D; i++) {
+    tj[i] = i == 0 || tj[i - 1] >= 0 ? next_tile() : -1;
+    tk[i] = tv[i] = 0;
+    if (tj[i] >= 0) {
+      tk[i] = __builtin_amdgcn_readlane(wk, tj[i] - wbase); tv[i] = __builtin_amdgcn_readlane(wv, tj[i] - wbase);
+      stage_issue<KM, VM>(lds_base + i * kStage, kv, row, tk[i], tv[i], w, lane_off);
     }
-    stage_wait<1>(0);
-    __syncthreads();
-  };
+  }
+  stage_wait<1>(0);
+  __syncthreads();
   // 2:4 operands of the sparse instruction are fetched from LDS a phase ahead of their use:
   // V of the current tile before the softmax, K of the next tile before GEMM2 (MID mode).
   uint4 ak[8], kix, av[8], vix;
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     if (KM != 1) kix = kl[512 + l];
   };
   auto request = [&]() {  // look up the tile D ahead and start its copy into the stage D ahead
-    tj[D] = tj[D - 1] >= 0 ? next_visible(tj[D - 1]) : -1;
+    tj[D] = tj[D - 1] >= 0 ? next_tile() : -1;
     tk[D] = tv[D] = 0;
     if (tj[D] >= 0) {
       tk[D] = __builtin_amdgcn_readlane(wk, tj[D] - wbase); tv[D] = __builtin_amdgcn_readlane(wv, tj[D] - wbase);
@@ -530,41 +539,29 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     typedef std::integral_constant<int, 0> I0;
     typedef std::integral_constant<int, 1> I1;
     typedef std::integral_constant<int, 2> I2;
-    if constexpr (ONLY16 && VM == 2) {
-      // Mixed V tiles of one encoding: two passes, first over the tiles whose V tile is 2:4, then
-      // over those whose V tile is dense (softmax does not care about the order of the tiles; the
-      // causal mask goes by the tile's index).  Each pass is one loop with one GEMM2 form.  Going
-      // back and forth between the two loops tile by tile costs a move of all accumulators at
-      // every change (the two loops hold them in different registers): measured 19 % at S = 0.75.
-      static_assert(!MID, "passes are written for the end-of-iteration barrier");
-      start_pass(-1);
-      while (tj[0] >= 0) iteration(I1{}, I0{});
-      __syncthreads();
-      start_pass(+1);
-      while (tj[0] >= 0) iteration(I1{}, I1{});
-      return;
-    }
-    start_pass(0);
     if (MID && valid && tj[0] >= 0) k_fetch(0);
     while (tj[0] >= 0) {
-      if constexpr (ONLY16) {
-        iteration(I1{}, I2{});
-      } else if constexpr (VM == 2) {  // four GEMM2 forms in one kernel: no second copy of the loop
-        iteration(I2{}, I2{});
+      // one loop per GEMM2 form, each run over consecutive tiles of its form (a branch around GEMM2
+      // inside one loop makes the compiler move all 64 accumulators per tile; going from one loop
+      // to another costs that move once per change, which the tile order keeps rare)
+      if (!ONLY16 && !hs_map_f16(tv[0])) {  // V tile in bf16 encoding: two terms of P; kind looked at per tile
+        do iteration(I0{}, I2{});
+        while (tj[0] >= 0 && !hs_map_f16(tv[0]));
+      } else if (VM == 2 && tv[0] > 0) {
+        do iteration(I1{}, I1{});
+        while (tj[0] >= 0 && tv[0] > 0 && (ONLY16 || hs_map_f16(tv[0])));
+      } else if (VM == 2) {
+        do iteration(I1{}, I0{});
+        while (tj[0] >= 0 && tv[0] < 0 && (ONLY16 || hs_map_f16(tv[0])));
       } else {
-        if (hs_map_f16(tv[0])) {
-          do iteration(I1{}, I2{});
-          while (tj[0] >= 0 && hs_map_f16(tv[0]));
-        } else {
-          do iteration(I0{}, I2{});
-          while (tj[0] >= 0 && !hs_map_f16(tv[0]));
-        }
+        do iteration(I1{}, I2{});
+        while (tj[0] >= 0 && (ONLY16 || hs_map_f16(tv[0])));
       }
     }
   };
   if constexpr (F16) {
     main_loop(std::integral_constant<bool, MID_OK>{}, std::true_type{});
-  } else if constexpr (MID_OK || VM == 2) {
+  } else if constexpr (MID_OK) {
     // bf16 cache: are all V tiles this workgroup can meet in fp16 encoding?  (every wave scans the
     // same entries, so the workgroup agrees; the answer is scalar)
     bool all16 = true;
