@@ -316,12 +316,14 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     // 2:4 V operands are fetched from LDS before the softmax, unless the K prefetch of MID mode
     // already holds the registers (both together spill; measured no gain there)
     constexpr bool V_EARLY = F16 && VM == 0 && !MID;
-    // One iteration = one tile.  The loop exists twice, for runs of V tiles in fp16 encoding (one fp16
-    // term of P) and in bf16 (two terms), so that each copy is straight-line code around its matrix
+    // One iteration = one tile.  The loop exists once per GEMM2 form (V tile dense or 2:4, one fp16
+    // term of P or two bf16 terms), so that each copy is straight-line code around its matrix
     // instructions and keeps the accumulators where they are (a per-tile branch around GEMM2 made
-    // the compiler move all 64 accumulator registers in and out of the branch).  The encoding is
+    // the compiler move all 64 accumulator registers in and out of the branch).  The form is
     // scalar: map entries come through v_readlane.
-    auto iteration = [&](auto enc, auto vkind) {  // vkind: 0 = V tile 2:4, 1 = dense, 2 = look at the tile  // enc: 0 = bf16 V tile, 1 = fp16-encoded, 2 = look at the tile (mixed dense / 2:4 V)
+    // enc: 0 = V tile in bf16 encoding, 1 = in fp16 encoding; vkind: 0 = V tile 2:4, 1 = dense,
+    // 2 = look at the tile (the tensor has one kind, or the rare bf16-encoded tiles of a mixed one)
+    auto iteration = [&](auto enc, auto vkind) {
       constexpr int kEnc = decltype(enc)::value;
       const int j = tj[0], mk = tk[0], mv = tv[0];
       // END mode: request the tile D ahead now; its stage held the tile of the previous iteration,
@@ -331,7 +333,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
       constexpr int kVK = decltype(vkind)::value;
       const bool v_sparse = kVK == 2 ? (VM == 0 || (VM == 2 && mv < 0)) : kVK == 0;
-      const bool v_f16 = kEnc == 2 ? (F16 || hs_map_f16(mv)) : kEnc == 1;
+      constexpr bool v_f16 = kEnc == 1;
       const uint4* kl = reinterpret_cast<const uint4*>(lds + st * kStage);
       const uint4* vl = reinterpret_cast<const uint4*>(lds + st * kStage + region_bytes<KM>());
       B16 ph[NB], pl[NB];
@@ -422,10 +424,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
             psum[nb] = acc;
           }
         };
-        auto softmax_tile = [&]() {
-          if (kEnc == 2 ? v_f16 : kEnc == 1) softmax_as(std::true_type{});
-          else softmax_as(std::false_type{});
-        };
+        auto softmax_tile = [&]() { softmax_as(std::integral_constant<bool, v_f16>{}); };
         softmax_tile();
         bool redo = false;
 #pragma unroll
