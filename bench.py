@@ -70,7 +70,8 @@ def cpu_baseline(cfg):
                       f"({nbytes / 1e6:.1f} MB packed) {t_d:.2f} s; prune+pack of the whole cache {t_c:.2f} s; "
                       f"causal prefill attention for {n_rows} sampled query rows {t_p:.2f} s "
                       f"({t_p / n_rows * 1e3:.0f} ms per row incl. one unpack of the cache)",
-            "compress_s": t_c, "decode_s": t_d, "prefill_rows": n_rows, "prefill_rows_s": t_p}
+            "compress_s": t_c, "decode_s": t_d, "prefill_rows": n_rows, "prefill_rows_s": t_p,
+            "prefill_full_s_extrapolated": t_p / n_rows * cfg["B"] * cfg["Hq"] * cfg["L"]}
 
 
 def _time(torch, fn, reps, warm=1):
@@ -160,7 +161,9 @@ def extra_legs(hb, torch, Q, K, V, qd, sh, args):
         nb = packed_bytes(B3, Hkv, L3 // 64, c3)
         sweep.append({"case": name3, "decode_us": t * 1e6, "decode_GBps": nb / t / 1e9, "hbm_frac": nb / t / 1e9 / HBM_PEAK_GBPS,
                       "packed_MB": nb / 1e6, "compress_us": t_c * 1e6,
-                      "compress_GBps": (2 * B3 * Hkv * L3 * 128 * 2 + nb) / t_c / 1e9})
+                      "compress_GBps": (2 * B3 * Hkv * L3 * 128 * 2 + nb) / t_c / 1e9,
+                      # floor: K, V read once + packed bytes written once at the HBM peak (a ranked policy reads twice)
+                      "compress_frac_of_single_read_floor": (2 * B3 * Hkv * L3 * 128 * 2 + nb) / (HBM_PEAK_GBPS * 1e9) / t_c})
         del kv3
     for r in sweep:
         r["speedup_vs_dense"] = sweep[0]["decode_us"] / r["decode_us"]
@@ -377,6 +380,18 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     t_dm = e0.elapsed_time(e1) / n_rep * 1e-3
+    # rate of the matrix pipes on this chip, register-resident (no memory, no LDS, no vector-ALU work)
+    sink = torch.zeros(4, dtype=torch.int64, device="cuda")
+    mfma_meas = {}
+    for kind, label in ((0, "dense_16x16x32_bf16"), (1, "sparse_16x16x64_bf16_dense_equiv")):
+        hb.probe_mfma_rate(kind, 2000, sink)
+        e0.record()
+        flop = hb.probe_mfma_rate(kind, 40000, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_meas[label] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        clk = sink.cpu().tolist()
+        mfma_meas[label + "_sustained_GHz"] = clk[0] / max(clk[1], 1) * 0.1
 
     kv_bytes = packed_bytes(B, Hkv, T, counts)
     q_bytes = B * Hq * D * 2
@@ -391,7 +406,9 @@ def main():
         "compress_us": cmp_s * 1e6, "compress_GBps": compress_bytes / cmp_s / 1e9,
         "compress_frac_of_prefill": cmp_s / pre_s,
         "prefill_ms": pre_s * 1e3, "prefill_dense_equiv_TFLOPs": prefill_flops / pre_s / 1e12,
-        "decode_us": dec_s * 1e6, "decode_us_min": float(t_d.min()) * 1e6, "decode_GBps": decode_bytes / dec_s / 1e9,
+        "decode_us": dec_s * 1e6, "decode_us_min": float(t_d.min()) * 1e6, "decode_us_median": float(np.median(t_d)) * 1e6,
+        "prefill_ms_median": float(np.median(t_p)) * 1e3, "compress_us_median": float(np.median(t_c)) * 1e6,
+        "decode_GBps": decode_bytes / dec_s / 1e9,
         "decode_split_kernel_us": dec_split_s * 1e6, "decode_split_kernel_GBps": decode_bytes / dec_split_s / 1e9,
         # back-to-back merge-only calls: bounded by the host's launch rate, not by the 4 us kernel
         # (its own duration is in profiles/bench_cfg1_kernel_trace.md)
@@ -464,7 +481,10 @@ def main():
         "roofline_prefill": {"bound": "mfma", "kernel": "prefill_kernel<0, 0, 2>", "achieved": prefill_flops / pre_s / 1e12,
                              "peak": MFMA_BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": prefill_flops / pre_s / 1e12 / MFMA_BF16_DENSE_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES["prefill"],
-                             "note": "dense-equivalent causal FLOPs over the dense bf16 peak"},
+                             "note": "dense-equivalent causal FLOPs over the dense bf16 peak",
+                             "measured_peak_TFLOPs": mfma_meas,
+                             "frac_of_measured_dense_peak": prefill_flops / pre_s / 1e12 / mfma_meas["dense_16x16x32_bf16"],
+                             "frac_of_measured_sparse_peak": prefill_flops / pre_s / 1e12 / mfma_meas["sparse_16x16x64_bf16_dense_equiv"]},
         "roofline_compress": {"bound": "hbm", "kernel": "pack_kernel", "achieved": compress_bytes / cmp_s / 1e9,
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": compress_bytes / cmp_s / 1e9 / HBM_PEAK_GBPS,
                               "traffic": TRAFFIC_BYTES["compress"]},

@@ -55,6 +55,7 @@ EXPORTS = {
     "hs_decode_attn_tail_rows": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "hs_recompress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(HsKV), C.POINTER(HsKV), C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
     "hs_prefill_attn": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_float, C.c_int, C.c_void_p, C.POINTER(HsKV),
@@ -261,6 +262,14 @@ def recompress_kv(shape, kv, target, counts=None, overflow=None, out=None, works
     a, b = kv.struct(), out.struct()
     _check(lib().hs_recompress_kv(C.byref(shape), C.byref(target), C.byref(a), C.byref(b), _ptr(ws), _ptr(overflow), _stream()))
     return out
+
+
+def probe_mfma_rate(kind, iters, sink):
+    """Launches the register-resident matrix-instruction loop (kind 0 dense, 1 sparse; sink: 4 int64 on the device); returns the
+    dense-equivalent flops of the launch.  Time it with events around the call."""
+    flop = C.c_double(0.0)
+    _check(lib().hs_probe_mfma_rate(int(kind), int(iters), _ptr(sink), C.byref(flop), _stream()))
+    return flop.value
 
 
 def unpack_kv(shape, kv):

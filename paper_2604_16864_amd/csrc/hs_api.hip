@@ -457,6 +457,20 @@ int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_splits, co
   return decode_common(shape, scale, n_splits, Q, kv, tail_k, tail_v, tail_len, nullptr, O, LSE, workspace, stream, 3);
 }
 
+int hs_probe_mfma_rate(int kind, int32_t iters, void* sink, double* flop, void* stream) {
+  if ((kind != 0 && kind != 1) || iters < 1 || sink == nullptr || ((uintptr_t)sink & 7u) || flop == nullptr) return HS_EINVAL;
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return hip_fail(e);
+  const int n_wg = 2 * cus;  // 4 waves each: 2 waves per SIMD
+  e = hs_launch_mfma_rate(kind, iters, n_wg, (long long*)sink, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  // dense-equivalent flops of the launch: 8 instructions per iteration and wave, 2*16*16*K each
+  *flop = (double)n_wg * 4.0 * 8.0 * (double)iters * 2.0 * 16.0 * 16.0 * (kind == 0 ? 32.0 : 64.0);
+  return HS_OK;
+}
+
 int hs_decode_attn_tail_rows(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
                              const void* tail_k, const void* tail_v, const int32_t* tail_lens, void* O, float* LSE,
                              void* workspace, void* stream) {

@@ -151,6 +151,8 @@ hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
                             hs_kv_dev kv, const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, const int32_t* tail_lens,
                             uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases, int dtype);
+// register-resident matrix-instruction loop (kind 0 dense 16x16x32, 1 sparse 16x16x64), 8 * iters instructions per wave
+hipError_t hs_launch_mfma_rate(int kind, int iters, int n_workgroups, long long* sink, hipStream_t st);
 // q_start: position in the cache of the first query (query i sees tokens <= q_start + i when causal)
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, int q_start, float scale, int causal, const uint16_t* Q,
                              hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st, int dtype);
