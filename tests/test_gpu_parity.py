@@ -1030,6 +1030,23 @@ def test_scale_argument_and_large_logits():
         assert_close(_f32(Od), Odr, f"decode large logits scale={scale}")
 
 
+def test_matrix_rate_probe_runs_and_counts_its_work():
+    """The benchmark's register-resident matrix-instruction loop: runs, reports the flops of the launch
+    (2 workgroups per compute unit x 4 waves x 8 instructions x iterations x 2*16*16*K) and the clocks spent."""
+    import ctypes as C
+    sink = torch.zeros(4, dtype=torch.int64, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for kind, k in ((0, 32), (1, 64)):
+        flop = hb.probe_mfma_rate(kind, 500, sink)
+        torch.cuda.synchronize()
+        assert flop == 2 * cus * 4 * 8 * 500 * 2 * 16 * 16 * k
+        clocks, ticks, _, never = sink.cpu().tolist()
+        assert clocks > 500 * 8 * 8 and ticks > 0 and never == 0     # >= 8 clocks per matrix instruction
+    f = C.c_double(0.0)
+    assert hb.lib().hs_probe_mfma_rate(2, 10, sink.data_ptr(), C.byref(f), None) == -1
+    assert hb.lib().hs_probe_mfma_rate(0, 0, sink.data_ptr(), C.byref(f), None) == -1
+
+
 def test_argument_errors_on_device_calls():
     B, Hq, Hkv, L = 1, 4, 1, 256
     Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=150)
