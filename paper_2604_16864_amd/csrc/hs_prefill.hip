@@ -187,10 +187,12 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   const int tid = threadIdx.x, l = tid & 63, a = l >> 4, c = l & 15;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, scalar: branches on it stay scalar
   const int G = Hq / Hkv;
-  const int hkv = blockIdx.y, b = blockIdx.z;
+  // kv head = block index mod Hkv: workgroups go round-robin over the 8 XCDs, so with 8 kv heads (or a
+  // divisor of 8) each XCD's L2 streams the tiles of its own heads only (measured 1-2.5 % faster)
+  const int hkv = blockIdx.x % Hkv, b = blockIdx.z;
   const int n_slabs = (Lq / QS) * G;
   // heavy (late) query positions first: causal work grows with the position
-  const int grp = (int)gridDim.x - 1 - (int)blockIdx.x;
+  const int grp = (int)(gridDim.x / Hkv) - 1 - (int)(blockIdx.x / Hkv);
   const int slab = 4 * grp + w;
   const bool valid = slab < n_slabs;
   const int qpos = valid ? (slab / G) * QS : 0, hg = valid ? slab % G : 0;
@@ -604,10 +606,10 @@ static hipError_t launch_prefill(int B, int Hq, int Hkv, int T, int Lq, int q_st
   const int G = Hq / Hkv;
   const int n_groups = ((Lq / (16 * NB)) * G + 3) / 4;
   if (f16)
-    hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, true>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
+    hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, true>), dim3(n_groups * Hkv, 1, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
                        q_start, sl2, causal, Q, kv, O, LSE);
   else
-    hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, false>), dim3(n_groups, Hkv, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
+    hipLaunchKernelGGL((prefill_kernel<KM, VM, NB, false>), dim3(n_groups * Hkv, 1, B), dim3(256), 0, st, Hq, Hkv, T, Lq,
                        q_start, sl2, causal, Q, kv, O, LSE);
   return hipGetLastError();
 }
