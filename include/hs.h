@@ -234,7 +234,8 @@ HS_API int hs_unpack_kv(const hs_shape* shape, const hs_kv* kv, void* K_out, voi
  * Query i sees token j iff tile(j) is not skipped and (!causal or
  * j <= i + L - Lq).  scale == 0 selects 1/sqrt(D) (Eq. 1).
  * O: bf16 [B, Hq, Lq, D]; LSE: fp32 [B, Hq, Lq] or NULL.  A query that sees no
- * token gets O = 0, LSE = -inf. */
+ * token gets O = 0, LSE = -inf.  A pool of more than 4 GiB per (batch, kv head) row
+ * (capacity x tile bytes) is HS_EUNSUPPORTED. */
 HS_API int hs_prefill_attn(const hs_shape* shape, int32_t Lq, float scale, int causal,
                     const void* Q, const hs_kv* kv, void* O, float* LSE,
                     void* workspace, void* stream);

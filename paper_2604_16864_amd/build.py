@@ -12,7 +12,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-    "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
+    "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-inline-asm",
 ]
 
 

@@ -429,6 +429,12 @@ int hs_prefill_attn_at(const hs_shape* shape, int32_t Lq, int32_t q_start, float
   if (Lq <= 0 || Lq > shape->L) return HS_EINVAL;
   if (q_start < 0 || q_start > shape->L - Lq) return HS_EINVAL;
   if (Lq % HS_BT != 0) return HS_EUNSUPPORTED;
+  // the prefill kernel addresses a tile inside its row's pool with a 32-bit byte offset
+  if ((int64_t)kv->cap_dense_k * HS_TILE_DENSE_BYTES > (int64_t)1 << 32 ||
+      (int64_t)kv->cap_dense_v * HS_TILE_DENSE_BYTES > (int64_t)1 << 32 ||
+      (int64_t)kv->cap_sparse_k * HS_TILE_NNZ_BYTES > (int64_t)1 << 32 ||
+      (int64_t)kv->cap_sparse_v * HS_TILE_NNZ_BYTES > (int64_t)1 << 32)
+    return HS_EUNSUPPORTED;
   if (!(scale >= 0.f)) return HS_EINVAL;
   if (scale == 0.f) scale = 1.0f / sqrtf((float)HS_D);
   const hipError_t e = hs_launch_prefill(shape->B, shape->Hq, shape->Hkv, shape->L / HS_BT, Lq / HS_BT, q_start, scale,

@@ -76,55 +76,99 @@ template <int KM, int VM> constexpr int min_loads_per_tile() { return (KM == 1 ?
 
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// One direct global->LDS load of 64 lanes x 16 B: lane l's bytes come from gbase + 16 l and land
-// at LDS address lds_addr + 16 l.  Written as inline assembly on purpose: the compiler treats
-// the built-in form as a vector-memory write to LDS that any later LDS read may alias, and puts a
-// full vmcnt(0) wait in front of the first such read, i.e. right after the prefetch is issued.
-// Completion is tracked by hand instead (stage_wait + workgroup barrier before a stage is read).
-// gbase and lds_addr are wave-uniform.
-__device__ __forceinline__ void lds_dma16(uint32_t lds_addr, const uint8_t* gbase, uint32_t lane_off) {
-  const uint64_t g = (uint64_t)gbase;
-  const uint32_t glo = __builtin_amdgcn_readfirstlane((uint32_t)g);
-  const uint32_t ghi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
-  const uint64_t gs = ((uint64_t)ghi << 32) | glo;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+// One direct global->LDS load of 64 lanes x 16 B: lane l's bytes come from gbase + voff (voff = 16 l
+// plus the tile's offset in its pool) and land at LDS address lds_addr + IMM + 16 l.  Written as
+// inline assembly on purpose: the compiler treats the built-in form as a vector-memory write to LDS
+// that any later LDS read may alias, and puts a full vmcnt(0) wait in front of the first such read,
+// i.e. right after the prefetch is issued.  Completion is tracked by hand instead (stage_wait +
+// workgroup barrier before a stage is read).  gbase and lds_addr are wave-uniform.
+template <int IMM>
+__device__ __forceinline__ void lds_dma16(uint32_t lds_addr, const uint8_t* gbase, uint32_t voff) {
+  asm volatile("s_add_i32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
                :
-               : "s"(lds_addr), "v"(lane_off), "s"(gs)
-               : "memory", "m0");
+               : "s"(lds_addr), "i"(IMM), "v"(voff), "s"((uint64_t)gbase)
+               : "memory", "m0", "scc");
 }
 
-// Copy one tile (K and V operands) from its pool slots into the LDS stage at LDS address `stage`:
-// a chunk is 64 lanes x 16 B = 1 KiB, stored in the pools in the order the lanes consume it.  The
-// 4 waves share the chunks round-robin.  2:4 tile: 8 value chunks + 1 metadata chunk per tensor
-// (value chunks at 0..8 KiB, metadata at 8 KiB of the tensor's region); dense: 16 chunks.
+__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
+  const uint64_t g = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)g);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
+  return (const uint8_t*)(((uint64_t)hi << 32) | lo);
+}
+
+// Where a wave's copies of a tile come from: the pools of the workgroup's (batch, kv head) row with the
+// wave's share of the 1 KiB chunks folded in (value chunk c of a tile goes to wave c % 4), one
+// pointer per chunk, so that a tile costs one shift-add for its offset in the pool and nothing
+// else per copy.  The per-tile scalar work counts: it is issued by every wave for every tile.
+struct TileSrc {
+  const uint8_t *k_sp[2], *k_meta, *k_dn[4], *v_sp[2], *v_meta, *v_dn[4];
+};
 template <int KM, int VM>
-__device__ __forceinline__ void stage_issue(uint32_t stage, const hs_kv_dev& kv, int64_t row, int mk, int mv, int w,
+__device__ __forceinline__ TileSrc tile_src(const hs_kv_dev& kv, int64_t row, int w) {
+  TileSrc s = {};
+  if (KM != 1) {
+    const uint8_t* b = kv.k_nnz + row * kv.cap_sparse_k * (int64_t)HS_TILE_NNZ_BYTES + w * 1024;
+    s.k_sp[0] = uniform_ptr(b);
+    s.k_sp[1] = uniform_ptr(b + 4096);
+    s.k_meta = uniform_ptr(kv.k_meta + row * kv.cap_sparse_k * (int64_t)HS_TILE_META_BYTES);
+  }
+  if (KM != 0) {
+    const uint8_t* b = kv.k_dense + row * kv.cap_dense_k * (int64_t)HS_TILE_DENSE_BYTES + w * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; i++) s.k_dn[i] = uniform_ptr(b + 4096 * i);
+  }
+  if (VM != 1) {
+    const uint8_t* b = kv.v_nnz + row * kv.cap_sparse_v * (int64_t)HS_TILE_NNZ_BYTES + w * 1024;
+    s.v_sp[0] = uniform_ptr(b);
+    s.v_sp[1] = uniform_ptr(b + 4096);
+    s.v_meta = uniform_ptr(kv.v_meta + row * kv.cap_sparse_v * (int64_t)HS_TILE_META_BYTES);
+  }
+  if (VM != 0) {
+    const uint8_t* b = kv.v_dense + row * kv.cap_dense_v * (int64_t)HS_TILE_DENSE_BYTES + w * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; i++) s.v_dn[i] = uniform_ptr(b + 4096 * i);
+  }
+  return s;
+}
+
+// Copy one tile (K and V operands) from its pool slots into an LDS stage: a chunk is 64 lanes x 16 B =
+// 1 KiB, stored in the pools in the order the lanes consume it.  The 4 waves share the chunks
+// round-robin.  2:4 tile: 8 value chunks + 1 metadata chunk per tensor (value chunks at 0..8 KiB,
+// metadata at 8 KiB of the tensor's region); dense: 16 chunks.  stage_w = LDS address of the stage
+// + 1024 w.  Offsets inside a row's pool are 32-bit (the launcher checks the pool sizes).
+template <int KM, int VM>
+__device__ __forceinline__ void stage_issue(uint32_t stage_w, const TileSrc& src, int mk, int mv, int w,
                                             uint32_t lane_off) {
   const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
   const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
-  mv = hs_map_plain(mv);  // without the encoding bit
-  constexpr uint32_t voff = region_bytes<KM>();
+  constexpr int voff = region_bytes<KM>();
   if (k_sparse) {
-    const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
-    const uint8_t* kd = kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES + w * 1024;
-#pragma unroll
-    for (int i = 0; i < 2; i++) lds_dma16(stage + (w + 4 * i) * 1024, kd + i * 4096, lane_off);
-    if (w == 0) lds_dma16(stage + 8192, kv.k_meta + slot * (int64_t)HS_TILE_META_BYTES, lane_off);
+    const uint32_t slot = (uint32_t)~mk;  // -mk - 1
+    const uint32_t off = lane_off + slot * (uint32_t)HS_TILE_NNZ_BYTES;
+    lds_dma16<0>(stage_w, src.k_sp[0], off);
+    lds_dma16<4096>(stage_w, src.k_sp[1], off);
+    if (w == 0) lds_dma16<8192>(stage_w, src.k_meta, lane_off + slot * (uint32_t)HS_TILE_META_BYTES);
   } else {
-    const uint8_t* kd = kv.k_dense + (row * kv.cap_dense_k + (mk - 1)) * (int64_t)HS_TILE_DENSE_BYTES + w * 1024;
-#pragma unroll
-    for (int i = 0; i < 4; i++) lds_dma16(stage + (w + 4 * i) * 1024, kd + i * 4096, lane_off);
+    const uint32_t off = lane_off + (uint32_t)(mk - 1) * (uint32_t)HS_TILE_DENSE_BYTES;
+    lds_dma16<0>(stage_w, src.k_dn[0], off);
+    lds_dma16<4096>(stage_w, src.k_dn[1], off);
+    lds_dma16<8192>(stage_w, src.k_dn[2], off);
+    lds_dma16<12288>(stage_w, src.k_dn[3], off);
   }
   if (v_sparse) {
-    const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
-    const uint8_t* vd = kv.v_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES + w * 1024;
-#pragma unroll
-    for (int i = 0; i < 2; i++) lds_dma16(stage + voff + (w + 4 * i) * 1024, vd + i * 4096, lane_off);
-    if (w == 1) lds_dma16(stage + voff + 8192, kv.v_meta + slot * (int64_t)HS_TILE_META_BYTES, lane_off);
+    const uint32_t slot = ((uint32_t)(-mv) & 0x3fffffffu) - 1u;  // -mv = slot + 1 (+ the encoding bit)
+    const uint32_t off = lane_off + slot * (uint32_t)HS_TILE_NNZ_BYTES;
+    lds_dma16<voff>(stage_w, src.v_sp[0], off);
+    lds_dma16<voff + 4096>(stage_w, src.v_sp[1], off);
+    // wave 1's metadata chunk lands at the region's 8 KiB: stage_w already carries its 1024
+    if (w == 1) lds_dma16<voff + 8192 - 1024>(stage_w, src.v_meta, lane_off + slot * (uint32_t)HS_TILE_META_BYTES);
   } else {
-    const uint8_t* vd = kv.v_dense + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES + w * 1024;
-#pragma unroll
-    for (int i = 0; i < 4; i++) lds_dma16(stage + voff + (w + 4 * i) * 1024, vd + i * 4096, lane_off);
+    const uint32_t off = lane_off + ((uint32_t)hs_map_plain(mv) - 1u) * (uint32_t)HS_TILE_DENSE_BYTES;
+    lds_dma16<voff>(stage_w, src.v_dn[0], off);
+    lds_dma16<voff + 4096>(stage_w, src.v_dn[1], off);
+    lds_dma16<voff + 8192>(stage_w, src.v_dn[2], off);
+    lds_dma16<voff + 12288>(stage_w, src.v_dn[3], off);
   }
 }
 
@@ -140,6 +184,17 @@ __device__ __forceinline__ void stage_wait(int tiles_in_flight) {
     case 1: __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER)); break;
     default: __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER)); break;
   }
+}
+
+// stage_wait with this wave's own load count per tile: waves 0 and 1 also fetch the metadata chunk of a
+// 2:4 K resp. V tile.  (Waiting by the smallest count of any wave made those two wait for the first
+// load of a tile requested only one iteration ago, and the workgroup with them at the barrier.)  Mixed
+// tensors: the count varies per tile, the smallest is used.
+template <int KM, int VM>
+__device__ __forceinline__ void stage_wait_wave(int tiles_in_flight, int w) {
+  constexpr int base = min_loads_per_tile<KM, VM>();
+  if ((KM == 0 && w == 0) || (VM == 0 && w == 1)) stage_wait<base + 1>(tiles_in_flight);
+  else stage_wait<base>(tiles_in_flight);
 }
 
 union B16 {  // one B operand of the 16x16x64 sparse instruction = two of the dense 16x16x32 one
@@ -200,6 +255,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   const int64_t row = (int64_t)b * Hkv + hkv;
   const int32_t* km = kv.k_map + row * T;
   const int32_t* vm = kv.v_map + row * T;
+  const TileSrc src = tile_src<KM, VM>(kv, row, w);
   // query i (absolute position i + off) sees token j iff j <= i + off; last KV tile this wave /
   // the workgroup may look at, and first tile that needs masking inside
   const int jmax_w = causal ? (qpos + QS - 1 + off) / HS_BT : T - 1;
@@ -236,7 +292,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
   // tj[i]: the i-th visible tile from the current one on (-1: none), tk / tv: its map entries;
   // tile tj[i] sits in (or is on its way to) stage (st + i) % NS.
   int tj[NS], tk[NS], tv[NS];
-  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds);
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)lds) + 1024 * w;
   const uint32_t lane_off = 16 * l;
   // The maps are read 64 tiles at a time, lane t of the window holding the entries of tile
   // wbase + t; entries are picked out with readlane and the next tile is found on a ballot.
@@ -288,7 +344,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
     tk[i] = tv[i] = 0;
     if (tj[i] >= 0) {
       tk[i] = __builtin_amdgcn_readlane(wk, tj[i] - wbase); tv[i] = __builtin_amdgcn_readlane(wv, tj[i] - wbase);
-      stage_issue<KM, VM>(lds_base + i * kStage, kv, row, tk[i], tv[i], w, lane_off);
+      stage_issue<KM, VM>(lds_wave + i * kStage, src, tk[i], tv[i], w, lane_off);
     }
   }
   stage_wait<1>(0);
@@ -309,7 +365,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
       tk[D] = __builtin_amdgcn_readlane(wk, tj[D] - wbase); tv[D] = __builtin_amdgcn_readlane(wv, tj[D] - wbase);
       int sd = st + D;
       if (sd >= NS) sd -= NS;
-      stage_issue<KM, VM>(lds_base + sd * kStage, kv, row, tk[D], tv[D], w, lane_off);
+      stage_issue<KM, VM>(lds_wave + sd * kStage, src, tk[D], tv[D], w, lane_off);
     }
   };
   // mid_tag: MID mode; only16_tag: every V tile ahead is known to be in fp16 encoding
@@ -462,7 +518,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         int later = 0;
 #pragma unroll
         for (int i = 2; i < D; i++) later += tj[i] >= 0;
-        stage_wait<min_loads_per_tile<KM, VM>()>(later);
+        stage_wait_wave<KM, VM>(later, w);
         __syncthreads();
         request();
         if (valid && tj[1] >= 0) {
@@ -530,7 +586,7 @@ __global__ __launch_bounds__(256, NB == 2 ? 2 : 1) void prefill_kernel(int Hq, i
         int later = 0;
 #pragma unroll
         for (int i = 2; i <= D; i++) later += tj[i] >= 0;
-        stage_wait<min_loads_per_tile<KM, VM>()>(later);
+        stage_wait_wave<KM, VM>(later, w);
         __syncthreads();
       }
 #pragma unroll
