@@ -28,8 +28,8 @@ HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_DENSE_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE on this workload (summary, commands and
 # the copy-kernel calibration: profiles/bench_cfg1_hbm_traffic.md).  Only valid for cfg1 with 2:4 on all tiles.
-TRAFFIC_BYTES = {"decode": (36950.25 * 2.000 + 544.0) * 1024, "compress": (65608.8 * 2.000 + 74255.6) * 1024,
-                 "prefill": (711828.0 * 2.000 + 262144.2) * 1024}
+TRAFFIC_BYTES = {"decode": (36975.5 * 2.000 + 544.0) * 1024, "compress": (65636.4 * 2.000 + 74195.6) * 1024,
+                 "prefill": (450005.8 * 2.000 + 278326.2) * 1024}
 
 
 def packed_bytes(B, Hkv, T, counts):
