@@ -1069,6 +1069,10 @@ def test_argument_errors_on_device_calls():
     O = torch.empty_like(Qd)
     assert hb.lib().hs_prefill_attn(C.byref(sh), 100, 0.0, 1, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, None, None) == -2
     assert hb.lib().hs_prefill_attn(C.byref(sh), 512, 0.0, 1, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, None, None) == -1
+    # a pool of more than 4 GiB per (batch, kv head) row: prefill addresses tiles with 32-bit offsets
+    kvs.cap_sparse_v = (1 << 32) // 8192 + 1
+    assert hb.lib().hs_prefill_attn(C.byref(sh), 256, 0.0, 1, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, None, None) == -2
+    kvs = kv.struct()
     # a uniform promise that the capacities contradict
     kvs.cap_sparse_k = 2
     assert hb.lib().hs_decode_attn(C.byref(sh), 0.0, 0, hb._ptr(Qd), C.byref(kvs), hb._ptr(O), None, hb._ptr(O), None) == -1
