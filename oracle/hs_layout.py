@@ -18,6 +18,14 @@ GEMM1 (S^T = K Q^T) has tokens as rows: its D registers hold, for lane group a,
 tokens 16m + 4a + i of row block m.  GEMM2 (O^T = V^T P^T) contracts over tokens
 and takes those registers, unmoved, as its B operand, element 4m + i.  That
 fixes which token each contraction index of GEMM2 means, hence V's token order.
+
+Pins (tests/test_oracle_layout_pins.py, CPU only): an emulation of the two matrix
+instructions, written in the test from the operand semantics above, reads the
+physical bytes chunk by chunk and must reproduce K~ Q^T and V~^T P^T of the
+canonical tile (exact integer data, equality); every order is shown to be a
+permutation; TOKEN_OF_K is re-derived from the lane maps; planted slips (chunk
+order, lane order, index halves, nibble order, token order) turn the checks red.
+No function here is "parity unpinned".
 """
 import numpy as np
 

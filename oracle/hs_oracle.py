@@ -14,7 +14,7 @@ decompressed, masked K~, V~.  So the oracle is that definition written out:
 prune -> pack -> unpack -> plain attention, all in fp64 on the exact values of
 the bf16 inputs.
 
-Pins (tests/test_oracle_*.py): top-2-of-4 invariants over exhaustive small
+Pins (tests/test_oracle_pins.py; tests/test_oracle_layout_pins.py for hs_layout): top-2-of-4 invariants over exhaustive small
 alphabets; pack/unpack bit-exact round trip; pool byte counts and compression
 ratios printed in Sec. III-D; attention special cases against an independent
 library routine (all-dense, masked, token-deleted); decode == last causal row;
@@ -29,18 +29,9 @@ import numpy as np
 
 SKIP, DENSE, SPARSE24 = 0, 1, 2
 
-# A v_map entry of a bf16 cache may carry this bit in its magnitude: the tile's stored values are
-# kept in fp16 encoding (same values; see pack_tensor).  Slot = (|entry| & ~MAP_F16) - 1.
-MAP_F16 = 1 << 30
-
-
 def map_slot(entry):
-    """Pool slot (0-based) named by a non-zero map entry."""
-    return (abs(int(entry)) & ~MAP_F16) - 1
-
-
-def map_is_f16(entry):
-    return bool(abs(int(entry)) & MAP_F16)
+    """Pool slot (0-based) named by a non-zero entry of the signed block index map (Sec. III-B)."""
+    return abs(int(entry)) - 1
 
 
 # ----------------------------------------------------------------------------
@@ -291,11 +282,19 @@ def unpack_v_tile(nnz, meta):
 
 
 class PackedKV:
-    """Canonical packed cache for one tensor (K or V): pools + signed map."""
+    """Canonical packed cache for one tensor (K or V): pools + signed block index map.
 
-    def __init__(self, kind, Bt, D, mp, dense, nnz, meta, dtype="bf16"):
+    map  int32 [B, Hkv, T]: the paper's map (Sec. III-B): +(slot+1) dense pool, -(slot+1) sparse
+         pool, 0 skipped.  Nothing else is folded into it.
+    f16  bool [B, Hkv, T]: a separate per-tile predicate, not part of the paper's format: the
+         tile's stored values are held in the pool in fp16 encoding (see v_tile_f16).  Always
+         False for K and for fp16 caches.
+    """
+
+    def __init__(self, kind, Bt, D, mp, dense, nnz, meta, dtype="bf16", f16=None):
         self.kind, self.Bt, self.D, self.dtype = kind, Bt, D, dtype
         self.map, self.dense, self.nnz, self.meta = mp, dense, nnz, meta
+        self.f16 = np.zeros(mp.shape, dtype=bool) if f16 is None else f16
 
     def nbytes(self):
         """Bytes actually occupied (used slots only) + the map."""
@@ -305,15 +304,20 @@ class PackedKV:
         return nd * tile + ns * (tile // 2 + tile // 16) + 4 * self.map.size
 
 
+def v_tile_f16(stored_bits, v_f16):
+    """The encoding predicate of one V tile, from its stored values (all of a dense tile, the kept
+    ones of a 2:4 tile): True when the cache is bf16 (v_f16) and every stored value is exact in
+    fp16.  Such a tile is kept in fp16 encoding -- the softmax numerators can then enter the
+    second product as one fp16 term (11 significant bits) instead of two bf16 terms.  The values
+    are the same either way; this is a storage choice of this build, outside the paper's format."""
+    return bool(v_f16 and bf16_bits_exact_in_f16(stored_bits).all())
+
+
 def _v_tile_store(stored_bits, v_f16):
-    """Encoding of one V tile's stored values (all of a dense tile, the kept ones of a 2:4 tile):
-    when the cache is bf16 and every stored value is exact in fp16, the tile is kept in fp16
-    encoding -- the softmax numerators can then enter the second product as one fp16 term (11
-    significant bits) instead of two bf16 terms -- and its map entry carries MAP_F16.
-    Returns (bits to store, flag)."""
-    if v_f16 and bf16_bits_exact_in_f16(stored_bits).all():
-        return bf16_bits_to_f16_bits(stored_bits), MAP_F16
-    return stored_bits, 0
+    """(bits to store, encoding predicate) of one V tile."""
+    if v_tile_f16(stored_bits, v_f16):
+        return bf16_bits_to_f16_bits(stored_bits), True
+    return stored_bits, False
 
 
 def pack_tensor(kind, X_bits, mask, state, Bt, v_f16=False):
@@ -324,6 +328,7 @@ def pack_tensor(kind, X_bits, mask, state, Bt, v_f16=False):
     B, H, L, D = X_bits.shape
     T = L // Bt
     mp = build_map(state)
+    f16 = np.zeros(mp.shape, dtype=bool)
     cap_d = max(1, int((state == DENSE).sum(axis=-1).max()))
     cap_s = max(1, int((state == SPARSE24).sum(axis=-1).max()))
     dense = np.zeros((B, H, cap_d, Bt, D), dtype=np.uint16)
@@ -340,8 +345,7 @@ def pack_tensor(kind, X_bits, mask, state, Bt, v_f16=False):
                 tile = X_bits[b, h, t * Bt:(t + 1) * Bt]
                 if m > 0:
                     if kind == "v":
-                        dense[b, h, m - 1], flag = _v_tile_store(tile, v_f16)
-                        mp[b, h, t] = m | flag
+                        dense[b, h, m - 1], f16[b, h, t] = _v_tile_store(tile, v_f16)
                     else:
                         dense[b, h, m - 1] = tile
                 elif m < 0:
@@ -350,9 +354,8 @@ def pack_tensor(kind, X_bits, mask, state, Bt, v_f16=False):
                         nnz[b, h, -m - 1], meta[b, h, -m - 1] = pack_k_tile(tile, tm)
                     else:
                         vals, meta[b, h, -m - 1] = pack_v_tile(tile, tm)
-                        nnz[b, h, -m - 1], flag = _v_tile_store(vals, v_f16)
-                        mp[b, h, t] = -(-m | flag)
-    return PackedKV(kind, Bt, D, mp, dense, nnz, meta)
+                        nnz[b, h, -m - 1], f16[b, h, t] = _v_tile_store(vals, v_f16)
+    return PackedKV(kind, Bt, D, mp, dense, nnz, meta, f16=f16)
 
 
 def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, element_rule="magnitude"):
@@ -381,8 +384,8 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
                     slot = int((p.map[b, h] > 0).sum())
                     if slot >= p.dense.shape[2]:
                         p.dense = np.concatenate([p.dense, np.zeros_like(p.dense[:, :, :1])], axis=2)
-                    p.dense[b, h, slot], flag = _v_tile_store(X[b, h], v_f16)
-                    p.map[b, h, t_b] = (slot + 1) | flag
+                    p.dense[b, h, slot], p.f16[b, h, t_b] = _v_tile_store(X[b, h], v_f16)
+                    p.map[b, h, t_b] = slot + 1
                 else:
                     slot = int((p.map[b, h] < 0).sum())
                     if slot >= p.nnz.shape[2]:
@@ -390,8 +393,8 @@ def append_tile(pk, pv, tile, K_tile_bits, V_tile_bits, state_k, state_v, elemen
                         p.meta = np.concatenate([p.meta, np.zeros_like(p.meta[:, :, :1])], axis=2)
                     pack = pack_k_tile if p.kind == "k" else pack_v_tile
                     vals, p.meta[b, h, slot] = pack(X[b, h], mask[b, h])
-                    p.nnz[b, h, slot], flag = _v_tile_store(vals, v_f16)
-                    p.map[b, h, t_b] = -((slot + 1) | flag)
+                    p.nnz[b, h, slot], p.f16[b, h, t_b] = _v_tile_store(vals, v_f16)
+                    p.map[b, h, t_b] = -(slot + 1)
 
 
 def _sparser(cur, target):
@@ -415,6 +418,7 @@ def recompress(p, target_state, element_rule="magnitude"):
     new = np.array([[[_sparser(int(cur[b, h, t]), int(target_state[b, h, t])) for t in range(T)]
                      for h in range(H)] for b in range(B)], dtype=np.int8).reshape(B, H, T)
     mp = build_map(new)
+    f16 = np.zeros(mp.shape, dtype=bool)
     cap_d = max(1, int((new == DENSE).sum(axis=-1).max()))
     cap_s = max(1, int((new == SPARSE24).sum(axis=-1).max()))
     dense = np.zeros((B, H, cap_d) + p.dense.shape[3:], dtype=np.uint16)
@@ -427,14 +431,14 @@ def recompress(p, target_state, element_rule="magnitude"):
                 m_old, m = int(p.map[b, h, t]), int(mp[b, h, t])
                 if m == 0:
                     continue
-                old_slot, old_flag = map_slot(m_old), abs(m_old) & MAP_F16
+                old_slot, old_flag = map_slot(m_old), bool(p.f16[b, h, t])
                 if m > 0:                                   # DENSE stays DENSE
                     dense[b, h, m - 1] = p.dense[b, h, old_slot]
-                    mp[b, h, t] = m | old_flag
+                    f16[b, h, t] = old_flag
                 elif m_old < 0:                             # SPARSE24 stays SPARSE24
                     nnz[b, h, -m - 1] = p.nnz[b, h, old_slot]
                     meta[b, h, -m - 1] = p.meta[b, h, old_slot]
-                    mp[b, h, t] = -(-m | old_flag)
+                    f16[b, h, t] = old_flag
                 else:                                       # DENSE -> SPARSE24: prune what is stored
                     tile = p.dense[b, h, old_slot]
                     if old_flag:
@@ -445,9 +449,8 @@ def recompress(p, target_state, element_rule="magnitude"):
                     else:
                         tm = element_mask_v(tile[None, None], element_rule)[0, 0]
                         vals, meta[b, h, -m - 1] = pack_v_tile(tile, tm)
-                        nnz[b, h, -m - 1], flag = _v_tile_store(vals, v_f16)
-                        mp[b, h, t] = -(-m | flag)
-    return PackedKV(p.kind, p.Bt, p.D, mp, dense, nnz, meta, dtype=p.dtype)
+                        nnz[b, h, -m - 1], f16[b, h, t] = _v_tile_store(vals, v_f16)
+    return PackedKV(p.kind, p.Bt, p.D, mp, dense, nnz, meta, dtype=p.dtype, f16=f16)
 
 
 def recompress_kv(pk, pv, target_k, target_v, element_rule="magnitude"):
@@ -469,7 +472,7 @@ def unpack_tensor(p):
                 if m == 0:
                     continue
                 slot = map_slot(m)
-                back = f16_bits_to_bf16_bits if map_is_f16(m) else (lambda x: x)
+                back = f16_bits_to_bf16_bits if p.f16[b, h, t] else (lambda x: x)
                 if m > 0:
                     out[b, h, t * p.Bt:(t + 1) * p.Bt] = back(p.dense[b, h, slot])
                 elif p.kind == "k":

@@ -54,9 +54,27 @@ def compress_both(B, Hq, Hkv, L, K, V, dtype="bf16", **pol):
     return sh, kv, pk, pv, info
 
 
+def lib_maps(k_map, v_map):
+    """The library's map arrays as (signed index map of K, signed index map of V, encoding flag of V):
+    a v_map entry of a bf16 cache may carry HS_MAP_F16 in its magnitude, which is not part of the
+    paper's signed index map (Sec. III-B) and is compared on its own."""
+    km = k_map.cpu().numpy()
+    vm = v_map.cpu().numpy().astype(np.int64)
+    mag = np.abs(vm)
+    assert not ((np.abs(km.astype(np.int64)) & hb.MAP_F16) != 0).any()
+    return km, (np.sign(vm) * (mag & ~hb.MAP_F16)).astype(np.int32), (mag & hb.MAP_F16) != 0
+
+
+def assert_maps_equal(kv, pk, pv, sel=None, osel=None):
+    """sel / osel: index into the library's / the oracle's [B, Hkv, T] arrays (default: everything)."""
+    km, vm, flag = lib_maps(kv.k_map if sel is None else kv.k_map[sel], kv.v_map if sel is None else kv.v_map[sel])
+    o = (lambda a: a) if osel is None else (lambda a: a[osel])
+    assert (km == o(pk.map)).all() and (vm == o(pv.map)).all(), "signed index maps"
+    assert (flag == o(pv.f16)).all(), "fp16-encoding predicate of the V tiles"
+
+
 def check_packed_bit_exact(sh, kv, pk, pv):
-    assert (kv.k_map.cpu().numpy() == pk.map).all()
-    assert (kv.v_map.cpu().numpy() == pv.map).all()
+    assert_maps_equal(kv, pk, pv)
     B, H = sh.B, sh.Hkv
     for name, p, dense, nnz, meta, cd, cs in (("k", pk, kv.k_dense, kv.k_nnz, kv.k_meta, kv.counts[1], kv.counts[2]),
                                                ("v", pv, kv.v_dense, kv.v_nnz, kv.v_meta, kv.counts[3], kv.counts[4])):
@@ -380,7 +398,7 @@ def test_decode_cfg3_shape_one_batch_row_skip75():
     batch row, 75 % of the tiles skipped + 2:4 in the rest, default launch configuration."""
     c, q, K, V = wl.make_config("cfg3_decode_b8_128k", B=1)
     sh, kv, pk, pv, info = compress_both(c["B"], c["Hq"], c["Hkv"], c["L"], K, V, skip_frac=0.75)
-    assert (kv.k_map.cpu().numpy() == pk.map).all() and (kv.v_map.cpu().numpy() == pv.map).all()
+    assert_maps_equal(kv, pk, pv)
     assert int((pk.map == 0).sum()) == 8 * 1536
     O, LSE = hb.decode_attn(sh, _dev(q), kv)
     torch.cuda.synchronize()
@@ -409,7 +427,7 @@ def test_decode_cfg3_full_batch_sampled_rows(pol):
         print(f"[cfg3 full batch {sorted(pol)}] row b={b} hkv={h}", flush=True)
         Kb, Vb = hb.bf16_tensor_to_bits(K[b:b + 1, h:h + 1]), hb.bf16_tensor_to_bits(V[b:b + 1, h:h + 1])
         pk, pv, _ = orc.compress_kv(Kb, Vb, Bt=64, **pol)
-        assert (kv.k_map[b, h].cpu().numpy() == pk.map[0, 0]).all() and (kv.v_map[b, h].cpu().numpy() == pv.map[0, 0]).all()
+        assert_maps_equal(kv, pk, pv, sel=(b, h), osel=(0, 0))
         for p, dense, nnz, meta, cd, cs in ((pk, kv.k_dense, kv.k_nnz, kv.k_meta, kv.counts[1], kv.counts[2]),
                                             (pv, kv.v_dense, kv.v_nnz, kv.v_meta, kv.counts[3], kv.counts[4])):
             ph = hl.physical_pools(p)
@@ -442,7 +460,7 @@ def test_selection_on_a_row_longer_than_the_register_cache():
     pol = dict(skip_frac=2 / (T - 4) + 1e-9, sparse_frac_k=0.5, sparse_frac_v=0.7, dense_first_tiles=1, dense_last_tiles=3)
     sh, kv, pk, pv, info = compress_both(B, Hq, Hkv, L, K, V, **pol)
     assert int((pk.map == 0).sum()) == 2 and pk.map[0, 0, 7] == 0 and pk.map[0, 0, 900] == 0 and pk.map[0, 0, 2200] != 0
-    assert (kv.k_map.cpu().numpy() == pk.map).all() and (kv.v_map.cpu().numpy() == pv.map).all()
+    assert_maps_equal(kv, pk, pv)
     Ku, Vu = hb.unpack_kv(sh, kv)
     torch.cuda.synchronize()
     assert (hb.bf16_tensor_to_bits(Ku) == orc.unpack_tensor(pk)).all()
@@ -454,7 +472,7 @@ def test_prefill_cfg4_full_size_skip75_sampled_rows():
     skipped, 2:4 in the rest): seeded sampled rows plus rows that see no token at all."""
     c, Q, K, V = wl.make_config("cfg4_prefill_64k")
     sh, kv, pk, pv, info = compress_both(c["B"], c["Hq"], c["Hkv"], c["L"], K, V, skip_frac=0.75)
-    assert (kv.k_map.cpu().numpy() == pk.map).all() and (kv.v_map.cpu().numpy() == pv.map).all()
+    assert_maps_equal(kv, pk, pv)
     # rows whose own and all earlier tiles are skipped (kv head 0 ... 7): O = 0, LSE = -inf
     extra = []
     for hkv in range(c["Hkv"]):
@@ -711,7 +729,7 @@ def test_chunked_prefill_appends_a_chunk_then_attends_from_its_position():
     torch.cuda.synchronize()
     assert int(ovf.item()) == 1
     assert (small.k_map.cpu().numpy()[0, 0] == [0, 0, 1, 2, 3, 4, 0, 0, 0, 0, 0, 0]).all()
-    assert ((np.abs(small.v_map.cpu().numpy()[1, 1]) & ~orc.MAP_F16) == [0, 0, 1, 2, 3, 4, 0, 0, 0, 0, 0, 0]).all()
+    assert ((np.abs(small.v_map.cpu().numpy()[1, 1]) & ~hb.MAP_F16) == [0, 0, 1, 2, 3, 4, 0, 0, 0, 0, 0, 0]).all()
     import ctypes as C
     kvs = small.struct()
     args = (hb._ptr(Kd), hb._ptr(Vd), None, C.byref(kvs), None, None)
@@ -865,7 +883,7 @@ def test_bf16_cache_with_both_v_tile_encodings(pol, planted):
                     Vf[b, h, 64 * t:64 * t + 64] *= 2.0 ** 18
     V = wl.f32_to_bf16_bits(Vf)                             # exact: powers of two
     sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, **pol)
-    flagged = (np.abs(pv.map.astype(np.int64)) & orc.MAP_F16) != 0
+    flagged = pv.f16
     live = pv.map != 0
     assert (flagged & live).any() and (~flagged & live).any()
     check_packed_bit_exact(sh, kv, pk, pv)
@@ -975,7 +993,7 @@ def test_recompress_capacity_overflow_and_argument_errors():
     assert int(flag.item()) == 1
     assert kv2.k_map.cpu().numpy().reshape(-1).tolist() == [-1, -2, -3, -4, -5, 0, 0, 0]
     vm = kv2.v_map.cpu().numpy().reshape(-1)
-    assert ((np.abs(vm) & ~orc.MAP_F16) == [1, 2, 3, 4, 5, 0, 0, 0]).all() and (vm <= 0).all()
+    assert ((np.abs(vm) & ~hb.MAP_F16) == [1, 2, 3, 4, 5, 0, 0, 0]).all() and (vm <= 0).all()
     flag.zero_()
     hb.recompress_kv(sh, kv, hb.make_policy(), overflow=flag)
     torch.cuda.synchronize()

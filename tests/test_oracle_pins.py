@@ -103,10 +103,10 @@ def test_mixed_states_roundtrip_and_map():
         for h in range(2):
             mp = p.map[0, h]
             assert ((mp == 0) == (st[0, h] == S)).all()
-            signed_slot = np.sign(mp) * (np.abs(mp) & ~orc.MAP_F16)        # V entries may carry the encoding bit
-            assert (signed_slot[st[0, h] == Dn] == np.arange(1, 1 + (st[0, h] == Dn).sum())).all()
-            assert (signed_slot[st[0, h] == Sp] == -np.arange(1, 1 + (st[0, h] == Sp).sum())).all()
-            assert p.kind == "v" or (signed_slot == mp).all()
+            # the paper's signed index map and nothing else: 1-based slots per pool in sequence order
+            assert (mp[st[0, h] == Dn] == np.arange(1, 1 + (st[0, h] == Dn).sum())).all()
+            assert (mp[st[0, h] == Sp] == -np.arange(1, 1 + (st[0, h] == Sp).sum())).all()
+            assert p.kind == "v" or not p.f16.any()
         tile_state = np.repeat(st, 16, axis=-1)[..., None]
         want = np.where(tile_state == Dn, X, np.where(tile_state == Sp, np.where(m, X, 0), 0))
         assert (orc.unpack_tensor(p) == want).all()
@@ -411,14 +411,14 @@ def test_append_in_tile_order_rebuilds_the_one_shot_cache():
     for t in range(3, 7):
         orc.append_tile(pk2, pv2, t, K[:, :, 16 * t:16 * (t + 1)], V[:, :, 16 * t:16 * (t + 1)], int(sk[t]), int(sv[t]))
     for a, b in ((pk1, pk2), (pv1, pv2)):
-        assert (a.map == b.map).all()
+        assert (a.map == b.map).all() and (a.f16 == b.f16).all()
         nd, ns = a.dense.shape[2], a.nnz.shape[2]
         assert (a.dense == b.dense[:, :, :nd]).all() and (a.nnz == b.nnz[:, :, :ns]).all() and (a.meta == b.meta[:, :, :ns]).all()
     assert (orc.unpack_tensor(pk2) == orc.unpack_tensor(pk1)).all()
 
 
 def _same_packed(a, b):
-    assert (a.map == b.map).all()
+    assert (a.map == b.map).all() and (a.f16 == b.f16).all()
     for t in np.argwhere(a.map != 0):
         m = int(a.map[tuple(t)])
         slot = orc.map_slot(m)
@@ -464,7 +464,7 @@ def test_further_pruning_of_a_packed_cache_equals_compressing_with_the_sparser_s
     B_v[skip_b] = 0
     pk, pv, _ = orc.compress_kv(K, V, Bt=Bt, state_k=A_k, state_v=A_v, dtype=dtype)
     if dtype == "bf16":
-        assert not orc.map_is_f16(pv.map[0, 0, 2]) and not orc.map_is_f16(pv.map[0, 0, 3])
+        assert not pv.f16[0, 0, 2] and not pv.f16[0, 0, 3]
     keep = (pk.map.copy(), pk.dense.copy(), pk.nnz.copy())
     rk, rv = orc.recompress_kv(pk, pv, B_k, B_v)
     assert (keep[0] == pk.map).all() and (keep[1] == pk.dense).all() and (keep[2] == pk.nnz).all()   # source untouched
@@ -475,7 +475,7 @@ def test_further_pruning_of_a_packed_cache_equals_compressing_with_the_sparser_s
     _same_packed(rk, ck)
     _same_packed(rv, cv)
     if dtype == "bf16":
-        assert orc.map_is_f16(rv.map[0, 0, 2]) and not orc.map_is_f16(rv.map[0, 0, 3])
+        assert rv.f16[0, 0, 2] and not rv.f16[0, 0, 3]
     # no further pruning asked for: nothing changes
     nk, nv = orc.recompress_kv(pk, pv, np.where(A_k == 0, 0, 1), np.where(A_v == 0, 0, 1))
     _same_packed(nk, pk)
@@ -581,16 +581,17 @@ def test_v_tiles_in_fp16_encoding_hold_the_same_values():
     V[0, 0, 16 + 3, 5] = bf(1e30)
     V[0, 0, 32:36, 7] = [bf(1.0), bf(-2.0), bf(2.0 ** -30), bf(0.5)]
     pk, pv, info = orc.compress_kv(K, V, Bt=16)
-    assert [orc.map_is_f16(m) for m in pv.map[0, 0]] == [True, False, True]
-    assert not any(orc.map_is_f16(m) for m in pk.map[0, 0])
+    assert pv.f16[0, 0].tolist() == [True, False, True]
+    assert not pk.f16.any()
+    assert (pv.map[0, 0] == [-1, -2, -3]).all()                                      # the index map stays the paper's
     assert (orc.unpack_tensor(pv) == np.where(info["mask_v"], V, 0)).all()           # values unchanged either way
     assert (pv.nnz[0, 0, 1] == orc.pack_v_tile(V[0, 0, 16:32], info["mask_v"][0, 0, 16:32])[0]).all()   # tile 1: bf16 bits
     assert (pv.nnz[0, 0, 0] != orc.pack_v_tile(V[0, 0, :16], info["mask_v"][0, 0, :16])[0]).any()       # tile 0: other encoding
     pkd, pvd, _ = orc.compress_kv(K, V, Bt=16, sparse_frac_k=0.0, sparse_frac_v=0.0)
-    assert [orc.map_is_f16(m) for m in pvd.map[0, 0]] == [True, False, False]        # dense: every value is stored
+    assert pvd.f16[0, 0].tolist() == [True, False, False]                            # dense: every value is stored
     assert (orc.unpack_tensor(pvd) == V).all()
     pkh, pvh, _ = orc.compress_kv(K, V, Bt=16, dtype="fp16")
-    assert not any(orc.map_is_f16(m) for m in pvh.map[0, 0])                         # fp16 caches need no flag
+    assert not pvh.f16.any()                                                         # fp16 caches need no flag
 
 
 def test_brute_force_python_floats_tiny():
