@@ -14,8 +14,12 @@
  *     IEEE fp16 (the paper's type), chosen by hs_shape.dtype for all four; "bf16" in the
  *     descriptions below stands for that type.  D (head dim) is contiguous.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
- *     the default stream), except where a call says that it synchronises.  The library allocates nothing, frees nothing and
+ *     the default stream): no call waits for the device, copies from host memory or
+ *     synchronises the stream.  The library allocates nothing, frees nothing and
  *     keeps no pointer after a call returns; the caller owns every buffer.
+ *   - There is no context object: every call is a function of its arguments alone (the
+ *     device is the one `stream` belongs to, which must be the current device), so there is
+ *     nothing to create or destroy.
  *   - Return value: HS_OK (0) or a negative hs_status.  Arguments are checked
  *     on the host before anything is launched; nothing is launched when an
  *     error is returned.  Faults inside a kernel are not recoverable.
@@ -84,9 +88,17 @@ enum { HS_BF16 = 0, HS_FP16 = 1 };
  *   sparse_frac_x  the paper's block sparsity S_K / S_V: of the tiles that are
  *                  kept, floor(S * n_kept) with the lowest pruning loss
  *                  || X * (1 - m) ||_1  (Eq. 2c) are stored 2:4, the rest dense.
- *   state_k/_v     [host] optional explicit per-tile states, int8 [B, Hkv, T];
- *                  when non-NULL (both or neither) they replace the fractions.
- *                  A tile must be SKIP in both or in neither.
+ *   state_k/_v     optional explicit per-tile states (the block-level masks of an external
+ *                  pruner, Sec. III-A), DEVICE int8 [B, Hkv, T], values HS_SKIP / HS_DENSE /
+ *                  HS_SPARSE24; when non-NULL (both or neither) they replace the fractions.
+ *                  A tile must be SKIP in both or in neither.  They are read by a kernel on
+ *                  `stream` and turned into maps there, so a pruner that runs on the device
+ *                  hands them over without a round trip through the host.
+ *   state_flag     optional DEVICE int32 (set to 0 by the caller), written only with explicit
+ *                  states, which the host cannot check: bit 0 = some row needed more slots than
+ *                  a pool of `out` has (the tiles that no longer fit are stored as SKIP in K
+ *                  and V and take no slot), bit 1 = a state pair was not valid (value outside
+ *                  0..2, or SKIP in only one tensor; the tile is stored as SKIP).
  *   dense_first_tiles, dense_last_tiles
  *                  the first / last so many tiles of every row stay DENSE in K and V and
  *                  take no part in either ranking (the "sink" and "local window" tokens
@@ -106,6 +118,7 @@ typedef struct {
   double sparse_frac_v;
   const int8_t* state_k;
   const int8_t* state_v;
+  int32_t* state_flag;
   int32_t dense_first_tiles;
   int32_t dense_last_tiles;
   int32_t element_rule;
@@ -142,9 +155,10 @@ HS_API const char* hs_strerror(int status);
 /* Text of the last HIP error this thread saw inside the library. [host] */
 HS_API const char* hs_last_hip_error(void);
 
-/* Tile counts a policy yields per (b, kv head): counts[0..4] = n_skip,
- * n_dense_k, n_sparse_k, n_dense_v, n_sparse_v.  With explicit states the
- * counts are the per-row maxima.  These are the pool capacities to allocate.
+/* Tile counts a fraction policy yields per (b, kv head): counts[0..4] = n_skip,
+ * n_dense_k, n_sparse_k, n_dense_v, n_sparse_v.  These are the pool capacities to allocate.
+ * With explicit states (device memory) the host cannot count: HS_EUNSUPPORTED; the caller sizes
+ * each pool for the largest per-row count it may produce (L / 64 is always enough).
  * [host, pure] */
 HS_API int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_t counts[5]);
 
@@ -154,7 +168,8 @@ HS_API int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_
 HS_API int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t bytes[8]);
 
 /* Workspace bytes needed by each call.  [host, pure]
- *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto), 3 re-compress */
+ *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto), 3 re-compress
+ *   (ops 1 and 3 need none: 0 bytes, the workspace argument of those calls may be NULL) */
 HS_API int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes);
 
 /* Number of KV splits hs_decode_attn uses when n_splits == 0. [host, pure] */
@@ -166,10 +181,9 @@ HS_API int hs_decode_auto_splits(const hs_shape* shape);
  * magnitudes of every 4 consecutive channels of a token, V of every 4
  * consecutive tokens of a channel (magnitude = bits & 0x7fff, ties to the lower
  * position; with HS_RULE_NONZERO the key is magnitude != 0 instead).  Writes maps and pools of `out`; slots beyond the used count are
- * left untouched.  workspace: hs_workspace_bytes(op 0).
- * With explicit states the maps are built on the host, copied over, and the stream is
- * synchronised once before the pack kernel is launched; fraction policies run without a
- * synchronisation. */
+ * left untouched.  workspace: hs_workspace_bytes(op 0), 8-byte aligned (tile scores; only read
+ * and written when the policy ranks tiles).  Capacities of `out` that a fraction policy would
+ * exceed are HS_EINVAL; with explicit states see hs_policy.state_flag. */
 HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],
                    const hs_kv* out, void* workspace, void* stream);
@@ -213,15 +227,17 @@ HS_API int hs_append_tile_rows(const hs_shape* shape, const int32_t* tiles, int3
  * 2:4 is pruned from the values it stores (element rule of `target`), a tile that becomes SKIP is
  * dropped; slots of `dst` are handed out again in tile order, one counter per pool (Sec. III-B).
  * The result equals hs_compress_kv of the original tensors with those states, bit for bit.
- * target: explicit states (host arrays, as for hs_compress_kv), or whole-tensor fractions --
+ * target: explicit states (device arrays, as for hs_compress_kv; target->state_flag is not used),
+ * or whole-tensor fractions --
  * skip_frac == 0 and sparse_frac_k, sparse_frac_v each 0 or 1, with dense_first_tiles /
  * dense_last_tiles kept DENSE; other fractions would need a ranking of packed data:
  * HS_EUNSUPPORTED.
  * src, dst: distinct caches of the same shape (no overlap); dst's capacities are the caller's
- * choice: a tile whose slot lies beyond one of them is left SKIP in K and V and `overflow` (device
- * int32, set to 0 by the caller; may be NULL) is set to 1.  dst->uniform is not read.
- * workspace: hs_workspace_bytes(op 3) device bytes.  Synchronises the stream once (upload of the
- * target states) before its two launches. */
+ * choice: a tile for which one of its pools has no slot left when its turn comes (tile order) is
+ * left SKIP in K and V, takes no slot in either pool -- the used slots of a pool stay 0 .. n-1, so
+ * hs_append_tile can go on from there -- and bit 0 of `overflow` (device int32, set to 0 by the
+ * caller; may be NULL) is set.  Bit 1 is set if an explicit target pair was not valid (such a tile
+ * keeps its state).  dst->uniform is not read.  workspace: not used, may be NULL. */
 HS_API int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv* src, const hs_kv* dst,
                      void* workspace, int32_t* overflow, void* stream);
 
@@ -279,26 +295,6 @@ HS_API int hs_decode_attn_tail(const hs_shape* shape, float scale, int32_t n_spl
 HS_API int hs_decode_attn_tail_rows(const hs_shape* shape, float scale, int32_t n_splits,
                              const void* Q, const hs_kv* kv, const void* tail_k, const void* tail_v,
                              const int32_t* tail_lens, void* O, float* LSE, void* workspace, void* stream);
-
-/* hs_decode_attn in separable phases, for benchmarking and profiling: `phases` bit 0 launches
- * the split-KV kernel (reads Q and the cache, writes the partials into `workspace`), bit 1
- * launches the merge kernel (reads the partials, writes O and LSE).  phases == 3 is
- * hs_decode_attn; phases == 1 lets a caller time the kernel that streams the cache on its own
- * (back-to-back launches between two events).  Everything else as hs_decode_attn. */
-HS_API int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_splits,
-                          const void* Q, const hs_kv* kv, void* O, float* LSE,
-                          void* workspace, void* stream, int phases);
-
-/* Benchmark support: launches a register-resident loop of matrix instructions (kind 0: the dense
- * 16x16x32 bf16 form, 1: the 2:4 sparse 16x16x64 bf16 form that prefill and decode use) on every
- * compute unit, two waves per SIMD, no memory traffic, so that a caller can time it between two
- * events and set the attention kernels against the rate the matrix pipes reach on the chip at
- * hand, next to the published peak.  *flop [host] receives the dense-equivalent floating-point
- * operations of the launch (the sparse form counts the multiplications its dense equivalent
- * would do).  sink: 32 device bytes, 8-byte aligned; the first two int64 receive the shader
- * clocks and the constant-rate 100 MHz ticks one wave spent in the loop (their ratio is the clock
- * the chip sustained).  Asynchronous on `stream`. */
-HS_API int hs_probe_mfma_rate(int kind, int32_t iters, void* sink, double* flop, void* stream);
 
 #ifdef __cplusplus
 }

@@ -453,11 +453,45 @@ def recompress(p, target_state, element_rule="magnitude"):
     return PackedKV(p.kind, p.Bt, p.D, mp, dense, nnz, meta, dtype=p.dtype, f16=f16)
 
 
-def recompress_kv(pk, pv, target_k, target_v, element_rule="magnitude"):
-    """recompress for K and V together; a tile is dropped from both or from neither."""
+def fit_states_to_capacity(state_k, state_v, caps):
+    """Walk the blocks of every row in sequence order with the pools' running counters
+    (Sec. III-B): a block is stored only if the pool its K state names and the pool its V state
+    names both still have a free slot; otherwise it is left out of K and V alike and takes no
+    slot.  caps = (dense K, sparse K, dense V, sparse V) slots per row.  Returns the states that
+    are actually stored and whether anything was left out."""
+    sk, sv = np.array(state_k, dtype=np.int8), np.array(state_v, dtype=np.int8)
+    B, H, T = sk.shape
+    dropped = False
+    for b in range(B):
+        for h in range(H):
+            n = {("k", DENSE): 0, ("k", SPARSE24): 0, ("v", DENSE): 0, ("v", SPARSE24): 0}
+            cap = {("k", DENSE): caps[0], ("k", SPARSE24): caps[1], ("v", DENSE): caps[2], ("v", SPARSE24): caps[3]}
+            for t in range(T):
+                a, c = int(sk[b, h, t]), int(sv[b, h, t])
+                if a == SKIP:
+                    continue
+                if n["k", a] < cap["k", a] and n["v", c] < cap["v", c]:
+                    n["k", a] += 1
+                    n["v", c] += 1
+                else:
+                    sk[b, h, t] = sv[b, h, t] = SKIP
+                    dropped = True
+    return sk, sv, dropped
+
+
+def recompress_kv(pk, pv, target_k, target_v, element_rule="magnitude", caps=None):
+    """recompress for K and V together; a tile is dropped from both or from neither.
+    caps: optional pool capacities of the result (see fit_states_to_capacity); then the third
+    return value says whether a tile was left out for lack of room."""
     target_k, target_v = np.asarray(target_k), np.asarray(target_v)
     assert ((target_k == SKIP) == (target_v == SKIP)).all()
-    return recompress(pk, target_k, element_rule), recompress(pv, target_v, element_rule)
+    if caps is None:
+        return recompress(pk, target_k, element_rule), recompress(pv, target_v, element_rule)
+    cur_k = np.where(pk.map > 0, DENSE, np.where(pk.map < 0, SPARSE24, SKIP))
+    cur_v = np.where(pv.map > 0, DENSE, np.where(pv.map < 0, SPARSE24, SKIP))
+    merge = np.vectorize(_sparser)
+    new_k, new_v, dropped = fit_states_to_capacity(merge(cur_k, target_k), merge(cur_v, target_v), caps)
+    return recompress(pk, new_k, element_rule), recompress(pv, new_v, element_rule), dropped
 
 
 def unpack_tensor(p):
@@ -484,7 +518,7 @@ def unpack_tensor(p):
 
 def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0,
                 state_k=None, state_v=None, dense_first_tiles=0, dense_last_tiles=0, element_rule="magnitude",
-                dtype="bf16"):
+                dtype="bf16", caps=None):
     """Whole compress step: element masks, tile states (policy or explicit),
     maps, pools.  Returns (PackedKV for K, PackedKV for V, dict of intermediates).
     dtype names the 16-bit format of the patterns; it matters for the tile scores and for
@@ -505,6 +539,8 @@ def compress_kv(K_bits, V_bits, Bt=64, skip_frac=0.0, sparse_frac_k=1.0, sparse_
     state_k = np.asarray(state_k, dtype=np.int8)
     state_v = np.asarray(state_v, dtype=np.int8)
     assert ((state_k == SKIP) == (state_v == SKIP)).all(), "a skipped tile removes its tokens from K and V alike"
+    if caps is not None:     # pools of a given size: blocks that find no free slot are left out (Sec. III-B counters)
+        state_k, state_v, info["dropped"] = fit_states_to_capacity(state_k, state_v, caps)
     info.update(state_k=state_k, state_v=state_v)
     pk = pack_tensor("k", K_bits, mk, state_k, Bt)
     pv = pack_tensor("v", V_bits, mv, state_v, Bt, v_f16=(dtype == "bf16"))

@@ -27,7 +27,7 @@ class HsShape(C.Structure):
 
 class HsPolicy(C.Structure):
     _fields_ = [("skip_frac", C.c_double), ("sparse_frac_k", C.c_double), ("sparse_frac_v", C.c_double),
-                ("state_k", C.c_void_p), ("state_v", C.c_void_p),
+                ("state_k", C.c_void_p), ("state_v", C.c_void_p), ("state_flag", C.c_void_p),
                 ("dense_first_tiles", C.c_int32), ("dense_last_tiles", C.c_int32), ("element_rule", C.c_int32)]
 
 
@@ -131,21 +131,56 @@ RULE_MAGNITUDE, RULE_NONZERO = 0, 1
 
 
 def make_policy(skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0, state_k=None, state_v=None,
-                dense_first_tiles=0, dense_last_tiles=0, element_rule=RULE_MAGNITUDE):
-    """state_k/state_v: optional host int8 arrays [B, Hkv, T].  The returned object
-    keeps them alive."""
-    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None,
+                dense_first_tiles=0, dense_last_tiles=0, element_rule=RULE_MAGNITUDE, device="cuda"):
+    """state_k/state_v: optional explicit tile states [B, Hkv, T]: int8 device tensors (handed to the
+    library as they are), or host arrays -- a convenience of this binding: they are checked here (the
+    library cannot read them on the host), copied to the device, and their per-row counts are kept
+    for tile_counts.  The returned object keeps the device tensors alive and owns the library's
+    device-side flag for explicit states (`state_flag`, see check_state_flag)."""
+    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None, None,
                  int(dense_first_tiles), int(dense_last_tiles), int(element_rule))
     if state_k is not None:
-        sk = np.ascontiguousarray(state_k, dtype=np.int8)
-        sv = np.ascontiguousarray(state_v, dtype=np.int8)
-        p.state_k = sk.ctypes.data
-        p.state_v = sv.ctypes.data
-        p._keep = (sk, sv)
+        if torch.is_tensor(state_k):
+            sk, sv = state_k, state_v
+            assert sk.dtype == torch.int8 and sv.dtype == torch.int8 and sk.is_cuda and sv.is_cuda
+            assert sk.is_contiguous() and sv.is_contiguous() and sk.shape == sv.shape
+            p._host_counts = None
+        else:
+            hk = np.ascontiguousarray(state_k, dtype=np.int8)
+            hv = np.ascontiguousarray(state_v, dtype=np.int8)
+            if hk.shape != hv.shape or hk.min() < 0 or hk.max() > 2 or hv.min() < 0 or hv.max() > 2 \
+                    or ((hk == SKIP) != (hv == SKIP)).any():
+                raise HsError("explicit tile states: values must be SKIP / DENSE / SPARSE24 and a tile must be "
+                              "skipped in K and V alike")
+            n = [int((a == v).sum(-1).max()) for a, v in ((hk, SKIP), (hk, DENSE), (hk, SPARSE24), (hv, DENSE), (hv, SPARSE24))]
+            p._host_counts = n
+            sk, sv = torch.from_numpy(hk).to(device), torch.from_numpy(hv).to(device)
+        flag = torch.zeros(1, dtype=torch.int32, device=sk.device)
+        p.state_k, p.state_v, p.state_flag = sk.data_ptr(), sv.data_ptr(), flag.data_ptr()
+        p._keep = (sk, sv, flag)
     return p
 
 
+def check_state_flag(policy):
+    """Reads the device flag that calls with explicit states raise (this synchronises): raises if a
+    pool capacity was exceeded or a state pair was not valid; clears the flag."""
+    if not policy.state_k:
+        return
+    flag = policy._keep[2]
+    v = int(flag.item())
+    flag.zero_()
+    if v:
+        raise HsError("explicit tile states: " + " and ".join(
+            m for b, m in ((1, "a row needed more slots than a pool has (those tiles were stored as SKIP)"),
+                           (2, "a state pair was not valid (those tiles were stored as SKIP)")) if v & b))
+
+
 def tile_counts(shape, policy):
+    """Pool capacities per (b, kv head) row for a policy.  Explicit states given as host arrays: their
+    per-row maxima; given as device tensors: the always-sufficient T per pool."""
+    if policy.state_k:
+        T = shape.L // TILE
+        return list(policy._host_counts) if policy._host_counts is not None else [0, T, T, T, T]
     c = (C.c_int32 * 5)()
     _check(lib().hs_tile_counts(C.byref(shape), C.byref(policy), c))
     return list(c)
@@ -258,9 +293,9 @@ def recompress_kv(shape, kv, target, counts=None, overflow=None, out=None, works
     # slot == tile survives when nothing was skipped before and each tensor ends up in one kind
     out.uniform = int(bool(kv.uniform) and not target.state_k and counts[1] * counts[2] == 0 and counts[3] * counts[4] == 0
                       and max(counts[1], counts[2]) == T and max(counts[3], counts[4]) == T)
-    ws = _workspace(workspace_bytes(shape, 3), kv.k_map.device) if workspace is None else workspace
     a, b = kv.struct(), out.struct()
-    _check(lib().hs_recompress_kv(C.byref(shape), C.byref(target), C.byref(a), C.byref(b), _ptr(ws), _ptr(overflow), _stream()))
+    _check(lib().hs_recompress_kv(C.byref(shape), C.byref(target), C.byref(a), C.byref(b), _ptr(workspace), _ptr(overflow),
+                                  _stream()))
     return out
 
 

@@ -3,9 +3,8 @@
 #include <stdio.h>
 #include <string.h>
 
-#include <vector>
-
 #include "hs_common.h"
+#include "hs_bench.h"
 
 namespace {
 
@@ -58,26 +57,6 @@ int check_policy(const hs_policy* p) {
     if (p->dense_first_tiles < 0 || p->dense_last_tiles < 0) return HS_EINVAL;
   }
   if (p->element_rule != HS_RULE_MAGNITUDE && p->element_rule != HS_RULE_NONZERO) return HS_EINVAL;
-  return HS_OK;
-}
-
-// Explicit states: validate and count (per-row maxima).
-int explicit_counts(const hs_shape* s, const hs_policy* p, int32_t c[5]) {
-  const int T = s->L / HS_BT;
-  const int64_t rows = (int64_t)s->B * s->Hkv;
-  for (int i = 0; i < 5; i++) c[i] = 0;
-  for (int64_t r = 0; r < rows; r++) {
-    int n[5] = {0, 0, 0, 0, 0};
-    for (int t = 0; t < T; t++) {
-      const int sk = p->state_k[r * T + t], sv = p->state_v[r * T + t];
-      if (sk < 0 || sk > 2 || sv < 0 || sv > 2) return HS_EINVAL;
-      if ((sk == HS_SKIP) != (sv == HS_SKIP)) return HS_EINVAL;
-      n[0] += sk == HS_SKIP;
-      n[1] += sk == HS_DENSE; n[2] += sk == HS_SPARSE24;
-      n[3] += sv == HS_DENSE; n[4] += sv == HS_SPARSE24;
-    }
-    for (int i = 0; i < 5; i++) c[i] = n[i] > c[i] ? n[i] : c[i];
-  }
   return HS_OK;
 }
 
@@ -154,7 +133,8 @@ int hs_tile_counts(const hs_shape* shape, const hs_policy* policy, int32_t count
   rc = check_policy(policy);
   if (rc != HS_OK) return rc;
   if (counts == nullptr) return HS_EINVAL;
-  if (policy->state_k != nullptr) return explicit_counts(shape, policy, counts);
+  // explicit states live on the device: their counts are the caller's to know (at most T per pool)
+  if (policy->state_k != nullptr) return HS_EUNSUPPORTED;
   policy_counts(shape->L / HS_BT, policy, counts);
   return HS_OK;
 }
@@ -205,7 +185,7 @@ int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes
       *bytes = (size_t)shape->B * shape->Hq * (size_t)n * (HS_D + 1) * sizeof(float);
       return HS_OK;
     }
-    case 3: *bytes = (2 * rows * T + 15) / 16 * 16; return HS_OK;
+    case 3: *bytes = 0; return HS_OK;
     default: return HS_EINVAL;
   }
 }
@@ -229,34 +209,13 @@ int hs_compress_kv(const hs_shape* shape, const hs_policy* policy, const void* K
   int32_t c[5];
   hipError_t e;
   int uni_k = 0, uni_v = 0;
-  // maps from per-tile states known on the host: walk the tiles in order with one counter per
-  // pool (Sec. III-B) and copy the result over (synchronously: the host vectors die at return)
-  auto maps_from_states = [&](const int8_t* sk_all, const int8_t* sv_all, int64_t row_stride) -> int {
-    std::vector<int32_t> mk((size_t)rows * T), mv((size_t)rows * T);
-    for (int r = 0; r < rows; r++) {
-      int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
-      for (int t = 0; t < T; t++) {
-        const size_t i = (size_t)r * T + t;
-        const int sk = sk_all[r * row_stride + t], sv = sv_all[r * row_stride + t];
-        mk[i] = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
-        mv[i] = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
-      }
-    }
-    hipError_t err = hipMemcpyAsync(out->k_map, mk.data(), mk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-    if (err != hipSuccess) return hip_fail(err);
-    err = hipMemcpyAsync(out->v_map, mv.data(), mv.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
-    if (err != hipSuccess) return hip_fail(err);
-    err = hipStreamSynchronize(s);
-    if (err != hipSuccess) return hip_fail(err);
-    return HS_OK;
-  };
   if (policy->state_k != nullptr) {
-    rc = explicit_counts(shape, policy, c);
-    if (rc != HS_OK) return rc;
-    if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
-      return HS_EINVAL;
-    rc = maps_from_states(policy->state_k, policy->state_v, T);
-    if (rc != HS_OK) return rc;
+    // states -> maps on the device (prefix counts = the sequential counters of Sec. III-B); what the host
+    // cannot see (a state pair that is not valid, a row that needs more slots than a pool has) is reported
+    // through policy->state_flag and such tiles are stored as SKIP
+    if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
+    e = hs_launch_states_to_maps(policy->state_k, policy->state_v, rows, T, hs_make_kv_dev(out), policy->state_flag, s);
+    if (e != hipSuccess) return hip_fail(e);
   } else {
     policy_counts(T, policy, c);
     if (c[1] > out->cap_dense_k || c[2] > out->cap_sparse_k || c[3] > out->cap_dense_v || c[4] > out->cap_sparse_v)
@@ -359,43 +318,24 @@ int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv
   if (rc != HS_OK) return rc;
   rc = check_kv(shape, dst);
   if (rc != HS_OK) return rc;
-  if (workspace == nullptr) return HS_EINVAL;
+  (void)workspace;
   if (src->k_map == dst->k_map || src->v_map == dst->v_map) return HS_EINVAL;  // not in place: slots move
   const int T = shape->L / HS_BT;
-  const int64_t rows = (int64_t)shape->B * shape->Hkv;
-  // target states on the host; [0, rows*T) keys, [rows*T, 2*rows*T) values
-  std::vector<int8_t> tgt((size_t)(2 * rows * T));
-  int8_t* tk = tgt.data();
-  int8_t* tv = tgt.data() + rows * T;
-  if (target->state_k != nullptr) {
-    int32_t c[5];
-    rc = explicit_counts(shape, target, c);  // validates the values and that K and V skip together
-    if (rc != HS_OK) return rc;
-    memcpy(tk, target->state_k, (size_t)(rows * T));
-    memcpy(tv, target->state_v, (size_t)(rows * T));
-  } else {
+  if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
+  int n_first = 0, n_last = 0, fk = HS_DENSE, fv = HS_DENSE;
+  if (target->state_k == nullptr) {
     // without a ranking only whole-tensor targets are defined: S in {0, 1}, nothing skipped
     if (target->skip_frac != 0.0) return HS_EUNSUPPORTED;
     if ((target->sparse_frac_k != 0.0 && target->sparse_frac_k != 1.0) ||
         (target->sparse_frac_v != 0.0 && target->sparse_frac_v != 1.0))
       return HS_EUNSUPPORTED;
-    int n_first, n_last;
     protected_tiles(T, target, &n_first, &n_last);
-    for (int64_t r = 0; r < rows; r++)
-      for (int t = 0; t < T; t++) {
-        const bool prot = t < n_first || t >= T - n_last;
-        tk[r * T + t] = prot || target->sparse_frac_k == 0.0 ? HS_DENSE : HS_SPARSE24;
-        tv[r * T + t] = prot || target->sparse_frac_v == 0.0 ? HS_DENSE : HS_SPARSE24;
-      }
+    fk = target->sparse_frac_k == 0.0 ? HS_DENSE : HS_SPARSE24;
+    fv = target->sparse_frac_v == 0.0 ? HS_DENSE : HS_SPARSE24;
   }
-  hipStream_t s = (hipStream_t)stream;
-  hipError_t e = hipMemcpyAsync(workspace, tgt.data(), tgt.size(), hipMemcpyHostToDevice, s);
-  if (e != hipSuccess) return hip_fail(e);
-  e = hipStreamSynchronize(s);  // the host vector dies at return
-  if (e != hipSuccess) return hip_fail(e);
-  e = hs_launch_recompress(shape->B, shape->Hkv, T, hs_make_kv_dev(src), (const int8_t*)workspace,
-                           (const int8_t*)workspace + rows * T, hs_make_kv_dev(dst), target->element_rule,
-                           shape->dtype == HS_BF16, overflow, s);
+  const hipError_t e = hs_launch_recompress(shape->B, shape->Hkv, T, hs_make_kv_dev(src), target->state_k, target->state_v,
+                                            fk, fv, n_first, n_last, hs_make_kv_dev(dst), target->element_rule,
+                                            shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

@@ -317,6 +317,103 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
   }
 }
 
+// ----------------------------------------------------------------------------------
+// Slot assignment for one row from known tile states (the two sequential counters per tensor of
+// Sec. III-B): tile t in state (sk, sv) = state(t) takes the next slot of the pool each state names.
+// A tile is stored only if both of its pools still have a free slot when its turn comes; otherwise
+// it is left out of K and V alike, takes no slot in either pool (so the used slots of a pool are
+// always 0 .. count-1 with no holes, which is what appending relies on), and bit 0 of *flag is set.
+// state(t) must return a consistent pair (both SKIP or neither).  emit(t, mk, mv) receives the map
+// entries +-(slot + 1) or 0.  One workgroup of 256 threads per row; each thread owns a contiguous
+// run of tiles.  When everything fits (the totals say so) the slots are prefix counts; a row that
+// overflows is walked again by one thread, in order, so that which tiles survive is exactly what a
+// sequential walk gives.
+// ----------------------------------------------------------------------------------
+struct SlotShared {
+  int wsum[4];
+  int total[4];
+};
+
+template <class State, class Emit>
+__device__ __forceinline__ void assign_slots_row(int T, int tid, int cap_dk, int cap_sk, int cap_dv, int cap_sv,
+                                                 SlotShared& sm, int32_t* flag, State state, Emit emit) {
+  const int per = (T + 255) / 256;
+  const int t0 = min(tid * per, T), t1 = min(t0 + per, T);
+  int n[4] = {0, 0, 0, 0};  // dense K, 2:4 K, dense V, 2:4 V
+  for (int t = t0; t < t1; t++) {
+    int sk, sv;
+    state(t, sk, sv);
+    n[0] += sk == HS_DENSE; n[1] += sk == HS_SPARSE24; n[2] += sv == HS_DENSE; n[3] += sv == HS_SPARSE24;
+  }
+  int base[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    base[i] = block_exclusive_scan(n[i], sm.wsum, tid);
+    if (tid == 255) sm.total[i] = base[i] + n[i];
+  }
+  __syncthreads();
+  const bool all_fit = sm.total[0] <= cap_dk && sm.total[1] <= cap_sk && sm.total[2] <= cap_dv && sm.total[3] <= cap_sv;
+  if (all_fit) {
+    for (int t = t0; t < t1; t++) {
+      int sk, sv;
+      state(t, sk, sv);
+      const int mk = sk == HS_DENSE ? ++base[0] : (sk == HS_SPARSE24 ? -(++base[1]) : 0);
+      const int mv = sv == HS_DENSE ? ++base[2] : (sv == HS_SPARSE24 ? -(++base[3]) : 0);
+      emit(t, mk, mv);
+    }
+  } else if (tid == 0) {
+    int c[4] = {0, 0, 0, 0};
+    bool dropped = false;
+    for (int t = 0; t < T; t++) {
+      int sk, sv;
+      state(t, sk, sv);
+      int mk = 0, mv = 0;
+      if (sk != HS_SKIP) {
+        const bool room_k = sk == HS_DENSE ? c[0] < cap_dk : c[1] < cap_sk;
+        const bool room_v = sv == HS_DENSE ? c[2] < cap_dv : c[3] < cap_sv;
+        if (room_k && room_v) {
+          mk = sk == HS_DENSE ? ++c[0] : -(++c[1]);
+          mv = sv == HS_DENSE ? ++c[2] : -(++c[3]);
+        } else {
+          dropped = true;
+        }
+      }
+      emit(t, mk, mv);
+    }
+    if (dropped && flag != nullptr) atomicOr(flag, 1);
+  }
+}
+
+// Explicit per-tile states (device int8 [rows, T], the block-level masks a pruner hands over:
+// Sec. III-A, "agnostic to the pruning algorithms") -> signed index maps (Sec. III-B).  A pair of
+// states that is not valid (a value outside SKIP / DENSE / SPARSE24, or a tile skipped in only one
+// of K and V) is stored as SKIP in both tensors and sets bit 1 of *flag.
+__global__ __launch_bounds__(256) void states_to_maps_kernel(const int8_t* __restrict__ state_k,
+                                                             const int8_t* __restrict__ state_v, int T, int cap_dk,
+                                                             int cap_sk, int cap_dv, int cap_sv,
+                                                             int32_t* __restrict__ k_map, int32_t* __restrict__ v_map,
+                                                             int32_t* flag) {
+  __shared__ SlotShared sm;
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int8_t* sk_row = state_k + (int64_t)row * T;
+  const int8_t* sv_row = state_v + (int64_t)row * T;
+  int32_t* km = k_map + (int64_t)row * T;
+  int32_t* vm = v_map + (int64_t)row * T;
+  bool invalid = false;
+  assign_slots_row(
+      T, tid, cap_dk, cap_sk, cap_dv, cap_sv, sm, flag,
+      [&](int t, int& sk, int& sv) {
+        sk = sk_row[t];
+        sv = sv_row[t];
+        if (sk < 0 || sk > 2 || sv < 0 || sv > 2 || (sk == HS_SKIP) != (sv == HS_SKIP)) {
+          invalid = true;
+          sk = sv = HS_SKIP;
+        }
+      },
+      [&](int t, int mk, int mv) { km[t] = mk; vm[t] = mv; });
+  if (invalid && flag != nullptr) atomicOr(flag, 2);
+}
+
 // Appending (Sec. III-B counters): map entries of tiles [tile, tile + n_tiles) of every row = the
 // next slots of the pool their state names, counted from how many tiles of that kind the row
 // holds; tiles for which a pool has no slot left stay skipped and raise *overflow.  One workgroup
@@ -567,54 +664,50 @@ __device__ __forceinline__ int sparser_state(int map_entry, int target) {
 }
 
 // Maps of the re-compressed cache: slots in ascending tile order with one counter per pool
-// (Sec. III-B); a tile that keeps its kind keeps its encoding bit.  A tile whose K or V slot
-// lies beyond the capacity of dst is left out of both tensors and *overflow is raised.
-// One workgroup per row, each thread owns a contiguous chunk of tiles.
+// (Sec. III-B); a tile that keeps its kind keeps its encoding bit.  A tile for which a pool of dst
+// has no slot left is left out of both tensors, takes no slot, and bit 0 of *overflow is raised
+// (assign_slots_row).  Target of tile t: tgt_k / tgt_v (device int8 [rows, T]) when given -- a
+// pair that is not valid leaves the tile as it is and raises bit 1 -- else DENSE for the n_first
+// first and n_last last tiles of the row and frac_state_k / frac_state_v in between.
+// One workgroup per row.
 __global__ __launch_bounds__(256) void restate_kernel(int T, hs_kv_dev src, const int8_t* __restrict__ tgt_k,
-                                                      const int8_t* __restrict__ tgt_v, hs_kv_dev dst,
+                                                      const int8_t* __restrict__ tgt_v, int frac_state_k,
+                                                      int frac_state_v, int n_first, int n_last, hs_kv_dev dst,
                                                       int32_t* overflow) {
-  __shared__ int part[4][256];
+  __shared__ SlotShared sm;
   const int row = blockIdx.x, tid = threadIdx.x;
   const int32_t* skm = src.k_map + (int64_t)row * T;
   const int32_t* svm = src.v_map + (int64_t)row * T;
   int32_t* km = const_cast<int32_t*>(dst.k_map) + (int64_t)row * T;
   int32_t* vm = const_cast<int32_t*>(dst.v_map) + (int64_t)row * T;
-  const int8_t* tk = tgt_k + (int64_t)row * T;
-  const int8_t* tv = tgt_v + (int64_t)row * T;
-  const int per = (T + 255) / 256;
-  const int t0 = min(tid * per, T), t1 = min(t0 + per, T);
-  int ndk = 0, nsk = 0, ndv = 0, nsv = 0;
-  for (int t = t0; t < t1; t++) {
-    const int sk = sparser_state(skm[t], tk[t]), sv = sparser_state(svm[t], tv[t]);
-    ndk += sk == HS_DENSE; nsk += sk == HS_SPARSE24; ndv += sv == HS_DENSE; nsv += sv == HS_SPARSE24;
-  }
-  part[0][tid] = ndk; part[1][tid] = nsk; part[2][tid] = ndv; part[3][tid] = nsv;
-  __syncthreads();
-  if (tid < 4) {
-    int acc = 0;
-    for (int i = 0; i < 256; i++) { const int v = part[tid][i]; part[tid][i] = acc; acc += v; }
-  }
-  __syncthreads();
-  ndk = part[0][tid]; nsk = part[1][tid]; ndv = part[2][tid]; nsv = part[3][tid];
-  for (int t = t0; t < t1; t++) {
-    const int mk_old = skm[t], mv_old = svm[t];
-    const int sk = sparser_state(mk_old, tk[t]), sv = sparser_state(mv_old, tv[t]);
-    int mk = sk == HS_DENSE ? ++ndk : (sk == HS_SPARSE24 ? -(++nsk) : 0);
-    int mv = sv == HS_DENSE ? ++ndv : (sv == HS_SPARSE24 ? -(++nsv) : 0);
-    const bool fits = (mk > 0 ? mk <= dst.cap_dense_k : -mk <= dst.cap_sparse_k) &&
-                      (mv > 0 ? mv <= dst.cap_dense_v : -mv <= dst.cap_sparse_v);
-    if (!fits || mk == 0 || mv == 0) {
-      if (mk != 0 || mv != 0) {
-        if (!fits && overflow != nullptr) *overflow = 1;
-      }
-      mk = 0;
-      mv = 0;
-    } else if ((mv > 0) == (mv_old > 0) && hs_map_f16(mv_old)) {
-      mv = mv > 0 ? (mv | HS_MAP_F16) : -(-mv | HS_MAP_F16);
-    }
-    km[t] = mk;
-    vm[t] = mv;
-  }
+  bool invalid = false;
+  assign_slots_row(
+      T, tid, dst.cap_dense_k, dst.cap_sparse_k, dst.cap_dense_v, dst.cap_sparse_v, sm, overflow,
+      [&](int t, int& sk, int& sv) {
+        int tk, tv;
+        if (tgt_k != nullptr) {
+          tk = tgt_k[(int64_t)row * T + t];
+          tv = tgt_v[(int64_t)row * T + t];
+          if (tk < 0 || tk > 2 || tv < 0 || tv > 2 || (tk == HS_SKIP) != (tv == HS_SKIP)) {
+            invalid = true;
+            tk = tv = HS_DENSE;  // no further pruning of this tile
+          }
+        } else {
+          const bool prot = t < n_first || t >= T - n_last;
+          tk = prot ? HS_DENSE : frac_state_k;
+          tv = prot ? HS_DENSE : frac_state_v;
+        }
+        sk = sparser_state(skm[t], tk);
+        sv = sparser_state(svm[t], tv);
+        if (sk == HS_SKIP || sv == HS_SKIP) sk = sv = HS_SKIP;  // a tile leaves K and V together
+      },
+      [&](int t, int mk, int mv) {
+        const int mv_old = svm[t];
+        if (mv != 0 && (mv > 0) == (mv_old > 0) && hs_map_f16(mv_old)) mv = mv > 0 ? (mv | HS_MAP_F16) : -(-mv | HS_MAP_F16);
+        km[t] = mk;
+        vm[t] = mv;
+      });
+  if (invalid && overflow != nullptr) atomicOr(overflow, 2);
 }
 
 // One workgroup per tile: tiles that keep their kind are copied slot to slot; a dense tile that
@@ -820,9 +913,19 @@ hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, in
   return hipGetLastError();
 }
 
+hipError_t hs_launch_states_to_maps(const int8_t* state_k, const int8_t* state_v, int rows, int T, hs_kv_dev kv,
+                                    int32_t* flag, hipStream_t st) {
+  hipLaunchKernelGGL(states_to_maps_kernel, dim3(rows), dim3(256), 0, st, state_k, state_v, T, kv.cap_dense_k,
+                     kv.cap_sparse_k, kv.cap_dense_v, kv.cap_sparse_v, const_cast<int32_t*>(kv.k_map),
+                     const_cast<int32_t*>(kv.v_map), flag);
+  return hipGetLastError();
+}
+
 hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,
-                                hs_kv_dev dst, int rule, int v_f16, int32_t* overflow, hipStream_t st) {
-  hipLaunchKernelGGL(restate_kernel, dim3(B * Hkv), dim3(256), 0, st, T, src, tgt_k, tgt_v, dst, overflow);
+                                int frac_state_k, int frac_state_v, int n_first, int n_last, hs_kv_dev dst, int rule,
+                                int v_f16, int32_t* overflow, hipStream_t st) {
+  hipLaunchKernelGGL(restate_kernel, dim3(B * Hkv), dim3(256), 0, st, T, src, tgt_k, tgt_v, frac_state_k, frac_state_v,
+                     n_first, n_last, dst, overflow);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(repack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, Hkv, T, src, dst, rule, v_f16);

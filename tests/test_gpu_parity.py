@@ -50,6 +50,7 @@ def compress_both(B, Hq, Hkv, L, K, V, dtype="bf16", **pol):
     policy = hb.make_policy(**lib_pol)
     kv = hb.compress_kv(sh, policy, _dev(K, dtype), _dev(V, dtype))
     torch.cuda.synchronize()
+    hb.check_state_flag(policy)          # explicit states: nothing left out, every pair valid
     pk, pv, info = orc.compress_kv(K, V, Bt=64, dtype=dtype, **pol)
     return sh, kv, pk, pv, info
 
@@ -393,6 +394,28 @@ def test_prefill_cfg2_full_size_sampled_rows():
     assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill cfg2 lse")
 
 
+@pytest.mark.parametrize("pol", [dict(), dict(sparse_frac_k=0.0, sparse_frac_v=1.0)])
+def test_prefill_on_the_benchmark_workload_full_size_sampled_rows(pol):
+    """Causal prefill on the inputs the benchmark's step times (L = 32768, keys with outlier channels, which
+    drive the lazily renewed softmax reference through its redo path), all tiles 2:4 and keys dense /
+    values 2:4: 160 seeded rows plus the first and last row and the rows around the first tile edge."""
+    c = wl.CONFIGS["cfg1_decode_llama8b_32k"]
+    B, Hq, Hkv, L = c["B"], c["Hq"], c["Hkv"], c["L"]
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, c["D"], L, c["seed"], c["k_outliers"])
+    rows = wl.sample_rows(B, Hq, L, 160, seed=c["seed"] + 4,
+                          extra=[(0, 0, 0), (0, Hq - 1, L - 1), (0, 7, 63), (0, 7, 64), (0, 13, L - 65)])
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv = hb.compress_kv(sh, hb.make_policy(**pol), _dev(K), _dev(V))
+    O, LSE = hb.prefill_attn(sh, _dev(Q), kv)
+    torch.cuda.synchronize()
+    pk, pv, _ = orc.compress_kv(K, V, **pol)
+    assert_maps_equal(kv, pk, pv)
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    assert_close(_f32(O)[idx], Or, f"prefill benchmark workload {sorted(pol)}")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill benchmark workload lse")
+
+
 def test_decode_cfg3_shape_one_batch_row_skip75():
     """Hierarchical decode sweep workload (L = 131072, 32/8 heads) at its full context for one
     batch row, 75 % of the tiles skipped + 2:4 in the rest, default launch configuration."""
@@ -407,7 +430,8 @@ def test_decode_cfg3_shape_one_batch_row_skip75():
     assert_lse_close(LSE.cpu().numpy(), Lr, "decode cfg3 lse")
 
 
-@pytest.mark.parametrize("pol", [dict(skip_frac=0.25), dict(sparse_frac_k=0.0, sparse_frac_v=1.0)])
+@pytest.mark.parametrize("pol", [dict(skip_frac=0.25), dict(skip_frac=0.5), dict(skip_frac=0.75),
+                                 dict(sparse_frac_k=0.0, sparse_frac_v=1.0)])
 def test_decode_cfg3_full_batch_sampled_rows(pol):
     """The hierarchical decode workload at its full size (B = 8, L = 131072: 4.3 GB of K and V, pools past
     2^31 bytes), default launch configuration.  Inputs are drawn on the device (seeded); the oracle
@@ -791,6 +815,120 @@ def test_random_shapes_and_policies(seed):
     assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode lse " + what)
 
 
+def test_explicit_states_on_the_device_run_with_no_host_wait():
+    """A pruner that leaves its block-level masks on the device (Sec. III-A: the compressor takes the
+    masks M as an input): compress with those states, causal prefill and decode are issued back to
+    back on one stream with no host synchronisation in between (the states are produced by device
+    work queued just before), and match the oracle."""
+    B, Hq, Hkv, T = 2, 8, 2, 13
+    L = 64 * T
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=300, k_outliers=True)
+    sk, sv = _mixed_states(B, Hkv, T, seed=301, p_skip=0.2)
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    Kd, Vd, Qd = _dev(K), _dev(V), _dev(Q)
+    qd = _dev(Q[:, :, -1, :].copy())
+    kv = hb.PackedKV(sh, [0, T, T, T, T])
+    kv.uniform = 0
+    stream = torch.cuda.Stream()
+    stage = torch.from_numpy(np.stack([sk, sv])).cuda()          # uploaded before the stream work starts
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        # the "pruner": device work that produces the states on the same stream
+        sk_d = (stage[0] + 0).contiguous()
+        sv_d = (stage[1] + 0).contiguous()
+        pol = hb.make_policy(state_k=sk_d, state_v=sv_d)
+        hb.compress_kv(sh, pol, Kd, Vd, out=kv)
+        O, LSE = hb.prefill_attn(sh, Qd, kv)
+        Od, LSEd = hb.decode_attn(sh, qd, kv, n_splits=3)
+    stream.synchronize()
+    hb.check_state_flag(pol)
+    pk, pv, _ = orc.compress_kv(K, V, state_k=sk, state_v=sv)
+    check_packed_bit_exact(sh, kv, pk, pv)
+    rows = wl.sample_rows(B, Hq, L, 150, seed=302, extra=[(0, 0, 0), (B - 1, Hq - 1, L - 1)])
+    Or, Lr = orc.attention_rows(Q, pk, pv, rows, causal=True)
+    idx = tuple(np.array(rows).T)
+    assert_close(_f32(O)[idx], Or, "prefill after device-state compress")
+    assert_lse_close(LSE.cpu().numpy()[idx], Lr, "prefill after device-state compress lse")
+    Odr, Ldr = orc.attention_decode(Q[:, :, -1, :].copy(), pk, pv)
+    assert_close(_f32(Od), Odr, "decode after device-state compress")
+    assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode after device-state compress lse")
+
+
+def test_explicit_states_into_pools_that_are_too_small():
+    """Pools with fewer slots than the states ask for: the tiles that find no slot when their turn comes
+    are left out of K and V, take no slot, and the flag goes up; the oracle walks the same counters."""
+    B, Hq, Hkv, T = 2, 4, 2, 11
+    L = 64 * T
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=310)
+    sk, sv = _mixed_states(B, Hkv, T, seed=311, p_skip=0.1)
+    caps = (2, 3, 3, 2)
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv = hb.PackedKV(sh, [0, *caps])
+    kv.uniform = 0
+    pol = hb.make_policy(state_k=sk, state_v=sv)
+    hb.compress_kv(sh, pol, _dev(K), _dev(V), out=kv)
+    torch.cuda.synchronize()
+    with pytest.raises(hb.HsError, match="more slots"):
+        hb.check_state_flag(pol)
+    pk, pv, info = orc.compress_kv(K, V, state_k=sk, state_v=sv, caps=caps)
+    assert info["dropped"]
+    check_packed_bit_exact(sh, kv, pk, pv)
+    q = Q[:, :, 0, :].copy()
+    O, LSE = hb.decode_attn(sh, _dev(q), kv, n_splits=2)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, pk, pv)
+    assert_close(_f32(O), Or, "decode over capacity-limited pools")
+
+
+def test_recompress_into_small_pools_then_append():
+    """Further pruning into pools that are too small, then an append: the dropped tiles took no slot, so
+    the appended tile gets a slot that no live tile uses (slots stay 0 .. n-1 per pool)."""
+    B, Hq, Hkv, T = 2, 4, 2, 10
+    L = 64 * T
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=320)
+    # source: keys dense, values mixed; the last two tiles not filled yet
+    sk = np.full((B, Hkv, T), orc.DENSE, dtype=np.int8)
+    _, sv = _mixed_states(B, Hkv, T, seed=321, p_skip=0.0)
+    sk[:, :, 8:], sv[:, :, 8:] = 0, 0
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, state_k=sk, state_v=sv)
+    tk = np.full((B, Hkv, T), orc.SPARSE24, dtype=np.int8)
+    tv = np.full((B, Hkv, T), orc.SPARSE24, dtype=np.int8)
+    caps = (0, 5, 0, 7)                                      # 5 key slots for 8 tiles
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kv2 = hb.recompress_kv(sh, kv, hb.make_policy(state_k=tk, state_v=tv), counts=[0, *caps], overflow=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 1
+    rk, rv, dropped = orc.recompress_kv(pk, pv, tk, tv, caps=caps)
+    assert dropped
+    check_packed_bit_exact(sh, kv2, rk, rv)
+    assert (np.abs(rv.map).max(axis=-1) == 5).all()          # V holds 5 tiles too: the dropped ones took no V slot
+    # append tile 8 as dense K? no dense pool: 2:4 K is full -> stays skipped, flag; V-only room does not help
+    flag.zero_()
+    Kd, Vd = _dev(K), _dev(V)
+    hb.append_tile(sh, kv2, 8, Kd[:, :, 512:576].contiguous(), Vd[:, :, 512:576].contiguous(), overflow=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 1 and (kv2.k_map[:, :, 8].cpu().numpy() == 0).all()
+    # with room for one more key tile the append takes slot 5 (the 6th) in K and in V
+    kv3 = hb.recompress_kv(sh, kv, hb.make_policy(state_k=tk, state_v=tv), counts=[0, 0, 6, 0, 7])
+    rk3, rv3, _ = orc.recompress_kv(pk, pv, tk, tv, caps=(0, 6, 0, 7))
+    # drop two tiles by hand so that room appears: recompress again towards a target that skips tiles 0, 1
+    tk2, tv2 = tk.copy(), tv.copy()
+    tk2[:, :, :2], tv2[:, :, :2] = 0, 0
+    kv4 = hb.recompress_kv(sh, kv3, hb.make_policy(state_k=tk2, state_v=tv2), counts=[0, 0, 6, 0, 7])
+    rk4, rv4, _ = orc.recompress_kv(rk3, rv3, tk2, tv2, caps=(0, 6, 0, 7))
+    hb.append_tile(sh, kv4, 8, Kd[:, :, 512:576].contiguous(), Vd[:, :, 512:576].contiguous(), overflow=flag)
+    orc.append_tile(rk4, rv4, 8, K[:, :, 512:576], V[:, :, 512:576], orc.SPARSE24, orc.SPARSE24)
+    torch.cuda.synchronize()
+    check_packed_bit_exact(sh, kv4, rk4, rv4)
+    live = rk4.map[0, 0][rk4.map[0, 0] != 0]
+    assert sorted((-live).tolist()) == list(range(1, live.size + 1))       # every slot used once
+    q = Q[:, :, 0, :].copy()
+    O, LSE = hb.decode_attn(sh, _dev(q), kv4, n_splits=2)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, rk4, rv4)
+    assert_close(_f32(O), Or, "decode after recompress into small pools + append")
+
+
 # ------------------------------------------------------------------ fp16 (the paper's element type)
 # fp16 output rounding alone is 8x finer than bf16's, so the same bars leave more room; the values checked
 # are the same ones as for bf16.
@@ -1074,11 +1212,21 @@ def test_argument_errors_on_device_calls():
     kv = hb.PackedKV(sh, hb.tile_counts(sh, hb.make_policy()))
     with pytest.raises(hb.HsError):
         hb.compress_kv(sh, hb.make_policy(sparse_frac_k=0.5), Kd, Vd, out=kv)
-    # explicit states: a tile skipped in K only is inconsistent
+    # explicit states: a tile skipped in K only is inconsistent.  Host arrays are checked by the binding;
+    # states that are already on the device are checked by the kernel that turns them into maps: the tile
+    # is stored as SKIP and bit 1 of the policy's flag goes up
     sk = np.array([[[2, 0, 2, 2]]], dtype=np.int8)
-    sv = np.array([[[2, 2, 2, 2]]], dtype=np.int8)
+    sv = np.array([[[2, 2, 2, 7]]], dtype=np.int8)
     with pytest.raises(hb.HsError):
-        hb.compress_kv(sh, hb.make_policy(state_k=sk, state_v=sv), Kd, Vd, out=kv)
+        hb.make_policy(state_k=sk, state_v=sv)
+    pol_dev = hb.make_policy(state_k=torch.from_numpy(sk).cuda(), state_v=torch.from_numpy(sv).cuda())
+    kv.uniform = 0
+    hb.compress_kv(sh, pol_dev, Kd, Vd, out=kv)
+    torch.cuda.synchronize()
+    assert kv.k_map.cpu().numpy().reshape(-1).tolist() == [-1, 0, -2, 0]
+    assert (np.abs(kv.v_map.cpu().numpy().reshape(-1)) & ~hb.MAP_F16).tolist() == [1, 0, 2, 0]
+    with pytest.raises(hb.HsError, match="not valid"):
+        hb.check_state_flag(pol_dev)
     kv = hb.compress_kv(sh, hb.make_policy(), Kd, Vd)
     # Lq not a multiple of the tile, Lq > L
     import ctypes as C

@@ -21,7 +21,7 @@ def L():
 
 
 def test_exports_every_declared_symbol(L):
-    hdr = open(os.path.join(ROOT, "include", "hs.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include"))))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(hs_[a-z_0-9]+)\s*\(", hdr))
     assert {"hs_compress_kv", "hs_prefill_attn", "hs_decode_attn", "hs_unpack_kv"} <= declared
@@ -110,5 +110,8 @@ def test_argument_errors(L):
     assert L.hs_prefill_attn(C.byref(ok), 64, 0.0, 1, None, C.byref(kv), None, None, None, None) == -1
     assert L.hs_compress_kv(C.byref(ok), C.byref(pol), None, None, None, C.byref(kv), None, None) == -1
     assert L.hs_strerror(-2).decode().startswith("unsupported")
+    # explicit states are device memory: the host cannot count them
+    pol_s = hb.HsPolicy(0.0, 1.0, 1.0, 16, 16, None, 0, 0, 0)
+    assert L.hs_tile_counts(C.byref(ok), C.byref(pol_s), c) == -2
     assert hb.workspace_bytes(ok, 2, 4) == 1 * 4 * 4 * 129 * 4
     assert hb.decode_auto_splits(ok) == 4

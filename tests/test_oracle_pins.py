@@ -493,6 +493,45 @@ def test_further_pruning_of_a_packed_cache_equals_compressing_with_the_sparser_s
     assert orc.to_f64(orc.unpack_tensor(hv2), dtype)[0, 0, :4, 5].tolist() == [0.0, 4.0, 0.0, -8.0]
 
 
+def test_pools_of_a_given_size_keep_the_blocks_that_find_a_slot_in_sequence_order():
+    """Sec. III-B counters with bounded pools, by hand: 2 dense-K, 2 sparse-K, 3 dense-V, 1 sparse-V slots.
+    A block needs a slot in its K pool and in its V pool; one that finds either full is left out of both
+    and takes no slot, so later blocks of the other kind still fit and the used slots have no holes."""
+    D_, S_, X_ = orc.DENSE, orc.SPARSE24, orc.SKIP
+    sk = np.array([[[D_, S_, D_, D_, S_, X_, S_, D_]]], dtype=np.int8)
+    sv = np.array([[[D_, S_, D_, D_, S_, X_, D_, S_]]], dtype=np.int8)
+    #   t0 K dense 1/2, V dense 1/3      kept
+    #   t1 K sparse 1/2, V sparse 1/1    kept
+    #   t2 K dense 2/2, V dense 2/3      kept
+    #   t3 K dense: full                 dropped (its V dense slot is not taken)
+    #   t4 V sparse: full                dropped (its K sparse slot is not taken)
+    #   t5 skipped
+    #   t6 K sparse 2/2, V dense 3/3     kept
+    #   t7 K dense: full                 dropped
+    nk, nv, dropped = orc.fit_states_to_capacity(sk, sv, (2, 2, 3, 1))
+    assert dropped
+    assert nk[0, 0].tolist() == [D_, S_, D_, X_, X_, X_, S_, X_]
+    assert nv[0, 0].tolist() == [D_, S_, D_, X_, X_, X_, D_, X_]
+    assert orc.build_map(nk)[0, 0].tolist() == [1, -1, 2, 0, 0, 0, -2, 0]
+    assert orc.build_map(nv)[0, 0].tolist() == [1, -1, 2, 0, 0, 0, 3, 0]
+    same_k, same_v, dropped = orc.fit_states_to_capacity(sk, sv, (4, 3, 4, 3))
+    assert not dropped and (same_k == sk).all() and (same_v == sv).all()
+    # through the whole compressor and through further pruning: same survivors, and an append goes on
+    # from the used counts
+    K, V = _rand_kv(21, B=1, H=1, L=16 * 8, D=16)
+    pk, pv, info = orc.compress_kv(K, V, Bt=16, state_k=sk, state_v=sv, caps=(2, 2, 3, 1))
+    assert info["dropped"] and pk.map[0, 0].tolist() == [1, -1, 2, 0, 0, 0, -2, 0]
+    fk, fv, _ = orc.compress_kv(K, V, Bt=16, state_k=np.where(sk == X_, X_, D_), state_v=np.where(sv == X_, X_, D_))
+    rk, rv, dropped = orc.recompress_kv(fk, fv, sk, sv, caps=(2, 2, 3, 1))
+    assert dropped
+    _same_packed(rk, pk)
+    _same_packed(rv, pv)
+    orc.append_tile(rk, rv, 5, K[:, :, 16 * 5:16 * 6], V[:, :, 16 * 5:16 * 6], S_, D_)
+    assert rk.map[0, 0, 5] == -3 and rv.map[0, 0, 5] == 4                  # next free slots: no slot is handed out twice
+    slots = sorted(abs(int(m)) for m in rk.map[0, 0] if m < 0)
+    assert slots == [1, 2, 3]
+
+
 def test_batch_rows_of_different_length_equal_separate_sequences():
     """Sequences of a batch differ in length: per-row tail lengths in decode and per-row append positions
     give, row by row, what each sequence gives on its own (the one-sequence forms are pinned above)."""
