@@ -46,7 +46,8 @@ typedef enum {
   HS_OK = 0,
   HS_EINVAL = -1,       /* null pointer, bad fraction, inconsistent states, capacity too small */
   HS_EUNSUPPORTED = -2, /* D != 128, tile != 64, L % 64 != 0, Hq % Hkv != 0, group size > 8 ... */
-  HS_EHIP = -3          /* a HIP runtime call failed; hs_last_hip_error() has the text */
+  HS_EHIP = -3,         /* a HIP runtime call failed; hs_last_hip_error() has the text */
+  HS_ENOSPACE = -4      /* hs_decode_attn_static: the split partials would not fit the static array */
 } hs_status;
 
 /* Tile states (Sec. III-A block-level mask M, plus SKIP). */
@@ -274,6 +275,22 @@ HS_API int hs_prefill_attn_at(const hs_shape* shape, int32_t Lq, int32_t q_start
 HS_API int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits,
                    const void* Q, const hs_kv* kv, void* O, float* LSE,
                    void* workspace, void* stream);
+
+/* hs_decode_attn for callers that cannot allocate device memory or be handed a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as hs_decode_attn, without the workspace: the split partials go to a fixed array of
+ * HS_STATIC_SCRATCH_BYTES (4 MiB) that the library holds in device memory on every GPU it is
+ * loaded on, for the life of the process.  The call allocates and frees nothing (no hipMalloc,
+ * hipFree or allocating library routine); the first call on a device looks the array's address up
+ * once (hipGetSymbolAddress), so make that first call outside a graph capture.
+ * If hs_workspace_bytes(op 2, n_splits) exceeds HS_STATIC_SCRATCH_BYTES: HS_ENOSPACE, nothing
+ * launched (B * Hq * n_splits * 516 bytes; the benchmark shapes need 0.5 MiB).
+ * All calls on one GPU share the one array: two calls that overlap in time on different streams of
+ * the same GPU race on it; calls on one stream are ordered and safe.  The array keeps the last
+ * call's partials; every entry a call reads it has written itself, so nothing needs clearing. */
+enum { HS_STATIC_SCRATCH_BYTES = 4 << 20 };
+HS_API int hs_decode_attn_static(const hs_shape* shape, float scale, int32_t n_splits,
+                          const void* Q, const hs_kv* kv, void* O, float* LSE, void* stream);
 
 /* Decode attention over the packed cache plus a dense tail: the tokens generated since the
  * last full tile was compressed are not in the pools yet; they are attended to as they are

@@ -64,6 +64,8 @@ EXPORTS = {
                                      C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_decode_attn": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_decode_attn_static": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
+                                        C.c_void_p, C.c_void_p]),
     "hs_append_tile": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
     "hs_decode_attn_tail": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
@@ -368,6 +370,19 @@ def decode_attn(shape, Q, kv, scale=0.0, n_splits=0, want_lse=True, out=None, ls
         _check(lib().hs_decode_attn_phases(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(O),
                                            _ptr(lse), _ptr(workspace), _stream(), int(phases)))
     return O, lse
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def decode_attn_static(shape, Q, kv, scale=0.0, n_splits=0, out=None, lse=None):
+    """hs_decode_attn_static: decode attention whose split partials live in the library's static device
+    array.  out (bf16 [B, Hq, D]) and lse (fp32 [B, Hq] or None) are the caller's: nothing is allocated."""
+    assert Q.dtype == torch_dtype(shape) and Q.is_contiguous() and Q.is_cuda and out is not None
+    kvs = kv.struct()
+    _check(lib().hs_decode_attn_static(C.byref(shape), float(scale), int(n_splits), _ptr(Q), C.byref(kvs), _ptr(out),
+                                       _ptr(lse), _stream()))
+    return out, lse
 
 
 def bits_to_bf16_tensor(bits, device="cuda", dtype=torch.bfloat16):

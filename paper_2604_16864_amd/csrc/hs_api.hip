@@ -121,6 +121,7 @@ const char* hs_strerror(int status) {
     case HS_EINVAL: return "invalid argument";
     case HS_EUNSUPPORTED: return "unsupported shape or option";
     case HS_EHIP: return "HIP runtime error";
+    case HS_ENOSPACE: return "the call needs more scratch memory than the library's static array holds";
     default: return "unknown status";
   }
 }
@@ -387,6 +388,23 @@ int hs_prefill_attn_at(const hs_shape* shape, int32_t Lq, int32_t q_start, float
 int hs_decode_attn(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
                    float* LSE, void* workspace, void* stream) {
   return hs_decode_attn_phases(shape, scale, n_splits, Q, kv, O, LSE, workspace, stream, 3);
+}
+
+int hs_decode_attn_static(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,
+                          float* LSE, void* stream) {
+  size_t need = 0;
+  if (n_splits < 0) return HS_EINVAL;
+  const int rc = hs_workspace_bytes(shape, 2, n_splits, &need);
+  if (rc != HS_OK) return rc;
+  if (need > HS_STATIC_SCRATCH_BYTES) return HS_ENOSPACE;
+  void* ws = nullptr;
+  size_t have = 0;
+  const hipError_t e = hs_static_scratch(&ws, &have);  // a symbol lookup on the first call per device, no allocation
+  if (e != hipSuccess) return hip_fail(e);
+  if (need > have) return HS_ENOSPACE;
+  // every partial the merge kernel reads is written by the split kernel of the same call: what an
+  // earlier call left in the array does not matter and nothing has to be cleared
+  return decode_common(shape, scale, n_splits, Q, kv, nullptr, nullptr, -1, nullptr, O, LSE, ws, stream, 3);
 }
 
 int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv, void* O,

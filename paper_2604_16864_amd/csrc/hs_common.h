@@ -158,6 +158,9 @@ hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out
 hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_splits, const uint16_t* Q,
                             hs_kv_dev kv, const uint16_t* tail_k, const uint16_t* tail_v, int tail_len, const int32_t* tail_lens,
                             uint16_t* O, float* LSE, float* ws, hipStream_t st, int phases, int dtype);
+// address (on the current device) and size of the library's static device array that hs_decode_attn_static
+// uses for its split partials; looked up once per device, never allocated
+hipError_t hs_static_scratch(void** ptr, size_t* bytes);
 // register-resident matrix-instruction loop (kind 0 dense 16x16x32, 1 sparse 16x16x64), 8 * iters instructions per wave
 hipError_t hs_launch_mfma_rate(int kind, int iters, int n_workgroups, long long* sink, hipStream_t st);
 // q_start: position in the cache of the first query (query i sees tokens <= q_start + i when causal)

@@ -8,6 +8,7 @@
 // order), so there is no LDS staging and no cross-lane shuffle in the main loop.  The
 // sparse matrix instruction is used as the decompressor: it consumes the 2-bit metadata
 // natively, so no vector-ALU work is spent on selecting operands.
+#include <mutex>
 #include <type_traits>
 
 #include "hs_common.h"
@@ -448,6 +449,32 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(int Hq, int Hkv, float
 }
 
 }  // namespace
+
+// Split partials of hs_decode_attn_static: a fixed array in device memory, one copy per GPU the
+// library is loaded on, held until the process ends.  In host code the name `scratch` is only a
+// handle for hipGetSymbolAddress; the address kernels and copies use is the one looked up below.
+static __device__ __align__(256) unsigned char scratch[HS_STATIC_SCRATCH_BYTES];
+
+hipError_t hs_static_scratch(void** ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* per_device[kMaxDevices] = {};  // each GPU has its own copy of the array at its own address
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (per_device[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // for the current device
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  *bytes = HS_STATIC_SCRATCH_BYTES;
+  return hipSuccess;
+}
 
 // Workspace: [partial O (normalised) [B*Hq][n_splits][128] fp32][partial LSE [B*Hq][n_splits] fp32].
 template <int KM, int VM, bool UNIFORM>
