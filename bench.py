@@ -356,6 +356,8 @@ def main():
                          "skipping, the paper's S_K=0/S_V=1 point)")
     ap.add_argument("--legs", default="all", help="comma-separated extra legs to run (default all): " + ", ".join(LEGS))
     ap.add_argument("--cases", default="all", help="comma-separated cases of the swept legs to run, e.g. skip0.5 (default all)")
+    ap.add_argument("--only-legs", action="store_true",
+                    help="run only the selected extra legs (no headline step): what the per-leg rocprofv3 runs use")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference kernel of known traffic for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -384,6 +386,17 @@ def main():
     qd = Q[:, :, -1, :].contiguous()
     del Qh, Kh, Vh
     sh = hb.make_shape(B, Hq, Hkv, L)
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.only_legs:
+        print(json.dumps({"legs_only": True, "data": "synthetic", "n_gpus": 1,
+                          "stages_extra": extra_legs(hb, torch, Q, K, V, qd, sh, args)}))
+        return
     pol = hb.make_policy()                       # 2:4 on every K and V tile, no skipping
     counts = hb.tile_counts(sh, pol)
     kvs = [hb.PackedKV(sh, counts) for _ in range(args.copies)]
@@ -407,14 +420,6 @@ def main():
         if ev: ev[2].record()
         hb.decode_attn(sh, qd, kv_r, n_splits=n_splits, out=Od, lse=lse_d, workspace=ws_d)
         if ev: ev[3].record()
-
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     for i in range(args.warmup):
         step(i)

@@ -100,6 +100,10 @@ enum { HS_BF16 = 0, HS_FP16 = 1 };
  *                  a pool of `out` has (the tiles that no longer fit are stored as SKIP in K
  *                  and V and take no slot), bit 1 = a state pair was not valid (value outside
  *                  0..2, or SKIP in only one tensor; the tile is stored as SKIP).
+ *   tile_scores    optional DEVICE double [3, B, Hkv, T] written by hs_score_tiles: what
+ *                  hs_recompress_kv ranks by when its target has fractions (a packed cache no
+ *                  longer holds the original values of its 2:4 tiles).  hs_compress_kv does not
+ *                  read it: it scores the tensors it is given.
  *   dense_first_tiles, dense_last_tiles
  *                  the first / last so many tiles of every row stay DENSE in K and V and
  *                  take no part in either ranking (the "sink" and "local window" tokens
@@ -120,6 +124,7 @@ typedef struct {
   const int8_t* state_k;
   const int8_t* state_v;
   int32_t* state_flag;
+  const double* tile_scores;
   int32_t dense_first_tiles;
   int32_t dense_last_tiles;
   int32_t element_rule;
@@ -170,7 +175,7 @@ HS_API int hs_kv_bytes(const hs_shape* shape, const int32_t counts[5], size_t by
 
 /* Workspace bytes needed by each call.  [host, pure]
  *   op = 0 compress, 1 prefill (Lq = arg), 2 decode (n_splits = arg, 0 = auto), 3 re-compress
- *   (ops 1 and 3 need none: 0 bytes, the workspace argument of those calls may be NULL) */
+ *   (op 1 needs none; op 3 only when the target ranks tiles: then 8 bytes per tile) */
 HS_API int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes);
 
 /* Number of KV splits hs_decode_attn uses when n_splits == 0. [host, pure] */
@@ -188,6 +193,13 @@ HS_API int hs_decode_auto_splits(const hs_shape* shape);
 HS_API int hs_compress_kv(const hs_shape* shape, const hs_policy* policy,
                    const void* K, const void* V, const int64_t kv_strides[3],
                    const hs_kv* out, void* workspace, void* stream);
+
+/* Tile scores of K, V (same arguments as hs_compress_kv): scores = DEVICE double [3, B, Hkv, T],
+ * plane 0 the tile energy sum(K^2) + sum(V^2), planes 1 and 2 the pruning losses of K and V
+ * (Eq. 2c: L1 norm of what the 2:4 mask of `element_rule` removes), fp64, fixed summation order:
+ * the numbers hs_compress_kv ranks by.  For hs_recompress_kv with ranked targets. */
+HS_API int hs_score_tiles(const hs_shape* shape, const void* K, const void* V, const int64_t kv_strides[3],
+                   int32_t element_rule, double* scores, void* stream);
 
 /* Fill one tile of a cache that grows during decode.  The pools hand out slots in sequence
  * order with one counter per pool (Sec. III-B), so a cache can be allocated for a capacity of
@@ -229,16 +241,19 @@ HS_API int hs_append_tile_rows(const hs_shape* shape, const int32_t* tiles, int3
  * dropped; slots of `dst` are handed out again in tile order, one counter per pool (Sec. III-B).
  * The result equals hs_compress_kv of the original tensors with those states, bit for bit.
  * target: explicit states (device arrays, as for hs_compress_kv; target->state_flag is not used),
- * or whole-tensor fractions --
- * skip_frac == 0 and sparse_frac_k, sparse_frac_v each 0 or 1, with dense_first_tiles /
- * dense_last_tiles kept DENSE; other fractions would need a ranking of packed data:
- * HS_EUNSUPPORTED.
+ * or fractions.  Whole-tensor fractions -- skip_frac == 0 and sparse_frac_k, sparse_frac_v each 0
+ * or 1, with dense_first_tiles / dense_last_tiles kept DENSE -- need nothing else.  Any other
+ * fractions rank the tiles exactly as hs_compress_kv would rank the original tensors (Eq. 2c-d;
+ * lowest energy skipped), from the scores the caller kept: target->tile_scores (hs_score_tiles,
+ * taken while the original K, V existed) and `workspace` of hs_workspace_bytes(op 3) bytes,
+ * 4-byte aligned; without tile_scores such a target is HS_EUNSUPPORTED.  The target state of a
+ * tile is the one that policy gives it; its new state is the sparser of that and its current one.
  * src, dst: distinct caches of the same shape (no overlap); dst's capacities are the caller's
  * choice: a tile for which one of its pools has no slot left when its turn comes (tile order) is
  * left SKIP in K and V, takes no slot in either pool -- the used slots of a pool stay 0 .. n-1, so
  * hs_append_tile can go on from there -- and bit 0 of `overflow` (device int32, set to 0 by the
  * caller; may be NULL) is set.  Bit 1 is set if an explicit target pair was not valid (such a tile
- * keeps its state).  dst->uniform is not read.  workspace: not used, may be NULL. */
+ * keeps its state).  dst->uniform is not read.  workspace: only for ranked targets, else may be NULL. */
 HS_API int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv* src, const hs_kv* dst,
                      void* workspace, int32_t* overflow, void* stream);
 

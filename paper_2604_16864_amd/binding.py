@@ -28,7 +28,7 @@ class HsShape(C.Structure):
 class HsPolicy(C.Structure):
     _fields_ = [("skip_frac", C.c_double), ("sparse_frac_k", C.c_double), ("sparse_frac_v", C.c_double),
                 ("state_k", C.c_void_p), ("state_v", C.c_void_p), ("state_flag", C.c_void_p),
-                ("dense_first_tiles", C.c_int32), ("dense_last_tiles", C.c_int32), ("element_rule", C.c_int32)]
+                ("tile_scores", C.c_void_p), ("dense_first_tiles", C.c_int32), ("dense_last_tiles", C.c_int32), ("element_rule", C.c_int32)]
 
 
 class HsKV(C.Structure):
@@ -54,6 +54,8 @@ EXPORTS = {
                                       C.c_void_p, C.POINTER(C.c_int64), C.POINTER(HsKV), C.c_void_p, C.c_void_p]),
     "hs_decode_attn_tail_rows": (C.c_int, [C.POINTER(HsShape), C.c_float, C.c_int32, C.c_void_p, C.POINTER(HsKV), C.c_void_p,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hs_score_tiles": (C.c_int, [C.POINTER(HsShape), C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_int32, C.c_void_p,
+                                 C.c_void_p]),
     "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "hs_recompress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(HsKV), C.POINTER(HsKV), C.c_void_p,
@@ -133,14 +135,19 @@ RULE_MAGNITUDE, RULE_NONZERO = 0, 1
 
 
 def make_policy(skip_frac=0.0, sparse_frac_k=1.0, sparse_frac_v=1.0, state_k=None, state_v=None,
-                dense_first_tiles=0, dense_last_tiles=0, element_rule=RULE_MAGNITUDE, device="cuda"):
+                dense_first_tiles=0, dense_last_tiles=0, element_rule=RULE_MAGNITUDE, device="cuda", tile_scores=None):
     """state_k/state_v: optional explicit tile states [B, Hkv, T]: int8 device tensors (handed to the
     library as they are), or host arrays -- a convenience of this binding: they are checked here (the
     library cannot read them on the host), copied to the device, and their per-row counts are kept
     for tile_counts.  The returned object keeps the device tensors alive and owns the library's
-    device-side flag for explicit states (`state_flag`, see check_state_flag)."""
-    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None, None,
+    device-side flag for explicit states (`state_flag`, see check_state_flag).
+    tile_scores: float64 device tensor [3, B, Hkv, T] from score_tiles, for ranked recompress_kv targets."""
+    p = HsPolicy(float(skip_frac), float(sparse_frac_k), float(sparse_frac_v), None, None, None, None,
                  int(dense_first_tiles), int(dense_last_tiles), int(element_rule))
+    if tile_scores is not None:
+        assert tile_scores.dtype == torch.float64 and tile_scores.is_cuda and tile_scores.is_contiguous()
+        p.tile_scores = tile_scores.data_ptr()
+        p._scores = tile_scores
     if state_k is not None:
         if torch.is_tensor(state_k):
             sk, sv = state_k, state_v
@@ -277,7 +284,7 @@ def append_tile(shape, kv, tile, K_tile, V_tile, state_k=SPARSE24, state_v=SPARS
 
 def recompress_kv(shape, kv, target, counts=None, overflow=None, out=None, workspace=None):
     """Prune the packed cache `kv` further towards the policy `target` (make_policy: explicit states,
-    or fractions 0 / 1 with protected end tiles).  Returns a new PackedKV; counts = capacities of
+    fractions 0 / 1 with protected end tiles, or any fractions together with tile_scores).  Returns a new PackedKV; counts = capacities of
     the new pools as [_, dense K, 2:4 K, dense V, 2:4 V] (default: enough for any outcome); out: a
     PackedKV to fill instead of a new one."""
     T = shape.L // TILE
@@ -293,11 +300,23 @@ def recompress_kv(shape, kv, target, counts=None, overflow=None, out=None, works
         out = PackedKV(shape, counts, kv.k_map.device)
     counts = out.counts
     # slot == tile survives when nothing was skipped before and each tensor ends up in one kind
-    out.uniform = int(bool(kv.uniform) and not target.state_k and counts[1] * counts[2] == 0 and counts[3] * counts[4] == 0
+    whole = not target.state_k and target.skip_frac == 0.0 and target.sparse_frac_k in (0.0, 1.0) and target.sparse_frac_v in (0.0, 1.0)
+    out.uniform = int(bool(kv.uniform) and whole and counts[1] * counts[2] == 0 and counts[3] * counts[4] == 0
                       and max(counts[1], counts[2]) == T and max(counts[3], counts[4]) == T)
+    if workspace is None and target.tile_scores:
+        workspace = _workspace(workspace_bytes(shape, 3), kv.k_map.device)
     a, b = kv.struct(), out.struct()
     _check(lib().hs_recompress_kv(C.byref(shape), C.byref(target), C.byref(a), C.byref(b), _ptr(workspace), _ptr(overflow),
                                   _stream()))
+    return out
+
+
+def score_tiles(shape, K, V, element_rule=RULE_MAGNITUDE):
+    """Tile scores [3, B, Hkv, T] float64 (energy, pruning loss of K, of V) of K, V [B, Hkv, L, D]."""
+    assert K.dtype == torch_dtype(shape) and V.dtype == K.dtype and K.stride() == V.stride() and K.stride(-1) == 1
+    out = torch.empty((3, shape.B, shape.Hkv, shape.L // TILE), dtype=torch.float64, device=K.device)
+    strides = (C.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
+    _check(lib().hs_score_tiles(C.byref(shape), _ptr(K), _ptr(V), strides, int(element_rule), _ptr(out), _stream()))
     return out
 
 

@@ -186,7 +186,7 @@ int hs_workspace_bytes(const hs_shape* shape, int op, int32_t arg, size_t* bytes
       *bytes = (size_t)shape->B * shape->Hq * (size_t)n * (HS_D + 1) * sizeof(float);
       return HS_OK;
     }
-    case 3: *bytes = 0; return HS_OK;
+    case 3: *bytes = 2 * rows * T * sizeof(int32_t); return HS_OK;
     default: return HS_EINVAL;
   }
 }
@@ -324,19 +324,51 @@ int hs_recompress_kv(const hs_shape* shape, const hs_policy* target, const hs_kv
   const int T = shape->L / HS_BT;
   if (T > kSelectMaxTiles) return HS_EUNSUPPORTED;
   int n_first = 0, n_last = 0, fk = HS_DENSE, fv = HS_DENSE;
+  const int32_t* tgt_map_k = nullptr;
+  const int32_t* tgt_map_v = nullptr;
+  hipStream_t s = (hipStream_t)stream;
   if (target->state_k == nullptr) {
-    // without a ranking only whole-tensor targets are defined: S in {0, 1}, nothing skipped
-    if (target->skip_frac != 0.0) return HS_EUNSUPPORTED;
-    if ((target->sparse_frac_k != 0.0 && target->sparse_frac_k != 1.0) ||
-        (target->sparse_frac_v != 0.0 && target->sparse_frac_v != 1.0))
-      return HS_EUNSUPPORTED;
     protected_tiles(T, target, &n_first, &n_last);
-    fk = target->sparse_frac_k == 0.0 ? HS_DENSE : HS_SPARSE24;
-    fv = target->sparse_frac_v == 0.0 ? HS_DENSE : HS_SPARSE24;
+    const bool whole = target->skip_frac == 0.0 && (target->sparse_frac_k == 0.0 || target->sparse_frac_k == 1.0) &&
+                       (target->sparse_frac_v == 0.0 || target->sparse_frac_v == 1.0);
+    if (whole) {
+      fk = target->sparse_frac_k == 0.0 ? HS_DENSE : HS_SPARSE24;
+      fv = target->sparse_frac_v == 0.0 ? HS_DENSE : HS_SPARSE24;
+    } else {
+      // ranked target: the states hs_compress_kv would give the original tensors, from the scores the
+      // caller kept; the selection kernel writes them as maps into the workspace (only their signs are used)
+      if (target->tile_scores == nullptr) return HS_EUNSUPPORTED;
+      if (workspace == nullptr || ((uintptr_t)workspace & 3u) || ((uintptr_t)target->tile_scores & 7u)) return HS_EINVAL;
+      int32_t c[5];
+      policy_counts(T, target, c);
+      int32_t* tk = (int32_t*)workspace;
+      int32_t* tv = tk + (int64_t)shape->B * shape->Hkv * T;
+      const hipError_t e0 = hs_launch_select(target->tile_scores, shape->B * shape->Hkv, T, c[0], c[2], c[4], n_first, n_last,
+                                             tk, tv, s);
+      if (e0 != hipSuccess) return hip_fail(e0);
+      tgt_map_k = tk;
+      tgt_map_v = tv;
+    }
   }
   const hipError_t e = hs_launch_recompress(shape->B, shape->Hkv, T, hs_make_kv_dev(src), target->state_k, target->state_v,
-                                            fk, fv, n_first, n_last, hs_make_kv_dev(dst), target->element_rule,
-                                            shape->dtype == HS_BF16, overflow, (hipStream_t)stream);
+                                            tgt_map_k, tgt_map_v, fk, fv, n_first, n_last, hs_make_kv_dev(dst),
+                                            target->element_rule, shape->dtype == HS_BF16, overflow, s);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
+int hs_score_tiles(const hs_shape* shape, const void* K, const void* V, const int64_t kv_strides[3], int32_t element_rule,
+                   double* scores, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != HS_OK) return rc;
+  if (K == nullptr || V == nullptr || scores == nullptr) return HS_EINVAL;
+  if ((((uintptr_t)K | (uintptr_t)V) & 15u) || ((uintptr_t)scores & 7u)) return HS_EINVAL;
+  if (element_rule != HS_RULE_MAGNITUDE && element_rule != HS_RULE_NONZERO) return HS_EINVAL;
+  int64_t sb = (int64_t)shape->Hkv * shape->L * HS_D, sh = (int64_t)shape->L * HS_D, st = HS_D;
+  if (kv_strides != nullptr) { sb = kv_strides[0]; sh = kv_strides[1]; st = kv_strides[2]; }
+  if (st < HS_D || sb < 0 || sh < 0 || (sb | sh | st) % 8 != 0) return HS_EINVAL;
+  const hipError_t e = hs_launch_score((const uint16_t*)K, (const uint16_t*)V, sb, sh, st, shape->B, shape->Hkv,
+                                       shape->L / HS_BT, element_rule, shape->dtype, 3, scores, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   return HS_OK;
 }

@@ -146,11 +146,13 @@ hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, in
 hipError_t hs_launch_states_to_maps(const int8_t* state_k, const int8_t* state_v, int rows, int T, hs_kv_dev kv,
                                     int32_t* flag, hipStream_t st);
 // packed cache -> packed cache, each tile in the sparser of its state and its target: tgt_k / tgt_v (device
-// int8 [rows, T]) or, when NULL, frac_state_k / frac_state_v for every tile but the n_first first and n_last
-// last of a row, which stay as they are
+// int8 [rows, T]), or the signs of tgt_map_k / tgt_map_v (device int32 [rows, T]), or, when all are NULL,
+// frac_state_k / frac_state_v for every tile but the n_first first and n_last last of a row, which stay as
+// they are
 hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,
-                                int frac_state_k, int frac_state_v, int n_first, int n_last, hs_kv_dev dst, int rule,
-                                int v_f16, int32_t* overflow, hipStream_t st);
+                                const int32_t* tgt_map_k, const int32_t* tgt_map_v, int frac_state_k, int frac_state_v,
+                                int n_first, int n_last, hs_kv_dev dst, int rule, int v_f16, int32_t* overflow,
+                                hipStream_t st);
 hipError_t hs_launch_unpack(int B, int Hkv, int T, hs_kv_dev kv, uint16_t* K_out, uint16_t* V_out, hipStream_t st);
 // tail_len < 0: no tail slot; tail_len >= 0: one extra partial per query head, computed from the
 // dense tail tokens (tail_k / tail_v, bf16 [B, Hkv, 64, D]); tail_lens (device, [B]) replaces

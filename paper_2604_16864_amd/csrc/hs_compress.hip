@@ -7,6 +7,22 @@ namespace {
 
 constexpr int kVStride = 132;  // LDS row stride (elements) of a staged V tile: 8-byte aligned rows, shifted banks
 
+// 16-byte global accesses of the compressor.  Every input byte is read once and every output byte
+// written once per call, so 2:4 tiles go through non-temporal loads and stores (measured: 1.21 ->
+// 1.09 ms at B 8 x L 131072, 42.4 -> 39.5 us at L 32768); for tiles that stay dense, where as many
+// bytes are written as read, the plain forms measured faster and are kept.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ uint4 ld16(const void* p) {
+  if (NT) return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p)));
+  return *reinterpret_cast<const uint4*>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void st16(void* p, uint4 v) {
+  if (NT) __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, v), reinterpret_cast<u32x4_t*>(p));
+  else *reinterpret_cast<uint4*>(p) = v;
+}
+
 // Top-2-of-4 by magnitude (Eq. 2a-b with an exact count of two): x0..x3 are bf16 bit
 // patterns; element j outranks element i if |x_j| > |x_i|, or |x_j| == |x_i| and j < i.
 // Returns the 4-bit keep mask (exactly two bits set).
@@ -40,13 +56,14 @@ template <bool F16> __device__ __forceinline__ double elem_val(uint32_t bits) { 
 // ----------------------------------------------------------------------------------
 // Staging of one V tile [64 tokens][128 ch] into LDS with coalesced 16-byte loads.
 // ----------------------------------------------------------------------------------
+template <bool NT = false>
 __device__ __forceinline__ void stage_v_tile(const uint16_t* vt, int64_t tok_stride, uint16_t* lds) {
   const int tid = threadIdx.x;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int q = tid + 256 * i;
     const int tok = q >> 4, c8 = q & 15;
-    const uint4 d = *reinterpret_cast<const uint4*>(vt + tok * tok_stride + 8 * c8);
+    const uint4 d = ld16<NT>(vt + tok * tok_stride + 8 * c8);
     uint2* dst = reinterpret_cast<uint2*>(lds + tok * kVStride + 8 * c8);
     dst[0] = make_uint2(d.x, d.y);
     dst[1] = make_uint2(d.z, d.w);
@@ -80,7 +97,10 @@ __device__ __forceinline__ double dropped_l1(uint32_t x0, uint32_t x1, uint32_t 
   return fabs(elem_val<F16>(pair & 0xffffu)) + fabs(elem_val<F16>(pair >> 16));
 }
 
-template <bool F16, int WHAT>
+// NT: non-temporal reads in the energy-only form.  They pay when K and V exceed the last-level
+// cache (B 8 x L 131072: 1.32 -> 1.26 ms for score + select + pack) and cost when they fit, because
+// the pack kernel's second read of the kept tiles then no longer hits that cache (L 32768: 56 -> 60 us).
+template <bool F16, int WHAT, bool NT>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                     int64_t sb, int64_t sh, int64_t st, int Hkv, int T, int rule,
                                                     double* __restrict__ scores) {
@@ -97,8 +117,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       const int q = tid + 256 * i, tok = q >> 4, c8 = q & 15;
-      e += sum_sq8<F16>(*reinterpret_cast<const uint4*>(kt + tok * st + 8 * c8));
-      e += sum_sq8<F16>(*reinterpret_cast<const uint4*>(vt + tok * st + 8 * c8));
+      e += sum_sq8<F16>(ld16<NT>(kt + tok * st + 8 * c8));
+      e += sum_sq8<F16>(ld16<NT>(vt + tok * st + 8 * c8));
     }
   } else {
     stage_v_tile(vt, st, vl);
@@ -492,7 +512,7 @@ __device__ __forceinline__ void k_sparse_store(uint8_t* nnz, uint8_t* meta, int 
       top2_emit(top2_mask(x0, x1, x2, x3, rule), x0, x1, x2, x3, out[q], nib);
       idx |= nib << (16 * kb + 4 * q);
     }
-    *reinterpret_cast<uint4*>(nnz + ((w * 2 + kb) * 64 + l) * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+    st16<true>(nnz + ((w * 2 + kb) * 64 + l) * 16, make_uint4(out[0], out[1], out[2], out[3]));
   }
   *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
 }
@@ -558,14 +578,14 @@ __device__ __forceinline__ void v_tile_store(const uint16_t* vl, int mv, int32_t
     uint8_t* dst = const_cast<uint8_t*>(kv.v_dense) + (row * kv.cap_dense_v + (mv - 1)) * (int64_t)HS_TILE_DENSE_BYTES;
 #pragma unroll
     for (int j = 0; j < 4; j++)
-      *reinterpret_cast<uint4*>(dst + ((4 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+      st16<false>(dst + ((4 * w + j) * 64 + l) * 16, make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]));
   } else {
     const int64_t slot = row * kv.cap_sparse_v + (-mv - 1);
     uint8_t* nnz = const_cast<uint8_t*>(kv.v_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES;
     uint8_t* meta = const_cast<uint8_t*>(kv.v_meta) + slot * (int64_t)HS_TILE_META_BYTES;
 #pragma unroll
     for (int j = 0; j < 2; j++)
-      *reinterpret_cast<uint4*>(nnz + ((2 * w + j) * 64 + l) * 16) = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+      st16<true>(nnz + ((2 * w + j) * 64 + l) * 16, make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]));
     *reinterpret_cast<uint32_t*>(meta + (l * 4 + w) * 4) = idx;
   }
 }
@@ -626,7 +646,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
   }
   const uint16_t* kt = K + b * sb + h * sh + (int64_t)ts * HS_BT * st;
   const uint16_t* vt = V + b * sb + h * sh + (int64_t)ts * HS_BT * st;
-  if (mv != 0) stage_v_tile(vt, st, vl);
+  if (mv < 0) stage_v_tile<true>(vt, st, vl);
+  else if (mv > 0) stage_v_tile<false>(vt, st, vl);
 
   // ---- K ----
   if (mk > 0) {  // dense: permuted copy into operand order
@@ -634,15 +655,14 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
     const uint16_t* src = kt + (int64_t)(16 * w + r) * st + 8 * a;
 #pragma unroll
     for (int s = 0; s < 4; s++) {
-      const uint4 d = *reinterpret_cast<const uint4*>(src + 32 * s);
-      *reinterpret_cast<uint4*>(dst + ((w * 4 + s) * 64 + l) * 16) = d;
+      st16<false>(dst + ((w * 4 + s) * 64 + l) * 16, ld16<false>(src + 32 * s));
     }
   } else if (mk < 0) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
     const uint16_t* src = kt + (int64_t)(16 * w + r) * st + 16 * a;
     k_sparse_store(const_cast<uint8_t*>(kv.k_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES,
                    const_cast<uint8_t*>(kv.k_meta) + slot * (int64_t)HS_TILE_META_BYTES, w, l, rule,
-                   [&](int kb, int half) { return *reinterpret_cast<const uint4*>(src + 64 * kb + 8 * half); });
+                   [&](int kb, int half) { return ld16<true>(src + 64 * kb + 8 * half); });
   }
 
   // ---- V ----
@@ -667,11 +687,14 @@ __device__ __forceinline__ int sparser_state(int map_entry, int target) {
 // (Sec. III-B); a tile that keeps its kind keeps its encoding bit.  A tile for which a pool of dst
 // has no slot left is left out of both tensors, takes no slot, and bit 0 of *overflow is raised
 // (assign_slots_row).  Target of tile t: tgt_k / tgt_v (device int8 [rows, T]) when given -- a
-// pair that is not valid leaves the tile as it is and raises bit 1 -- else DENSE for the n_first
-// first and n_last last tiles of the row and frac_state_k / frac_state_v in between.
-// One workgroup per row.
+// pair that is not valid leaves the tile as it is and raises bit 1 --; else the sign of
+// tgt_map_k / tgt_map_v (maps the selection kernel wrote for a ranked target: > 0 dense, < 0 2:4,
+// 0 skipped) when given; else DENSE for the n_first first and n_last last tiles of the row and
+// frac_state_k / frac_state_v in between.  One workgroup per row.
 __global__ __launch_bounds__(256) void restate_kernel(int T, hs_kv_dev src, const int8_t* __restrict__ tgt_k,
-                                                      const int8_t* __restrict__ tgt_v, int frac_state_k,
+                                                      const int8_t* __restrict__ tgt_v,
+                                                      const int32_t* __restrict__ tgt_map_k,
+                                                      const int32_t* __restrict__ tgt_map_v, int frac_state_k,
                                                       int frac_state_v, int n_first, int n_last, hs_kv_dev dst,
                                                       int32_t* overflow) {
   __shared__ SlotShared sm;
@@ -692,6 +715,10 @@ __global__ __launch_bounds__(256) void restate_kernel(int T, hs_kv_dev src, cons
             invalid = true;
             tk = tv = HS_DENSE;  // no further pruning of this tile
           }
+        } else if (tgt_map_k != nullptr) {
+          const int a = tgt_map_k[(int64_t)row * T + t], c = tgt_map_v[(int64_t)row * T + t];
+          tk = a > 0 ? HS_DENSE : (a < 0 ? HS_SPARSE24 : HS_SKIP);
+          tv = c > 0 ? HS_DENSE : (c < 0 ? HS_SPARSE24 : HS_SKIP);
         } else {
           const bool prot = t < n_first || t >= T - n_last;
           tk = prot ? HS_DENSE : frac_state_k;
@@ -876,8 +903,13 @@ __global__ __launch_bounds__(256) void unpack_kernel(int Hkv, int T, hs_kv_dev k
 hipError_t hs_launch_score(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
                            int T, int rule, int dtype, int what, double* scores, hipStream_t st) {
   const dim3 grid(T, Hkv, B), block(256);
-#define HS_SCORE(F16_, WHAT_) \
-  hipLaunchKernelGGL((score_kernel<F16_, WHAT_>), grid, block, 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores)
+  // non-temporal reads once K and V together are larger than the 256 MB last-level cache
+  const bool nt = what == 1 && 2.0 * B * Hkv * T * HS_BT * HS_D * 2.0 > 256e6;
+#define HS_SCORE(F16_, WHAT_)                                                                                              \
+  do {                                                                                                                     \
+    if (nt) hipLaunchKernelGGL((score_kernel<F16_, WHAT_, true>), grid, block, 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores); \
+    else hipLaunchKernelGGL((score_kernel<F16_, WHAT_, false>), grid, block, 0, st, K, V, sb, sh, st_, Hkv, T, rule, scores);   \
+  } while (0)
   if (dtype == HS_FP16) {
     if (what == 1) HS_SCORE(true, 1); else if (what == 2) HS_SCORE(true, 2); else HS_SCORE(true, 3);
   } else {
@@ -922,10 +954,11 @@ hipError_t hs_launch_states_to_maps(const int8_t* state_k, const int8_t* state_v
 }
 
 hipError_t hs_launch_recompress(int B, int Hkv, int T, hs_kv_dev src, const int8_t* tgt_k, const int8_t* tgt_v,
-                                int frac_state_k, int frac_state_v, int n_first, int n_last, hs_kv_dev dst, int rule,
-                                int v_f16, int32_t* overflow, hipStream_t st) {
-  hipLaunchKernelGGL(restate_kernel, dim3(B * Hkv), dim3(256), 0, st, T, src, tgt_k, tgt_v, frac_state_k, frac_state_v,
-                     n_first, n_last, dst, overflow);
+                                const int32_t* tgt_map_k, const int32_t* tgt_map_v, int frac_state_k, int frac_state_v,
+                                int n_first, int n_last, hs_kv_dev dst, int rule, int v_f16, int32_t* overflow,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(restate_kernel, dim3(B * Hkv), dim3(256), 0, st, T, src, tgt_k, tgt_v, tgt_map_k, tgt_map_v,
+                     frac_state_k, frac_state_v, n_first, n_last, dst, overflow);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(repack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, Hkv, T, src, dst, rule, v_f16);

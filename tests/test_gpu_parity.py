@@ -1119,6 +1119,43 @@ def test_recompress_prefill_policy_to_decode_policy(first, last):
     assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode after recompress lse")
 
 
+def test_recompress_ranked_targets_from_kept_tile_scores():
+    """Decode-phase policy with fractions (skip the quietest quarter, half of the key tiles 2:4 by lowest
+    pruning loss, sink and local-window tiles dense) applied to a prefill cache (keys dense, values 2:4): the
+    ranking uses the tile scores taken from the original tensors (hs_score_tiles), which equal the oracle's,
+    and the result equals the oracle's further pruning towards the states that policy gives the originals."""
+    B, Hq, Hkv, T = 2, 8, 2, 24
+    L = 64 * T
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=330, k_outliers=True)
+    K[0, 0, 64 * 9:64 * 10] = K[0, 0, 64 * 3:64 * 4]           # an exact tie in energy and in loss
+    V[0, 0, 64 * 9:64 * 10] = V[0, 0, 64 * 3:64 * 4]
+    Kd, Vd = _dev(K), _dev(V)
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, sparse_frac_k=0.0, sparse_frac_v=1.0)
+    scores = hb.score_tiles(sh, Kd, Vd)
+    tgt = dict(skip_frac=0.25, sparse_frac_k=0.5, sparse_frac_v=1.0, dense_first_tiles=1, dense_last_tiles=2)
+    _, _, info = orc.compress_kv(K, V, **tgt)                    # states the policy gives the original tensors
+    torch.cuda.synchronize()
+    sc = scores.cpu().numpy()
+    for plane, key in enumerate(("energy", "loss_k", "loss_v")):
+        assert np.allclose(sc[plane], info[key], rtol=1e-12, atol=0.0), key
+        srt = np.sort(info[key], axis=-1)
+        gaps = np.diff(srt, axis=-1) / srt[..., 1:]
+        assert ((gaps > 1e-12) | (gaps == 0)).all()              # no cut on a rounding-level near-tie
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kv2 = hb.recompress_kv(sh, kv, hb.make_policy(tile_scores=scores, **tgt), overflow=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0 and kv2.uniform == 0
+    rk, rv = orc.recompress_kv(pk, pv, info["state_k"], info["state_v"])
+    check_packed_bit_exact(sh, kv2, rk, rv)
+    assert int((rk.map == 0).sum()) == B * Hkv * 5 and (rv.map[:, :, 0] < 0).all()      # V was 2:4 already: stays
+    q = Q[:, :, 0, :].copy()
+    O, LSE = hb.decode_attn(sh, _dev(q), kv2, n_splits=3)
+    torch.cuda.synchronize()
+    Or, Lr = orc.attention_decode(q, rk, rv)
+    assert_close(_f32(O), Or, "decode after ranked recompress")
+    assert_lse_close(LSE.cpu().numpy(), Lr, "decode after ranked recompress lse")
+
+
 def test_recompress_capacity_overflow_and_argument_errors():
     B, Hq, Hkv, L = 1, 4, 1, 64 * 8
     T = L // 64
@@ -1136,7 +1173,7 @@ def test_recompress_capacity_overflow_and_argument_errors():
     hb.recompress_kv(sh, kv, hb.make_policy(), overflow=flag)
     torch.cuda.synchronize()
     assert int(flag.item()) == 0
-    with pytest.raises(hb.HsError):                         # needs a ranking of packed data
+    with pytest.raises(hb.HsError):                         # a ranked target needs the tile scores
         hb.recompress_kv(sh, kv, hb.make_policy(sparse_frac_k=0.5))
     with pytest.raises(hb.HsError):
         hb.recompress_kv(sh, kv, hb.make_policy(skip_frac=0.25))

@@ -111,7 +111,7 @@ def test_argument_errors(L):
     assert L.hs_compress_kv(C.byref(ok), C.byref(pol), None, None, None, C.byref(kv), None, None) == -1
     assert L.hs_strerror(-2).decode().startswith("unsupported")
     # explicit states are device memory: the host cannot count them
-    pol_s = hb.HsPolicy(0.0, 1.0, 1.0, 16, 16, None, 0, 0, 0)
+    pol_s = hb.HsPolicy(0.0, 1.0, 1.0, 16, 16, None, None, 0, 0, 0)
     assert L.hs_tile_counts(C.byref(ok), C.byref(pol_s), c) == -2
     assert hb.workspace_bytes(ok, 2, 4) == 1 * 4 * 4 * 129 * 4
     assert hb.decode_auto_splits(ok) == 4
