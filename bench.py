@@ -451,6 +451,22 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     t_dm = e0.elapsed_time(e1) / n_rep * 1e-3
+    # what the memory system gives the split kernel's access pattern with nothing else in the kernel: a load-only
+    # kernel of the same launch shape, pools, tile order and depth (with a combine through LDS and a partial
+    # store per workgroup), over rotating cold buffers of the same size
+    n_tiles = B * Hkv * T
+    arena = torch.empty(args.copies * n_tiles * 18432, dtype=torch.uint8, device="cuda").fill_(1)
+    probe_sink = torch.zeros(16 + 512 * n_splits * Hkv * B, dtype=torch.float32, device="cuda")
+    views = [arena[i * n_tiles * 18432:(i + 1) * n_tiles * 18432] for i in range(args.copies)]
+    for v in views:
+        hb.probe_stream_read(v, n_tiles, n_splits * Hkv * B, True, probe_sink)
+    e0.record()
+    for i in range(n_rep):
+        hb.probe_stream_read(views[i % args.copies], n_tiles, n_splits * Hkv * B, True, probe_sink)
+    e1.record()
+    torch.cuda.synchronize()
+    t_probe = e0.elapsed_time(e1) / n_rep * 1e-3
+    del arena, views
     # rate of the matrix pipes on this chip, register-resident (no memory, no LDS, no vector-ALU work)
     sink = torch.zeros(4, dtype=torch.int64, device="cuda")
     mfma_meas = {}
@@ -549,6 +565,8 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": decode_bytes / dec_split_s / 1e9 / HBM_PEAK_GBPS,
                      "traffic": traffic_from_profile("decode_split_kernel<0, 0, true"), "traffic_source": "profiles/bench_cfg1_hbm_traffic.md",
                      "algorithmic_bytes": decode_bytes, "avg_launch_us": dec_split_s * 1e6,
+                     # load-only kernel with the same access pattern and launch shape (hs_probe_stream_read)
+                     "load_only_probe_us": t_probe * 1e6, "load_only_probe_frac": n_tiles * 18432 / t_probe / 1e9 / HBM_PEAK_GBPS,
                      "whole_call_us": dec_s * 1e6, "whole_call_frac": decode_bytes / dec_s / 1e9 / HBM_PEAK_GBPS},
         # prefill against the matrix pipes: every tile is 2:4, so half of the dense-equivalent multiplications are
         # executed; `achieved` counts the executed ones and `peak` is the dense bf16 rate, i.e. frac = t_floor / t with

@@ -31,6 +31,17 @@ HS_API int hs_decode_attn_phases(const hs_shape* shape, float scale, int32_t n_s
  * the chip sustained).  Asynchronous on `stream`. */
 HS_API int hs_probe_mfma_rate(int kind, int32_t iters, void* sink, double* flop, void* stream);
 
+/* Benchmark support: a load-only kernel with the access pattern of the split-KV decode kernel, so that a
+ * caller can time what the memory system gives that pattern at a given size next to the 8 TB/s peak.
+ * buf: device, n_tiles * 18432 bytes, 16-byte aligned, read as four pool regions (kept values of K: n_tiles
+ * x 8192 B, positions of K: n_tiles x 1024 B, then the same for V); workgroups of 4 waves, wave w of workgroup
+ * g reads tiles (n_tiles / n_workgroups) g + w + 4 i with two tiles in flight (non-temporal 16-byte loads);
+ * n_tiles must be a multiple of 4 n_workgroups.  with_epilogue != 0 adds a combine through LDS and a 2 KiB
+ * store per workgroup (what the decode kernel does with its partials).  sink: device, 64 + 2048 n_workgroups
+ * bytes, 16-byte aligned.  Asynchronous on `stream`. */
+HS_API int hs_probe_stream_read(const void* buf, int32_t n_tiles, int32_t n_workgroups, int with_epilogue,
+                         void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

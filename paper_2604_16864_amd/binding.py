@@ -58,6 +58,7 @@ EXPORTS = {
                                  C.c_void_p]),
     "hs_unpack_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsKV), C.c_void_p, C.c_void_p, C.c_void_p]),
     "hs_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
+    "hs_probe_stream_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int, C.c_void_p, C.c_void_p]),
     "hs_recompress_kv": (C.c_int, [C.POINTER(HsShape), C.POINTER(HsPolicy), C.POINTER(HsKV), C.POINTER(HsKV), C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
     "hs_prefill_attn": (C.c_int, [C.POINTER(HsShape), C.c_int32, C.c_float, C.c_int, C.c_void_p, C.POINTER(HsKV),
@@ -326,6 +327,15 @@ def probe_mfma_rate(kind, iters, sink):
     flop = C.c_double(0.0)
     _check(lib().hs_probe_mfma_rate(int(kind), int(iters), _ptr(sink), C.byref(flop), _stream()))
     return flop.value
+
+
+def probe_stream_read(buf, n_tiles, n_workgroups, with_epilogue, sink):
+    """Launches the load-only kernel with the decode kernel's access pattern over buf (uint8, n_tiles * 18432 bytes);
+    sink: float32 device tensor of at least 16 + 512 * n_workgroups elements.  Time it with events around the call."""
+    assert buf.is_cuda and buf.numel() * buf.element_size() >= n_tiles * 18432
+    assert sink.dtype == torch.float32 and sink.numel() >= 16 + 512 * n_workgroups
+    _check(lib().hs_probe_stream_read(_ptr(buf), int(n_tiles), int(n_workgroups), int(bool(with_epilogue)), _ptr(sink),
+                                      _stream()))
 
 
 def unpack_kv(shape, kv):

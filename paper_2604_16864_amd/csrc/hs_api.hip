@@ -467,6 +467,16 @@ int hs_probe_mfma_rate(int kind, int32_t iters, void* sink, double* flop, void* 
   return HS_OK;
 }
 
+int hs_probe_stream_read(const void* buf, int32_t n_tiles, int32_t n_workgroups, int with_epilogue, void* sink,
+                         void* stream) {
+  if (buf == nullptr || sink == nullptr || (((uintptr_t)buf | (uintptr_t)sink) & 15u)) return HS_EINVAL;
+  if (n_tiles < 1 || n_workgroups < 1 || n_workgroups > 65535 || n_tiles % (4 * n_workgroups) != 0) return HS_EINVAL;
+  const hipError_t e = hs_launch_stream_read((const uint8_t*)buf, n_tiles, n_workgroups, with_epilogue != 0, (float*)sink,
+                                             (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return HS_OK;
+}
+
 int hs_decode_attn_tail_rows(const hs_shape* shape, float scale, int32_t n_splits, const void* Q, const hs_kv* kv,
                              const void* tail_k, const void* tail_v, const int32_t* tail_lens, void* O, float* LSE,
                              void* workspace, void* stream) {

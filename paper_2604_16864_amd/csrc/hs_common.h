@@ -165,6 +165,9 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_sp
 hipError_t hs_static_scratch(void** ptr, size_t* bytes);
 // register-resident matrix-instruction loop (kind 0 dense 16x16x32, 1 sparse 16x16x64), 8 * iters instructions per wave
 hipError_t hs_launch_mfma_rate(int kind, int iters, int n_workgroups, long long* sink, hipStream_t st);
+// load-only kernel with the decode kernel's access pattern over n_tiles tiles laid out as four pool regions in buf
+hipError_t hs_launch_stream_read(const uint8_t* buf, int n_tiles, int n_workgroups, int with_epilogue, float* sink,
+                                 hipStream_t st);
 // q_start: position in the cache of the first query (query i sees tokens <= q_start + i when causal)
 hipError_t hs_launch_prefill(int B, int Hq, int Hkv, int T, int Tq, int q_start, float scale, int causal, const uint16_t* Q,
                              hs_kv_dev kv, uint16_t* O, float* LSE, hipStream_t st, int dtype);

@@ -8,9 +8,9 @@ namespace {
 constexpr int kVStride = 132;  // LDS row stride (elements) of a staged V tile: 8-byte aligned rows, shifted banks
 
 // 16-byte global accesses of the compressor.  Every input byte is read once and every output byte
-// written once per call, so 2:4 tiles go through non-temporal loads and stores (measured: 1.21 ->
-// 1.09 ms at B 8 x L 131072, 42.4 -> 39.5 us at L 32768); for tiles that stay dense, where as many
-// bytes are written as read, the plain forms measured faster and are kept.
+// written once per call, so the pool bytes of 2:4 tiles are written with non-temporal stores, and
+// their inputs read non-temporally when the tensors are large (pack_kernel); for tiles that stay
+// dense, where as many bytes are written as read, the plain forms measured faster and are kept.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 template <bool NT>
 __device__ __forceinline__ uint4 ld16(const void* p) {
@@ -617,6 +617,10 @@ __device__ __forceinline__ void v_dense_to_lds(const uint8_t* src, bool is_f16, 
 // uni_k / uni_v: 0 = read the tile's map entries (written by an earlier launch); HS_DENSE or
 // HS_SPARSE24 = every tile of that tensor is of this kind, the entry is +-(tile+1) and this
 // kernel writes it (saves the separate map-fill launch of the unranked policies).
+// NTL: the inputs of tiles that become 2:4 are read non-temporally.  That pays when K and V exceed the
+// last-level cache (B 8 x L 131072: 1.20 -> 1.08 ms) and costs a little when they fit (L 32768: 38.7 -> 40.3 us;
+// the two 16-byte reads a lane makes of one K line then both go to L2), so the launcher decides by size.
+template <bool NTL>
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                                    int64_t sb, int64_t sh, int64_t st, int Hkv, int T, hs_kv_dev kv,
                                                    int uni_k, int uni_v, int rule, int t0, int v_f16,
@@ -646,7 +650,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
   }
   const uint16_t* kt = K + b * sb + h * sh + (int64_t)ts * HS_BT * st;
   const uint16_t* vt = V + b * sb + h * sh + (int64_t)ts * HS_BT * st;
-  if (mv < 0) stage_v_tile<true>(vt, st, vl);
+  if (mv < 0) stage_v_tile<NTL>(vt, st, vl);
   else if (mv > 0) stage_v_tile<false>(vt, st, vl);
 
   // ---- K ----
@@ -662,7 +666,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
     const uint16_t* src = kt + (int64_t)(16 * w + r) * st + 16 * a;
     k_sparse_store(const_cast<uint8_t*>(kv.k_nnz) + slot * (int64_t)HS_TILE_NNZ_BYTES,
                    const_cast<uint8_t*>(kv.k_meta) + slot * (int64_t)HS_TILE_META_BYTES, w, l, rule,
-                   [&](int kb, int half) { return ld16<true>(src + 64 * kb + 8 * half); });
+                   [&](int kb, int half) { return ld16<NTL>(src + 64 * kb + 8 * half); });
   }
 
   // ---- V ----
@@ -928,8 +932,12 @@ hipError_t hs_launch_select(const double* scores, int rows, int T, int n_skip, i
 
 hipError_t hs_launch_pack(const uint16_t* K, const uint16_t* V, int64_t sb, int64_t sh, int64_t st_, int B, int Hkv,
                           int T, hs_kv_dev kv, int uni_k, int uni_v, int rule, int v_f16, hipStream_t st) {
-  hipLaunchKernelGGL(pack_kernel, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0, v_f16,
-                     (const int32_t*)nullptr);
+  if (2.0 * B * Hkv * T * HS_BT * HS_D * 2.0 > 256e6)  // K and V together beyond the 256 MB last-level cache
+    hipLaunchKernelGGL(pack_kernel<true>, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0,
+                       v_f16, (const int32_t*)nullptr);
+  else
+    hipLaunchKernelGGL(pack_kernel<false>, dim3(T, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, uni_k, uni_v, rule, 0,
+                       v_f16, (const int32_t*)nullptr);
   return hipGetLastError();
 }
 
@@ -940,8 +948,12 @@ hipError_t hs_launch_append(const uint16_t* K, const uint16_t* V, int64_t sb, in
                      kv, overflow);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(pack_kernel, dim3(n_tiles, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile, v_f16,
-                     tile_rows);
+  if (2.0 * B * Hkv * n_tiles * HS_BT * HS_D * 2.0 > 256e6)
+    hipLaunchKernelGGL(pack_kernel<true>, dim3(n_tiles, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile,
+                       v_f16, tile_rows);
+  else
+    hipLaunchKernelGGL(pack_kernel<false>, dim3(n_tiles, Hkv, B), dim3(256), 0, st, K, V, sb, sh, st_, Hkv, T, kv, 0, 0, rule, tile,
+                       v_f16, tile_rows);
   return hipGetLastError();
 }
 

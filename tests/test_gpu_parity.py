@@ -1240,6 +1240,22 @@ def test_matrix_rate_probe_runs_and_counts_its_work():
     assert hb.lib().hs_probe_mfma_rate(0, 0, sink.data_ptr(), C.byref(f), None) == -1
 
 
+def test_stream_read_probe_runs():
+    """The benchmark's load-only kernel (the decode kernel's access pattern): runs over a buffer of pool-shaped
+    regions, with and without its epilogue, and rejects shapes it cannot split evenly."""
+    n_tiles, n_wg = 512, 32
+    buf = torch.ones(n_tiles * 18432, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16 + 512 * n_wg, dtype=torch.float32, device="cuda")
+    hb.probe_stream_read(buf, n_tiles, n_wg, True, sink)
+    torch.cuda.synchronize()
+    # every byte is 1: each lane's xor over 4 x 18 tiles' words ends up 0 -> the combined partials are 0
+    assert float(sink[16:].abs().max().item()) == 0.0
+    hb.probe_stream_read(buf, n_tiles, n_wg, False, sink)
+    torch.cuda.synchronize()
+    with pytest.raises(hb.HsError):
+        hb.probe_stream_read(buf, n_tiles, 24, True, sink)            # 512 tiles do not split over 24 workgroups of 4 waves
+
+
 def test_argument_errors_on_device_calls():
     B, Hq, Hkv, L = 1, 4, 1, 256
     Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, L, seed=150)
