@@ -469,6 +469,97 @@ def test_decode_cfg3_full_batch_sampled_rows(pol):
         assert_lse_close(LSE[b:b + 1, G * h:G * (h + 1)].cpu().numpy(), Lr, "decode cfg3 full batch lse")
 
 
+def _check_sampled_heads(sh, kv, K, V, Q, O, LSE, q_dec, O_dec, LSE_dec, pol, heads, n_rows, seed, dtype="bf16", q_start=None):
+    """Oracle check of device-generated full-size inputs on sampled (batch, kv head) rows: maps and a few pool
+    slots bit for bit, prefill on n_rows sampled queries of one query head of the group, decode on the group."""
+    B, Hq, Hkv, L = sh.B, sh.Hq, sh.Hkv, sh.L
+    G = Hq // Hkv
+    rng = np.random.default_rng(seed)
+    for b, h in heads:
+        print(f"[sampled heads] b={b} hkv={h} {sorted(pol)}", flush=True)
+        Kb, Vb = hb.bf16_tensor_to_bits(K[b:b + 1, h:h + 1]), hb.bf16_tensor_to_bits(V[b:b + 1, h:h + 1])
+        pk, pv, _ = orc.compress_kv(Kb, Vb, Bt=64, dtype=dtype, **pol)
+        assert_maps_equal(kv, pk, pv, sel=(b, h), osel=(0, 0))
+        if Q is not None:
+            Lq = Q.shape[2]
+            hq = G * h + int(rng.integers(G))
+            qi = sorted(set([0, Lq - 1] + [int(x) for x in rng.integers(0, Lq, size=n_rows)]))
+            Qb = hb.bf16_tensor_to_bits(Q[b:b + 1, hq:hq + 1])
+            Or, Lr = orc.attention_rows(Qb, pk, pv, [(0, 0, i) for i in qi], causal=True, q_offset=q_start)
+            assert_close(_f32(O[b, hq])[qi], Or, f"prefill sampled b{b} hq{hq}")
+            assert_lse_close(LSE[b, hq].cpu().numpy()[qi], Lr, f"prefill sampled lse b{b} hq{hq}")
+        if q_dec is not None:
+            qb = hb.bf16_tensor_to_bits(q_dec[b:b + 1, G * h:G * (h + 1)])
+            Or, Lr = orc.attention_decode(qb, pk, pv)
+            assert_close(_f32(O_dec[b:b + 1, G * h:G * (h + 1)]), Or, f"decode sampled b{b} hkv{h}")
+            assert_lse_close(LSE_dec[b:b + 1, G * h:G * (h + 1)].cpu().numpy(), Lr, f"decode sampled lse b{b} hkv{h}")
+
+
+@pytest.mark.parametrize("pol", [dict(), dict(sparse_frac_k=0.0, sparse_frac_v=1.0)])
+def test_paper_kernel_shape_b8_32k_sampled_heads(pol):
+    """The shape of the paper's own kernel benchmarks (Sec. V-B: batch 8, 32K tokens, 32 / 8 heads) at full size,
+    as the benchmark leg runs it: prefill and decode, all tiles 2:4 and keys dense / values 2:4, against the
+    oracle on two sampled (batch, kv head) rows."""
+    B, Hq, Hkv, L = 8, 32, 8, 32768
+    g = torch.Generator(device="cuda")
+    g.manual_seed(500)
+    K = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    V = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Q = torch.randn((B, Hq, L, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    sh = hb.make_shape(B, Hq, Hkv, L)
+    kv = hb.compress_kv(sh, hb.make_policy(**pol), K, V)
+    O, LSE = hb.prefill_attn(sh, Q, kv)
+    q = Q[:, :, -1, :].contiguous()
+    Od, LSEd = hb.decode_attn(sh, q, kv)
+    torch.cuda.synchronize()
+    _check_sampled_heads(sh, kv, K, V, Q, O, LSE, q, Od, LSEd, pol, [(0, 0), (6, 5)], 24, seed=501)
+
+
+def test_fp16_benchmark_shape_sampled_heads():
+    """fp16 (the paper's element type) at the benchmark workload's shape (L = 32768), as the fp16 leg runs it."""
+    B, Hq, Hkv, L = 1, 32, 8, 32768
+    g = torch.Generator(device="cuda")
+    g.manual_seed(510)
+    K = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.float16, generator=g)
+    V = torch.randn((B, Hkv, L, 128), device="cuda", dtype=torch.float16, generator=g)
+    Q = torch.randn((B, Hq, L, 128), device="cuda", dtype=torch.float16, generator=g)
+    sh = hb.make_shape(B, Hq, Hkv, L, dtype=hb.FP16)
+    for pol in (dict(), dict(sparse_frac_k=0.0, sparse_frac_v=1.0)):
+        kv = hb.compress_kv(sh, hb.make_policy(**pol), K, V)
+        O, LSE = hb.prefill_attn(sh, Q, kv)
+        q = Q[:, :, -1, :].contiguous()
+        Od, LSEd = hb.decode_attn(sh, q, kv)
+        torch.cuda.synchronize()
+        _check_sampled_heads(sh, kv, K, V, Q, O, LSE, q, Od, LSEd, pol, [(0, 3)], 32, seed=511, dtype="fp16")
+
+
+def test_chunked_prefill_128k_in_32k_chunks_sampled_head():
+    """Chunked prefill as the benchmark leg runs it (a cache allocated for 128K tokens, 32K-token chunks, per
+    chunk one append and one causal attention call at the chunk's position): the last chunk's outputs and the
+    final cache against the oracle on one sampled kv head."""
+    Hq, Hkv, Lc, chunk = 32, 8, 131072, 32768
+    Tc, nct = Lc // 64, chunk // 64
+    g = torch.Generator(device="cuda")
+    g.manual_seed(520)
+    K = torch.randn((1, Hkv, Lc, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    V = torch.randn((1, Hkv, Lc, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    Q = torch.randn((1, Hq, chunk, 128), device="cuda", dtype=torch.bfloat16, generator=g)
+    sh = hb.make_shape(1, Hq, Hkv, Lc)
+    kv = hb.PackedKV(sh, [0, Tc, 0, 0, Tc])                  # keys dense, values 2:4
+    kv.uniform = 0
+    kv.k_map.zero_()
+    kv.v_map.zero_()
+    ovf = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for c in range(Lc // chunk):
+        hb.append_tile(sh, kv, nct * c, K[:, :, chunk * c:chunk * (c + 1)], V[:, :, chunk * c:chunk * (c + 1)],
+                       state_k=hb.DENSE, state_v=hb.SPARSE24, overflow=ovf)
+        O, LSE = hb.prefill_attn(sh, Q, kv, q_start=chunk * c)
+    torch.cuda.synchronize()
+    assert int(ovf.item()) == 0
+    pol = dict(sparse_frac_k=0.0, sparse_frac_v=1.0)          # what the appended states amount to
+    _check_sampled_heads(sh, kv, K, V, Q, O, LSE, None, None, None, pol, [(0, 6)], 12, seed=521, q_start=Lc - chunk)
+
+
 def test_selection_on_a_row_longer_than_the_register_cache():
     """Tile selection with more than 8 tiles per thread (rows over 2048 tiles take the path that re-reads
     the scores instead of holding them in registers): maps against the oracle, with planted equal tiles
