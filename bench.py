@@ -11,7 +11,8 @@ that the decode stage of a step reads a cache that was written several steps
 (> 512 MB of other traffic) earlier: its bytes come from HBM, not from the
 256 MB last-level cache.
 
-Prints ONE JSON line (see README / DESIGN notes for the fields).
+Prints ONE JSON line: metric / value / unit / stages, the roofline objects of the three kernels, the extra
+legs (stages_extra) and the oracle timed on the host (cpu_baseline).
 """
 import argparse
 import json
@@ -451,6 +452,13 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     t_dm = e0.elapsed_time(e1) / n_rep * 1e-3
+    # whole decode calls back to back, as a decode loop issues them (still one cold cache per call)
+    e0.record()
+    for i in range(n_rep):
+        hb.decode_attn(sh, qd, kvs[i % args.copies], n_splits=n_splits, out=Od, lse=lse_d, workspace=ws_d)
+    e1.record()
+    torch.cuda.synchronize()
+    t_dc = e0.elapsed_time(e1) / n_rep * 1e-3
     # the compress kernel alone, the same way: back-to-back launches into rotating output buffers
     hb.compress_kv(sh, pol, K, V, out=kvs[0], workspace=ws_c)
     e0.record()
@@ -508,6 +516,7 @@ def main():
         # back-to-back merge-only calls: bounded by the host's launch rate, not by the 4 us kernel
         # (its own duration is in profiles/bench_cfg1_kernel_trace.md)
         "decode_merge_call_us_host_bound": t_dm * 1e6,
+        "decode_call_us_back_to_back": t_dc * 1e6, "decode_call_GBps_back_to_back": decode_bytes / t_dc / 1e9,
         "decode_n_splits": n_splits, "packed_MB": kv_bytes / 1e6, "dense_MB": 2 * B * Hkv * L * D * 2 / 1e6,
         "compression_ratio": 2 * B * Hkv * L * D * 2 / kv_bytes,
         "ideal_decode_speedup": 1.0 / (1.0 - 0.21875 * 2), "ideal_prefill_speedup": 2.0,
