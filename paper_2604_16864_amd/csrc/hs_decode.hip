@@ -16,6 +16,9 @@
 #ifndef HS_DEC_DEPTH
 #define HS_DEC_DEPTH 2
 #endif
+#ifndef HS_DEC_BYCOUNT_MIN_PER
+#define HS_DEC_BYCOUNT_MIN_PER 128  /* tiles per split from which the kept tiles are handed out by count */
+#endif
 #ifndef HS_DEC_OCC
 #define HS_DEC_OCC ((KM == 0 && VM == 0) || KM == 2 || VM == 2 ? 2 : 1)  /* a dense tensor at depth 2 needs > 256 registers */
 #endif
@@ -186,13 +189,42 @@ __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const ui
   }
 }
 
+// Which tile forms (bit 0 K dense, bit 1 V dense, bit 2 V in bf16 encoding) a kernel instantiation can meet:
+// KM / VM 0 = every tile 2:4, 1 = every tile dense, 2 = any mix; an fp16 cache has no bf16-encoded tiles.
+template <int KM, int VM, bool F16>
+__host__ __device__ constexpr bool form_allowed(int f) {
+  return ((f & 1) ? KM != 0 : KM != 1) && ((f & 2) ? VM != 0 : VM != 1) && ((f & 4) ? !F16 : true);
+}
+// fn(std::integral_constant<int, f>) for every allowed form f except SKIP_FORM, in ascending order
+template <int KM, int VM, bool F16, int SKIP_FORM, int F = 0, typename Fn>
+__device__ __forceinline__ void static_for_forms(Fn&& fn) {
+  if constexpr (F < 8) {
+    if constexpr (F != SKIP_FORM && form_allowed<KM, VM, F16>(F)) fn(std::integral_constant<int, F>{});
+    static_for_forms<KM, VM, F16, SKIP_FORM, F + 1>(fn);
+  }
+}
+
 // Split-KV kernel.  grid = (n_splits, Hkv, B); workgroup = 4 waves; split s owns tiles
 // [s*per, (s+1)*per); wave w takes every 4th tile of them.  Each wave preloads the map
 // entries of its tiles with one vector load, drops the skipped ones, and streams the rest
 // with a two-deep register pipeline (the loads of tile i+1 are in flight while tile i is
 // being multiplied).
 // Each workgroup emits a normalised partial output and its log-sum-exp per query head.
-template <int KM, int VM, bool UNIFORM, bool F16>
+//
+// MODE (how the tiles of a row are handed out):
+//   kByRange    split s owns tiles [s*per, (s+1)*per), wave w every 4th of them; skipped tiles are dropped
+//               as they are met, so a split or a wave may end up with fewer tiles than its neighbours.
+//   kUniform    as kByRange, for a cache the caller promises to be uniform (no tile skipped, one kind per
+//               tensor, slot == tile): the K map is not read at all.
+//   kByCount    the kept (not skipped) tiles of the row are numbered in tile order, split s owns the numbers
+//               [n*s/S, n*(s+1)/S) and wave w every 4th of them: every wave of the grid gets the same number
+//               of tiles to within one, whatever the skip pattern.  Costs two passes over the row's maps
+//               at kernel start (count, then list through LDS), so the host picks it for long rows only.
+enum { kByRange = 0, kUniform = 1, kByCount = 2 };
+constexpr int kListCap = 2048;  // tiles listed in LDS at a time (kByCount); longer shares take several passes
+constexpr int kScanBatch = 2048;  // tiles of the row looked at per scan step: 8 per thread
+
+template <int KM, int VM, int MODE, bool F16>
 __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, int Hkv, int T, float scale_log2,
                                                                              int n_splits, int per,
                                                                              const uint16_t* __restrict__ Q,
@@ -221,37 +253,42 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
   for (int i = 0; i < 8; i++) o[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
 
-  // DEPTH tiles in flight per wave.  Measured on the 32K-context shape: depth 1, 2, 3 and 4 (the
-  // deeper ones at 1 wave per SIMD) all land within run-to-run noise, and even a variant with
-  // the arithmetic removed is only ~10 % faster: the kernel is bound by the load stream.
-  constexpr int DEPTH = (KM == 2 || VM == 2) ? 1 : HS_DEC_DEPTH;  // a mixed tensor carries both code paths: keep it small
-  TileRegs<KM, VM> ring[DEPTH];
-  // One sweep over this wave's tiles for one V encoding (enc: 1 = fp16, 0 = bf16): a tile of
-  // the other encoding is left out and reported, so that the matrix instructions of a sweep are
-  // of one type and no branch sits between them.  The softmax recurrence does not care in which
-  // order tiles arrive.
-  auto sweep = [&](auto enc) -> bool {
-    constexpr int kEnc = decltype(enc)::value;
-    bool others = false;
-    for (int base = t_begin + w; base < t_end; base += 256) {  // up to 64 tiles of this wave per round
-      const int t_mine = base + 4 * l;
+  // A tile's form: bit 0 = K tile dense, bit 1 = V tile dense, bit 2 = V tile stored in bf16 encoding (bf16
+  // caches only; a V tile of a bf16 cache is normally stored in fp16 encoding, HS_MAP_F16).  The tiles are
+  // worked through one form at a time ("sweeps"): the loads and matrix instructions of a sweep are all of one
+  // type, no branch sits between them, and each sweep keeps as many tiles in flight as its operands leave
+  // registers for.  The softmax recurrence does not care in which order tiles arrive.
+  auto form_of = [](int mk, int mv) -> int { return (mk > 0 ? 1 : 0) | (mv > 0 ? 2 : 0) | ((!F16 && !hs_map_f16(mv)) ? 4 : 0); };
+  constexpr bool kMixed = KM == 2 || VM == 2;
+  constexpr int kFirstForm = (KM == 1 ? 1 : 0) | (VM == 1 ? 2 : 0);  // swept first: it also notes which other forms occur
+  // One sweep.  The tiles come as a sequence of map entry pairs numbered [first, last): `entry(i, mk, mv)` yields
+  // pair i; wave w takes every 4th pair starting at first + w.  Returns (COLLECT) the set of forms among them.
+  auto sweep = [&](auto form_c, auto collect_c, int first, int last, auto entry) -> unsigned {
+    constexpr int kForm = decltype(form_c)::value;
+    constexpr bool COLLECT = decltype(collect_c)::value;
+    constexpr int KK = kForm & 1, VK = (kForm >> 1) & 1, kEnc = (kForm & 4) ? 0 : 1;
+    // Tiles in flight per wave.  Measured on the 32K-context shape: depth 1, 2, 3 and 4 (the deeper ones at
+    // 1 wave per SIMD) all land within run-to-run noise, and even a variant with the arithmetic removed is only
+    // ~10 % faster: the kernel is bound by the load stream.  A kernel for mixed tensors runs at 2 waves per
+    // SIMD, where only two 2:4 tiles (or one tile with a dense operand) fit.
+    constexpr int DEPTH = kMixed ? ((KK == 0 && VK == 0) ? 2 : 1) : HS_DEC_DEPTH;
+    TileRegs<KK, VK> ring[DEPTH];
+    unsigned seen = 0;
+    for (int base = first + w; base < last; base += 256) {  // up to 64 tiles of this wave per round
+      const int i_mine = base + 4 * l;
       int mk_v = 0, mv_v = 0;
-      if (t_mine < t_end) {
-        if (UNIFORM) {  // promised by the caller: no tile skipped, one kind per tensor, slot == tile
-          mk_v = KM == 0 ? -(t_mine + 1) : t_mine + 1;
-          mv_v = F16 ? (VM == 0 ? -(t_mine + 1) : t_mine + 1) : kv.v_map[row * T + t_mine];  // bf16: encoding bit
-        } else {
-          mk_v = kv.k_map[row * T + t_mine];
-          mv_v = kv.v_map[row * T + t_mine];
-        }
-      }
+      if (i_mine < last) entry(i_mine, mk_v, mv_v);
       // Tile kinds must reach the branches below as scalar (wave-uniform) values: matrix
       // instructions ignore the EXEC mask, so a branch the compiler treats as divergent would run
       // both the dense and the 2:4 instruction on every tile.  Lane values are therefore read
       // with v_readlane, never with a lane shuffle.
-      const bool mine = F16 || hs_map_f16(mv_v) == (kEnc == 1);
-      unsigned long long act = __ballot(mk_v != 0 && mine);
-      if (!F16) others = others || __ballot(mk_v != 0 && !mine) != 0ull;
+      const int form_v = form_of(mk_v, mv_v);
+      unsigned long long act = __ballot(mk_v != 0 && form_v == kForm);
+      if (COLLECT) {
+#pragma unroll
+        for (int f = 0; f < 8; f++)
+          if (f != kForm && form_allowed<KM, VM, F16>(f)) seen |= (__ballot(mk_v != 0 && form_v == f) != 0ull ? 1u : 0u) << f;
+      }
       bool have[DEPTH];
 #pragma unroll
       for (int d = 0; d < DEPTH; d++) {
@@ -259,7 +296,7 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
         if (have[d]) {
           const int i = __builtin_ctzll(act);
           act &= act - 1;
-          tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
+          tile_load<KK, VK>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
         }
       }
       bool go = have[0];
@@ -267,12 +304,12 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
 #pragma unroll
         for (int d = 0; d < DEPTH; d++) {
           if (go && have[d]) {  // tiles are consumed in issue order: the first empty slot ends the round
-            tile_compute<KM, VM, F16, kEnc>(ring[d], qb, scale_log2, c, o, m_run, l_run);
+            tile_compute<KK, VK, F16, kEnc>(ring[d], qb, scale_log2, c, o, m_run, l_run);
             have[d] = act != 0ull;
             if (have[d]) {
               const int i = __builtin_ctzll(act);
               act &= act - 1;
-              tile_load<KM, VM>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
+              tile_load<KK, VK>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
             }
           } else {
             go = false;
@@ -280,10 +317,97 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
         }
       }
     }
-    return others;
+    return seen;
   };
-  const bool bf16_tiles_left = sweep(std::integral_constant<int, 1>{});
-  if (!F16 && bf16_tiles_left) sweep(std::integral_constant<int, 0>{});
+  auto all_sweeps = [&](int first, int last, auto entry) {
+    const unsigned seen = sweep(std::integral_constant<int, kFirstForm>{}, std::true_type{}, first, last, entry);
+    static_for_forms<KM, VM, F16, kFirstForm>([&](auto form_c) {
+      if ((seen >> decltype(form_c)::value) & 1u) sweep(form_c, std::false_type{}, first, last, entry);
+    });
+  };
+  auto from_map = [&](int t, int& mk, int& mv) {
+    if (MODE == kUniform) {  // promised by the caller: no tile skipped, one kind per tensor, slot == tile
+      mk = KM == 0 ? -(t + 1) : t + 1;
+      mv = F16 ? (VM == 0 ? -(t + 1) : t + 1) : kv.v_map[row * T + t];  // bf16: encoding bit
+    } else {
+      mk = kv.k_map[row * T + t];
+      mv = kv.v_map[row * T + t];
+    }
+  };
+  if constexpr (MODE != kByCount) {
+    all_sweeps(t_begin, t_end, from_map);
+  } else {
+    __shared__ int2 sm_list[kListCap];  // (k_map, v_map) entries of this workgroup's tiles, in tile order
+    __shared__ int sm_cnt[36];          // [0..3] kept tiles per wave (count pass); [4 + 4 j + w] per scan segment
+    const int* kmap = kv.k_map + row * T;
+    const int* vmap = kv.v_map + row * T;
+    const unsigned long long lanes_below = (1ull << l) - 1ull;
+    // pass 1: kept tiles of the row
+    int mine_cnt = 0;
+    for (int b0 = 0; b0 < T; b0 += kScanBatch) {
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        const int t = b0 + 256 * j + tid;
+        const int mk = t < T ? kmap[t] : 0;
+        const int mv = t < T ? vmap[t] : 0;  // not needed yet: fetched so that pass 2 finds both maps in the L2
+        asm volatile("" ::"v"(mv));
+        mine_cnt += __builtin_popcountll(__ballot(mk != 0));
+      }
+    }
+    if (l == 0) sm_cnt[w] = mine_cnt;
+    __syncthreads();
+    const int n_kept = sm_cnt[0] + sm_cnt[1] + sm_cnt[2] + sm_cnt[3];
+    const int n_work = gridDim.x;
+    const int lo = (int)((int64_t)n_kept * split / n_work), hi = (int)((int64_t)n_kept * (split + 1) / n_work);
+    if (n_kept == T) {  // nothing skipped: a tile's number is its index, no list needed
+      all_sweeps(lo, hi, from_map);
+    } else
+    for (int r0 = lo; r0 < hi; r0 += kListCap) {  // workgroup-uniform bounds: every thread takes the same trips
+      const int r1 = min(hi, r0 + kListCap);
+      // pass 2: list the tiles numbered [r0, r1)
+      int carried = 0;  // kept tiles before the scan step
+      for (int b0 = 0; b0 < T && carried < r1; b0 += kScanBatch) {
+        int mk8[8], mv8[8];  // read again in every pass (from L2 by now) rather than held across the tile loop
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const int t = b0 + 256 * j + tid;
+          mk8[j] = t < T ? kmap[t] : 0;
+          mv8[j] = t < T ? vmap[t] : 0;
+        }
+        unsigned long long kept[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          kept[j] = __ballot(mk8[j] != 0);
+          if (l == 0) sm_cnt[4 + 4 * j + w] = __builtin_popcountll(kept[j]);
+        }
+        __syncthreads();
+        int run = carried;  // tile t = b0 + 256 j + 64 w + l: segments in (j, w) order are in tile order
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          int before = run;
+#pragma unroll
+          for (int ww = 0; ww < 4; ww++) {
+            const int c_seg = sm_cnt[4 + 4 * j + ww];
+            if (ww < w) before += c_seg;
+            run += c_seg;
+          }
+          const int number = before + __builtin_popcountll(kept[j] & lanes_below);
+          if (mk8[j] != 0 && number >= r0 && number < r1) sm_list[number - r0] = make_int2(mk8[j], mv8[j]);
+        }
+        carried = run;
+        __syncthreads();  // the counts are rewritten by the next scan step
+      }
+      const int n_list = r1 - r0;
+      // the same sweeps, over the list: pair i goes to wave i % 4
+      auto from_list = [&](int i, int& mk, int& mv) {
+        const int2 e = sm_list[i];
+        mk = e.x;
+        mv = e.y;
+      };
+      all_sweeps(0, n_list, from_list);
+      __syncthreads();  // the list is rewritten by the next pass
+    }
+  }
 
   // ---------------- combine: lane groups, hi/lo columns, then the 4 waves ----------------
   l_run += __shfl_xor(l_run, 16);
@@ -477,14 +601,14 @@ hipError_t hs_static_scratch(void** ptr, size_t* bytes) {
 }
 
 // Workspace: [partial O (normalised) [B*Hq][n_splits][128] fp32][partial LSE [B*Hq][n_splits] fp32].
-template <int KM, int VM, bool UNIFORM>
+template <int KM, int VM, int MODE>
 static hipError_t launch_split(dim3 grid, hipStream_t st, int Hq, int Hkv, int T, float sl2, int n_splits, int per,
                                const uint16_t* Q, const hs_kv_dev& kv, float* wo, float* wl, bool f16) {
   if (f16)
-    hipLaunchKernelGGL((decode_split_kernel<KM, VM, UNIFORM, true>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits,
+    hipLaunchKernelGGL((decode_split_kernel<KM, VM, MODE, true>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits,
                        per, Q, kv, wo, wl);
   else
-    hipLaunchKernelGGL((decode_split_kernel<KM, VM, UNIFORM, false>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits,
+    hipLaunchKernelGGL((decode_split_kernel<KM, VM, MODE, false>), grid, dim3(256), 0, st, Hq, Hkv, T, sl2, n_splits,
                        per, Q, kv, wo, wl);
   return hipGetLastError();
 }
@@ -505,11 +629,20 @@ hipError_t hs_launch_decode(int B, int Hq, int Hkv, int T, float scale, int n_wo
   const int vm = kv.cap_dense_v == 0 ? 0 : (kv.cap_sparse_v == 0 ? 1 : 2);
   hipError_t e = hipSuccess;
   if (phases & 1) {
-#define HS_GO(KM_, VM_)                                                                                         \
-  e = kv.uniform ? launch_split<KM_, VM_, true>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16)  \
-                 : launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16); \
+  // tiles by count on long splits only: the two passes over the maps at kernel start cost about 3 us, which
+  // the even shares win back (3-7 % of the kernel when tiles are skipped) from 128 tiles per split for
+  // all-2:4 tensors and from 256 for the other kernels (measured)
+  const bool by_count = per >= (km == 0 && vm == 0 ? HS_DEC_BYCOUNT_MIN_PER : 2 * HS_DEC_BYCOUNT_MIN_PER);
+#define HS_GO_DYN(KM_, VM_)                                                                                            \
+  e = by_count ? launch_split<KM_, VM_, kByCount>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16)       \
+               : launch_split<KM_, VM_, kByRange>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16);      \
   break
-#define HS_GO_DYN(KM_, VM_) e = launch_split<KM_, VM_, false>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16); break
+#define HS_GO(KM_, VM_)                                                                                       \
+  if (kv.uniform) {                                                                                           \
+    e = launch_split<KM_, VM_, kUniform>(grid, st, Hq, Hkv, T, sl2, n_splits, per, Q, kv, wo, wl, f16);       \
+    break;                                                                                                    \
+  }                                                                                                           \
+  HS_GO_DYN(KM_, VM_)
   switch (km * 3 + vm) {
     case 0: HS_GO(0, 0);
     case 1: HS_GO(0, 1);

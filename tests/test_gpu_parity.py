@@ -277,6 +277,56 @@ def test_decode_skip_policy_outlier_keys(skip):
     assert_lse_close(LSE, Lr, f"decode skip={skip} lse")
 
 
+# Rows long enough for the library to hand the kept tiles out by count (from 128 tiles per split with all-2:4
+# tensors, from 256 otherwise): every wave gets the same number of tiles whatever the skip pattern.  The results
+# must not depend on it.
+@pytest.mark.parametrize("n_splits", [1, 2, 3, 7])
+@pytest.mark.parametrize("pol", [dict(skip_frac=0.5), dict(skip_frac=0.75, sparse_frac_k=0.5, sparse_frac_v=0.25),
+                                 dict(skip_frac=0.3, sparse_frac_k=0.0, sparse_frac_v=1.0)])
+def test_decode_tiles_handed_out_by_count(pol, n_splits):
+    O, LSE, Or, Lr = _decode_case(2, 8, 2, 64 * 512, seed=75, n_splits=n_splits, k_outliers=True, **pol)
+    assert_close(O, Or, f"decode by count {pol} splits={n_splits}")
+    assert_lse_close(LSE, Lr, f"decode by count {pol} splits={n_splits} lse")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_decode_by_count_explicit_states_with_empty_and_nearly_empty_rows(dtype):
+    B, Hq, Hkv, L = 2, 8, 2, 64 * 520
+    T = L // 64
+    sk, sv = _mixed_states(B, Hkv, T, seed=76, p_skip=0.6)
+    sk[0, 1, :] = 0                       # a row with nothing kept
+    sv[0, 1, :] = 0
+    sk[1, 0, :] = 0                       # a row with fewer kept tiles (1) than splits (2): one split gets none
+    sv[1, 0, :] = 0
+    sk[1, 0, 77] = 2
+    sv[1, 0, 77] = 1
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=77, dtype=dtype)
+    if dtype == "bf16":                   # both V encodings in one row: a few values fp16 cannot hold
+        V = V.copy()
+        V[:, :, 64 * 5 + 3, 9] = 0x0080   # 2^-126
+        V[:, :, 64 * 350 + 1, 100] = 0x4780   # 65536
+    q = Q[:, :, 0, :].copy()
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, dtype=dtype, state_k=sk, state_v=sv)
+    Or, Lr = orc.attention_decode(q, pk, pv)
+    for ns in (1, 2):
+        O, LSE = hb.decode_attn(sh, _dev(q, dtype), kv, n_splits=ns)
+        torch.cuda.synchronize()
+        O, LSE = _f32(O), LSE.cpu().numpy()
+        assert (O[0, 4:8] == 0).all() and np.isneginf(LSE[0, 4:8]).all()
+        assert_close(O, Or, f"decode by count mixed {dtype} splits={ns}")
+        assert_lse_close(LSE, Lr, f"decode by count mixed {dtype} splits={ns} lse")
+
+
+@pytest.mark.parametrize("n_splits", [1, 3])
+def test_decode_by_count_row_longer_than_one_scan_step_and_one_list(n_splits):
+    """4608 tiles in a row: three scan steps of 2048 tiles; with one split its 3456 kept tiles fill the
+    workgroup's list of 2048 twice."""
+    B, Hq, Hkv, L = 1, 2, 1, 64 * 4608
+    O, LSE, Or, Lr = _decode_case(B, Hq, Hkv, L, seed=78, n_splits=n_splits, skip_frac=0.25)
+    assert_close(O, Or, f"decode long row splits={n_splits}")
+    assert_lse_close(LSE, Lr, f"decode long row splits={n_splits} lse")
+
+
 def test_decode_cfg1_full_size():
     """The benchmark workload at full size, in the launch configuration the benchmark times."""
     c, q, K, V = wl.make_config("cfg1_decode_llama8b_32k")
