@@ -584,9 +584,9 @@ def main():
         "stages": stages,
         # dominant kernel of the metric: the split-KV kernel alone (back-to-back launches with the merge kernel
         # left out); `value` above is the whole decode call (split + merge + launch gap) inside the step
-        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0, 0, true>", "achieved": decode_bytes / dec_split_s / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel<0, 0, 1>", "achieved": decode_bytes / dec_split_s / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": decode_bytes / dec_split_s / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": traffic_from_profile("decode_split_kernel<0, 0, true"), "traffic_source": "profiles/bench_cfg1_hbm_traffic.md",
+                     "traffic": traffic_from_profile("decode_split_kernel<0, 0, 1"), "traffic_source": "profiles/bench_cfg1_hbm_traffic.md",
                      "algorithmic_bytes": decode_bytes, "avg_launch_us": dec_split_s * 1e6,
                      # load-only kernel with the same access pattern and launch shape (hs_probe_stream_read)
                      "load_only_probe_us": t_probe * 1e6, "load_only_probe_frac": n_tiles * 18432 / t_probe / 1e9 / HBM_PEAK_GBPS,
