@@ -327,6 +327,21 @@ def test_decode_by_count_row_longer_than_one_scan_step_and_one_list(n_splits):
     assert_lse_close(LSE, Lr, f"decode long row splits={n_splits} lse")
 
 
+def test_decode_by_count_with_a_dense_tail():
+    """The dense tail's partial sits behind the cache splits whichever way the tiles are handed out."""
+    B, Hq, Hkv, L = 1, 8, 2, 64 * 300
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L + 64, 128, 1, seed=79)
+    q = Q[:, :, 0, :].copy()
+    Kc, Vc, Kt, Vt = K[:, :, :L].copy(), V[:, :, :L].copy(), K[:, :, L:].copy(), V[:, :, L:].copy()
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, Kc, Vc, skip_frac=0.6)
+    for ns in (1, 2):      # 300 and 150 tiles per split: by count
+        O, LSE = hb.decode_attn(sh, _dev(q), kv, n_splits=ns, tail_k=_dev(Kt), tail_v=_dev(Vt), tail_len=23)
+        torch.cuda.synchronize()
+        Or, Lr = orc.attention_decode(q, pk, pv, tail_k=Kt, tail_v=Vt, tail_len=23)
+        assert_close(_f32(O), Or, f"decode by count with tail, splits {ns}")
+        assert_lse_close(LSE.cpu().numpy(), Lr, "decode by count with tail lse")
+
+
 def test_decode_cfg1_full_size():
     """The benchmark workload at full size, in the launch configuration the benchmark times."""
     c, q, K, V = wl.make_config("cfg1_decode_llama8b_32k")
