@@ -971,6 +971,40 @@ def test_random_shapes_and_policies(seed):
     assert_lse_close(LSEd.cpu().numpy(), Ldr, "decode lse " + what)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_long_rows_decode(seed):
+    """Seeded sweep over rows long enough for decode to hand its tiles out by count (and some just under the
+    limits, which go by range): random skip patterns, kinds, protected end tiles, split counts, GQA groups."""
+    rng = np.random.default_rng(5000 + seed)
+    B = int(rng.integers(1, 3))
+    Hkv = int(rng.integers(1, 3))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * G
+    T = int(rng.integers(120, 1100))
+    L = 64 * T
+    dtype = "fp16" if seed % 4 == 3 else "bf16"
+    Q, K, V = wl.make_qkv(B, Hq, Hkv, L, 128, 1, seed=6000 + seed, k_outliers=bool(rng.integers(0, 2)), dtype=dtype)
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        pol = dict(skip_frac=float(rng.choice([0.1, 0.5, 0.9])))
+    elif kind == 1:
+        pol = dict(skip_frac=float(rng.choice([0.0, 0.6])), sparse_frac_k=float(rng.choice([0.0, 0.5, 1.0])),
+                   sparse_frac_v=float(rng.choice([0.3, 1.0])), dense_first_tiles=int(rng.integers(0, 3)),
+                   dense_last_tiles=int(rng.integers(0, 5)))
+    else:
+        sk, sv = _mixed_states(B, Hkv, T, seed=7000 + seed, p_skip=float(rng.choice([0.2, 0.8])))
+        pol = dict(state_k=sk, state_v=sv)
+    q = Q[:, :, 0, :].copy()
+    sh, kv, pk, pv, _ = compress_both(B, Hq, Hkv, L, K, V, dtype=dtype, **pol)
+    Or, Lr = orc.attention_decode(q, pk, pv)
+    for ns in (1, int(rng.integers(2, 9))):
+        O, LSE = hb.decode_attn(sh, _dev(q, dtype), kv, n_splits=ns)
+        torch.cuda.synchronize()
+        what = f"seed {seed}: B{B} Hq{Hq} Hkv{Hkv} T{T} {dtype} splits {ns} {sorted(pol)}"
+        assert_close(_f32(O), Or, "decode " + what)
+        assert_lse_close(LSE.cpu().numpy(), Lr, "decode lse " + what)
+
+
 def test_explicit_states_on_the_device_run_with_no_host_wait():
     """A pruner that leaves its block-level masks on the device (Sec. III-A: the compressor takes the
     masks M as an input): compress with those states, causal prefill and decode are issued back to
