@@ -38,26 +38,23 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p) {
 
 
 // Operand registers of one tile (K and V), filled by tile_load and consumed by tile_compute.
-// KM / VM (per tensor): 0 = every tile 2:4 or skipped, 1 = every tile dense or skipped, 2 = any mix.
+// KM / VM: kind of the K / V tile, 0 = 2:4, 1 = dense (the kernel sorts its tiles by kind first).
 template <int KM, int VM>
 struct TileRegs {
+  static_assert((KM == 0 || KM == 1) && (VM == 0 || VM == 1), "one kind per operand");
   static constexpr int kNK = KM == 0 ? 8 : 16;  // 16-byte chunks per lane: 2:4 tile 8, dense tile 16
   static constexpr int kNV = VM == 0 ? 8 : 16;
   uint4 k[kNK];
   uint4 v[kNV];
   uint4 km, vm;  // the lane's four 32-bit index words of the K / V tile
-  int mk, mv;
 };
 
 template <int KM, int VM>
 __device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& kv, int64_t row, int mk, int mv, int l) {  // mk, mv: wave-uniform
-  r.mk = mk;
-  r.mv = mv;  // with the encoding bit, for tile_compute
   mv = hs_map_plain(mv);
   r.km = make_uint4(0, 0, 0, 0);  // only 2:4 tiles carry index words
   r.vm = make_uint4(0, 0, 0, 0);
-  const bool k_sparse = KM == 0 || (KM == 2 && mk < 0);
-  const bool v_sparse = VM == 0 || (VM == 2 && mv < 0);
+  constexpr bool k_sparse = KM == 0, v_sparse = VM == 0;
   if (k_sparse) {
     const int64_t slot = row * kv.cap_sparse_k + (-mk - 1);
     const uint4* p = reinterpret_cast<const uint4*>(kv.k_nnz + slot * (int64_t)HS_TILE_NNZ_BYTES) + l;
@@ -94,8 +91,7 @@ __device__ __forceinline__ void tile_load(TileRegs<KM, VM>& r, const hs_kv_dev& 
 template <int KM, int VM, bool F16, int ENC>
 __device__ __forceinline__ void tile_compute(const TileRegs<KM, VM>& r, const uint4 (&qb)[4], float scale_log2, int c,
                                              f32x4_t (&o)[8], float& m_run, float& l_run) {
-  const bool k_sparse = KM == 0 || (KM == 2 && r.mk < 0);
-  const bool v_sparse = VM == 0 || (VM == 2 && r.mv < 0);
+  constexpr bool k_sparse = KM == 0, v_sparse = VM == 0;
   constexpr int kNK = TileRegs<KM, VM>::kNK, kNV = TileRegs<KM, VM>::kNV;
   typedef hs_elem<F16> E;
   typedef hs_elem<true> E16;
