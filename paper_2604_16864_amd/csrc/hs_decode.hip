@@ -19,6 +19,9 @@
 #ifndef HS_DEC_BYCOUNT_MIN_PER
 #define HS_DEC_BYCOUNT_MIN_PER 128  /* tiles per split from which the kept tiles are handed out by count */
 #endif
+#ifndef HS_DEC_EARLY
+#define HS_DEC_EARLY 1  /* uniform bf16 caches: first tile loads issued behind the map read, not after it */
+#endif
 #ifndef HS_DEC_OCC
 #define HS_DEC_OCC ((KM == 0 && VM == 0) || KM == 2 || VM == 2 ? 2 : 1)  /* a dense tensor at depth 2 needs > 256 registers */
 #endif
@@ -259,9 +262,17 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
   constexpr int kFirstForm = (KM == 1 ? 1 : 0) | (VM == 1 ? 2 : 0);  // swept first: it also notes which other forms occur
   // One sweep.  The tiles come as a sequence of map entry pairs numbered [first, last): `entry(i, mk, mv)` yields
   // pair i; wave w takes every 4th pair starting at first + w.  Returns (COLLECT) the set of forms among them.
-  auto sweep = [&](auto form_c, auto collect_c, int first, int last, auto entry) -> unsigned {
+  // SPEC (uniform caches, first sweep): where the wave's first tiles sit is known without the maps (slot ==
+  // tile), only their form is not (the encoding bit of the V map), so in the first round their loads are issued
+  // right behind the map read instead of waiting for it (the map read is a sixth of the kernel's 7 us start-up
+  // at the 32K-context shape).  If one of them turns out to be of another form (a V tile that fp16 cannot
+  // hold) the sweep returns kGuessFailed before it has touched the accumulators, and is run again without
+  // guessing.
+  constexpr unsigned kGuessFailed = 1u << 31;
+  auto sweep = [&](auto form_c, auto collect_c, auto spec_c, int first, int last, auto entry) -> unsigned {
     constexpr int kForm = decltype(form_c)::value;
     constexpr bool COLLECT = decltype(collect_c)::value;
+    constexpr bool SPEC = decltype(spec_c)::value;
     constexpr int KK = kForm & 1, VK = (kForm >> 1) & 1, kEnc = (kForm & 4) ? 0 : 1;
     // Tiles in flight per wave.  Measured on the 32K-context shape: depth 1, 2, 3 and 4 (the deeper ones at
     // 1 wave per SIMD) all land within run-to-run noise, and even a variant with the arithmetic removed is only
@@ -270,7 +281,57 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
     constexpr int DEPTH = kMixed ? ((KK == 0 && VK == 0) ? 2 : 1) : HS_DEC_DEPTH;
     TileRegs<KK, VK> ring[DEPTH];
     unsigned seen = 0;
-    for (int base = first + w; base < last; base += 256) {  // up to 64 tiles of this wave per round
+// what the two copies of a round below share: the form ballots, and the loop that consumes the tiles in
+// flight and refills their ring slots from `act`
+#define HS_ROUND_BALLOTS                                                                                              \
+  const int form_v = form_of(mk_v, mv_v);                                                                             \
+  unsigned long long act = __ballot(mk_v != 0 && form_v == kForm);                                                    \
+  if (COLLECT) {                                                                                                      \
+    _Pragma("unroll") for (int f = 0; f < 8; f++)                                                                     \
+      if (f != kForm && form_allowed<KM, VM, F16>(f)) seen |= (__ballot(mk_v != 0 && form_v == f) != 0ull ? 1u : 0u) << f; \
+  }
+#define HS_ROUND_CONSUME                                                                                              \
+  bool go = have[0];                                                                                                  \
+  while (go) {                                                                                                        \
+    _Pragma("unroll") for (int d = 0; d < DEPTH; d++) {                                                               \
+      if (go && have[d]) { /* tiles are consumed in issue order: the first empty slot ends the round */               \
+        tile_compute<KK, VK, F16, kEnc>(ring[d], qb, scale_log2, c, o, m_run, l_run);                                 \
+        have[d] = act != 0ull;                                                                                        \
+        if (have[d]) {                                                                                                \
+          const int i = __builtin_ctzll(act);                                                                         \
+          act &= act - 1;                                                                                             \
+          tile_load<KK, VK>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l); \
+        }                                                                                                             \
+      } else {                                                                                                        \
+        go = false;                                                                                                   \
+      }                                                                                                               \
+    }                                                                                                                 \
+  }
+    int base = first + w;
+    if constexpr (SPEC) {
+      if (base < last) {  // first round, tiles guessed
+        const int i_mine = base + 4 * l;
+        int mk_v = 0, mv_v = 0;
+        if (i_mine < last) entry(i_mine, mk_v, mv_v);
+        bool have[DEPTH];
+        unsigned long long guessed = 0ull;
+#pragma unroll
+        for (int d = 0; d < DEPTH; d++) {
+          const int t = base + 4 * d;
+          have[d] = t < last;
+          if (have[d]) {
+            guessed |= 1ull << d;
+            tile_load<KK, VK>(ring[d], kv, row, KK == 0 ? -(t + 1) : t + 1, VK == 0 ? -(t + 1) : t + 1, l);
+          }
+        }
+        HS_ROUND_BALLOTS
+        if ((act & ((1ull << DEPTH) - 1ull)) != guessed) return kGuessFailed;
+        act &= ~guessed;
+        HS_ROUND_CONSUME
+        base += 256;
+      }
+    }
+    for (; base < last; base += 256) {  // up to 64 tiles of this wave per round
       const int i_mine = base + 4 * l;
       int mk_v = 0, mv_v = 0;
       if (i_mine < last) entry(i_mine, mk_v, mv_v);
@@ -278,13 +339,7 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
       // instructions ignore the EXEC mask, so a branch the compiler treats as divergent would run
       // both the dense and the 2:4 instruction on every tile.  Lane values are therefore read
       // with v_readlane, never with a lane shuffle.
-      const int form_v = form_of(mk_v, mv_v);
-      unsigned long long act = __ballot(mk_v != 0 && form_v == kForm);
-      if (COLLECT) {
-#pragma unroll
-        for (int f = 0; f < 8; f++)
-          if (f != kForm && form_allowed<KM, VM, F16>(f)) seen |= (__ballot(mk_v != 0 && form_v == f) != 0ull ? 1u : 0u) << f;
-      }
+      HS_ROUND_BALLOTS
       bool have[DEPTH];
 #pragma unroll
       for (int d = 0; d < DEPTH; d++) {
@@ -295,30 +350,20 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
           tile_load<KK, VK>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
         }
       }
-      bool go = have[0];
-      while (go) {
-#pragma unroll
-        for (int d = 0; d < DEPTH; d++) {
-          if (go && have[d]) {  // tiles are consumed in issue order: the first empty slot ends the round
-            tile_compute<KK, VK, F16, kEnc>(ring[d], qb, scale_log2, c, o, m_run, l_run);
-            have[d] = act != 0ull;
-            if (have[d]) {
-              const int i = __builtin_ctzll(act);
-              act &= act - 1;
-              tile_load<KK, VK>(ring[d], kv, row, __builtin_amdgcn_readlane(mk_v, i), __builtin_amdgcn_readlane(mv_v, i), l);
-            }
-          } else {
-            go = false;
-          }
-        }
-      }
+      HS_ROUND_CONSUME
     }
+#undef HS_ROUND_BALLOTS
+#undef HS_ROUND_CONSUME
     return seen;
   };
   auto all_sweeps = [&](int first, int last, auto entry) {
-    const unsigned seen = sweep(std::integral_constant<int, kFirstForm>{}, std::true_type{}, first, last, entry);
+    constexpr bool kGuess = HS_DEC_EARLY && MODE == kUniform && !F16;  // an fp16 cache has no map to wait for
+    unsigned seen = sweep(std::integral_constant<int, kFirstForm>{}, std::true_type{}, std::integral_constant<bool, kGuess>{},
+                          first, last, entry);
+    if (kGuess && seen == kGuessFailed)
+      seen = sweep(std::integral_constant<int, kFirstForm>{}, std::true_type{}, std::false_type{}, first, last, entry);
     static_for_forms<KM, VM, F16, kFirstForm>([&](auto form_c) {
-      if ((seen >> decltype(form_c)::value) & 1u) sweep(form_c, std::false_type{}, first, last, entry);
+      if ((seen >> decltype(form_c)::value) & 1u) sweep(form_c, std::false_type{}, std::false_type{}, first, last, entry);
     });
   };
   auto from_map = [&](int t, int& mk, int& mv) {
