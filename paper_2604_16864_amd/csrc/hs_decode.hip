@@ -20,7 +20,7 @@
 #define HS_DEC_BYCOUNT_MIN_PER 128  /* tiles per split from which the kept tiles are handed out by count */
 #endif
 #ifndef HS_DEC_EARLY
-#define HS_DEC_EARLY 1  /* uniform bf16 caches: first tile loads issued behind the map read, not after it */
+#define HS_DEC_EARLY 1  /* uniform caches: the first round of a wave guesses its tiles' form and loads them at once */
 #endif
 #ifndef HS_DEC_OCC
 #define HS_DEC_OCC ((KM == 0 && VM == 0) || KM == 2 || VM == 2 ? 2 : 1)  /* a dense tensor at depth 2 needs > 256 registers */
@@ -263,11 +263,12 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
   // One sweep.  The tiles come as a sequence of map entry pairs numbered [first, last): `entry(i, mk, mv)` yields
   // pair i; wave w takes every 4th pair starting at first + w.  Returns (COLLECT) the set of forms among them.
   // SPEC (uniform caches, first sweep): where the wave's first tiles sit is known without the maps (slot ==
-  // tile), only their form is not (the encoding bit of the V map), so in the first round their loads are issued
-  // right behind the map read instead of waiting for it (the map read is a sixth of the kernel's 7 us start-up
-  // at the 32K-context shape).  If one of them turns out to be of another form (a V tile that fp16 cannot
-  // hold) the sweep returns kGuessFailed before it has touched the accumulators, and is run again without
-  // guessing.
+  // tile), only their form is not (the encoding bit of the V map of a bf16 cache), so the first round is a
+  // straight-line copy of its own that issues their loads at once, behind the map read instead of after it
+  // and with no ballot or branch in front of them (4-6 % of the kernel at the 32K-context shape, fp16 caches,
+  // which have no map to wait for, included).  If one of the tiles turns out to be of another form (a V tile
+  // that fp16 cannot hold) the sweep returns kGuessFailed before it has touched the accumulators, and is run
+  // again without guessing.
   constexpr unsigned kGuessFailed = 1u << 31;
   auto sweep = [&](auto form_c, auto collect_c, auto spec_c, int first, int last, auto entry) -> unsigned {
     constexpr int kForm = decltype(form_c)::value;
@@ -325,7 +326,8 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
           }
         }
         HS_ROUND_BALLOTS
-        if ((act & ((1ull << DEPTH) - 1ull)) != guessed) return kGuessFailed;
+        if constexpr (!F16)  // an fp16 cache has one encoding: nothing to guess wrong
+          if ((act & ((1ull << DEPTH) - 1ull)) != guessed) return kGuessFailed;
         act &= ~guessed;
         HS_ROUND_CONSUME
         base += 256;
@@ -357,10 +359,10 @@ __global__ __launch_bounds__(256, HS_DEC_OCC) void decode_split_kernel(int Hq, i
     return seen;
   };
   auto all_sweeps = [&](int first, int last, auto entry) {
-    constexpr bool kGuess = HS_DEC_EARLY && MODE == kUniform && !F16;  // an fp16 cache has no map to wait for
+    constexpr bool kGuess = HS_DEC_EARLY && MODE == kUniform;
     unsigned seen = sweep(std::integral_constant<int, kFirstForm>{}, std::true_type{}, std::integral_constant<bool, kGuess>{},
                           first, last, entry);
-    if (kGuess && seen == kGuessFailed)
+    if (kGuess && !F16 && seen == kGuessFailed)
       seen = sweep(std::integral_constant<int, kFirstForm>{}, std::true_type{}, std::false_type{}, first, last, entry);
     static_for_forms<KM, VM, F16, kFirstForm>([&](auto form_c) {
       if ((seen >> decltype(form_c)::value) & 1u) sweep(form_c, std::false_type{}, std::false_type{}, first, last, entry);
